@@ -1,0 +1,212 @@
+/*
+ * libdetinfer -- deterministic, batch-invariant transformer decode step for AMD MI355X (gfx950).
+ *
+ * Every entry point is a pure function of its input bytes and shape arguments: the output bytes
+ * never depend on the stream, the launch order, what else runs on the device, the contents of a
+ * workspace before the call, or on the batch size (row i of an output is the same whether the call
+ * carries 1 row or 256, and whatever the other rows hold).  This is the contract of the paper's
+ * section 6.1 (inference as a pure function whose honest re-executions are bit-identical) carried
+ * by the three kernel invariants of its section 6.5: a fixed mapping of workgroups to output tiles
+ * with no communication between workgroups, canonical stride-halving tree reductions, and no
+ * floating-point atomics.
+ *
+ * Conventions
+ *   - Plain C ABI.  All pointers are DEVICE pointers unless a comment says "host".
+ *   - The caller owns every buffer.  The library allocates nothing and only enqueues work on the
+ *     caller's HIP stream (`stream` is a hipStream_t passed as void*; NULL is the default stream).
+ *     No call synchronises; results are ready when the stream reaches them.
+ *   - bf16 tensors are arrays of 16-bit patterns (upper half of an IEEE fp32), row-major.
+ *   - Workspaces need no initialisation: kernels overwrite whatever they later read.
+ *   - Every call returns DET_OK or an error code below and launches nothing on error.  After
+ *     DET_EHIP, det_last_hip_error() returns the hipError_t value seen by the calling thread.
+ *   - Pointers must be 16-byte aligned (DET_EALIGN otherwise).
+ */
+#ifndef DETINFER_H
+#define DETINFER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DET_OK 0
+#define DET_EINVAL 1     /* null pointer, non-positive size, bad enum */
+#define DET_ESHAPE 2     /* shape outside what the kernels support (see each call) */
+#define DET_EALIGN 3     /* pointer or leading dimension not 16-byte aligned */
+#define DET_EWORKSPACE 4 /* workspace smaller than the matching *_workspace_bytes() */
+#define DET_EHIP 5       /* a HIP runtime call failed */
+
+#define DET_BF16 0
+#define DET_F32 1
+
+/* ---------------------------------------------------------------------------------------------
+ * Deterministic GEMM (section 6.5: custom GEMM kernels; invariants 1 and 3).
+ *
+ *   C[i][j] = sum_k A[i][k] * B[k][j],  bf16 inputs, fp32 accumulation, output rounded once to
+ *   bf16 (nearest even) or left in fp32.
+ *
+ * Each output element has ONE fp32 accumulator that starts at +0 and takes K/32 matrix-core steps
+ * in ascending order; step t adds the 32 products of a fixed set of k indices (k in
+ * [64*(t/2), 64*(t/2)+64), see det_gemm_pack_b).  There is no split of K across workgroups or
+ * waves, no atomics, and the kernel configuration (columns per workgroup, K staging) is a function
+ * of (N, K) only: M decides how many 16-row blocks of the fixed tile hold data, nothing else.
+ *
+ *   A        [M, K] bf16, row stride lda elements (lda >= K, lda % 8 == 0)
+ *   B_packed output of det_gemm_pack_b for the same (N, K)
+ *   C        [M, N] bf16 (out_dtype DET_BF16) or fp32 (DET_F32), row stride ldc elements
+ *            (ldc >= N, ldc % 4 == 0)
+ *   Shapes: M >= 1, N % 16 == 0, K % 64 == 0; DET_ESHAPE otherwise.
+ */
+int det_gemm_bf16(const void *A, int lda, const void *B_packed, void *C, int ldc, int M, int N,
+                  int K, int out_dtype, void *stream);
+
+/* Bytes of the packed form of a [K, N] bf16 matrix (= 2*K*N). 0 if the shape is unsupported. */
+size_t det_gemm_packed_b_bytes(int N, int K);
+
+/* One-time, layout-only, bit-preserving repack of a row-major [K, N] bf16 weight matrix into the
+ * order the GEMM kernel streams it: each workgroup's column slab becomes one contiguous run, cut
+ * into 64-deep K stages already in matrix-core operand order.  B_kn and B_packed must not
+ * overlap. */
+int det_gemm_pack_b(const void *B_kn, void *B_packed, int N, int K, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * RMSNorm (section 6.5, invariant 2: canonical tree reduction; tree of Fig. "kernel_tree").
+ *
+ *   y[i][e] = bf16( (x[i][e] * r_i) * w[e] ),  r_i = 1 / sqrt( mean_e x[i][e]^2 + eps )
+ *
+ * Sum of squares: element e belongs to lane (e/8) mod 256; a lane folds its elements in ascending
+ * e with fma(x, x, acc) from +0; the 256 lane sums are reduced by six stride-halving levels inside
+ * each group of 64 lanes (offsets 32..1) and the four group sums as (q0+q2)+(q1+q3).  mean = ss/H;
+ * divide and square root are correctly rounded fp32.
+ *
+ *   x, y [M, H] bf16 contiguous; w [H] bf16.  H % 8 == 0, H <= 16384.
+ */
+int det_rmsnorm(const void *x, const void *w, void *y, int M, int H, float eps, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Single-query attention over a KV cache, grouped-query heads (the paper is silent on attention;
+ * the reductions follow section 6.5's invariants).
+ *
+ * For sequence b and query head h (reading KV head h / (Hq/Hkv)), len = seqlens[b]:
+ *   s_j = scale * (q . k_j), j < len, contraction on matrix cores with fp32 accumulation;
+ *   chunk c = tokens [256c, min(256c+256, len)):  m_c = max s_j;  e_j = det_expf(s_j - m_c);
+ *   l_c = tree-sum of e_j (same 256-leaf tree as RMSNorm, leaf = j - 256c);
+ *   O_c[d] = sum_j e_j * v_jd in fp32 in a fixed order;
+ *   combine in ascending c:  m = max m_c;  w_c = det_expf(m_c - m);  L = sum w_c*l_c;
+ *   O[d] = sum w_c*O_c[d];  out[d] = bf16(O[d] / L).
+ * The number of chunks depends only on that sequence's length.  Cache contents at or past len are
+ * never used.  len = 0 gives zeros.
+ *
+ *   q, out   [B, Hq, D] bf16
+ *   kcache, vcache [B, Hkv, Lmax, D] bf16
+ *   seqlens  [B] int32, 0 <= seqlens[b] <= Lmax (values above Lmax are clamped to Lmax)
+ *   ws       det_attn_decode_workspace_bytes(B, Hq, D, Lmax) bytes
+ *   Shapes: D == 128, Hq % Hkv == 0, Hq/Hkv in {1, 2, 4, 8}.
+ */
+size_t det_attn_decode_workspace_bytes(int B, int Hq, int D, int Lmax);
+int det_attn_decode(const void *q, const void *kcache, const void *vcache, const int32_t *seqlens,
+                    void *out, void *ws, size_t ws_bytes, int B, int Hq, int Hkv, int D, int Lmax,
+                    float scale, void *stream);
+
+/* Test hook: the softmax statistics of det_attn_decode on caller-provided fp32 scores, computed by
+ * the same device code.  s, p [R, Lmax] fp32; lens [R]; m_out, l_out [R] fp32.
+ * p_j = (w_c * e_j) / L for j < lens[r]; entries at or past lens[r] are not written.
+ * lens[r] = 0 gives m = -inf, L = 0.  Lmax <= 262144. */
+int det_softmax_f32(const float *s, const int32_t *lens, float *p, float *m_out, float *l_out, int R,
+                    int Lmax, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Greedy sampling (section 6.6: deterministic decoding in a canonical iteration order).
+ * idx[b] = smallest index attaining the maximum of row b; -0 equals +0; NaN never wins; a row of
+ * NaNs gives 0.  logits [B, V] fp32 (DET_F32) or bf16 (DET_BF16); idx [B] int32. */
+int det_argmax(const void *logits, int32_t *idx, int B, int V, int dtype, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Elementwise steps of the decoder layer, exported so each can be checked bit for bit.
+ *
+ * det_rope: rotary embedding, rotate-half pairing (i, i + D/2), on nh heads of one token per row.
+ *   y_lo = bf16( fma(-x_hi, sin, x_lo*cos) ),  y_hi = bf16( fma(x_lo, sin, x_hi*cos) )
+ *   x, y [R, nh, D] bf16 (row stride ldx / ldy elements); pos [R] int32 (< Lmax);
+ *   cos_t, sin_t [Lmax, D/2] fp32 built by the caller.  D == 128.
+ * det_swiglu: y = bf16( (g / (1 + det_expf(-g))) * u ); g, u, y [R, F] bf16 with row strides.
+ * det_residual_add: z = bf16( fp32(x) + fp32(y) ), n elements, n % 8 == 0; z may alias x.
+ */
+int det_rope(const void *x, int ldx, void *y, int ldy, const int32_t *pos, const float *cos_t,
+             const float *sin_t, int R, int nh, int D, int Lmax, void *stream);
+int det_swiglu(const void *g, int ldg, const void *u, int ldu, void *y, int ldy, int R, int F,
+               void *stream);
+int det_residual_add(const void *x, const void *y, void *z, int64_t n, void *stream);
+
+/* out[b][:] = table[tokens[b]][:]  (exact copy).  table [V, H] bf16; tokens [B] int32 in [0, V);
+ * out [B, H] bf16.  H % 8 == 0.  Out-of-range ids are clamped into [0, V). */
+int det_embed_gather(const void *table, const int32_t *tokens, void *out, int B, int H, int V,
+                     void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * One Llama-style decoder layer on one new token per sequence.
+ *
+ *   h = rmsnorm(x, w_norm1);  [q|k|v] = h Wqkv;  q, k = rope(q, k) at positions[b];
+ *   k, v are written into the caches at row positions[b];
+ *   a = attn_decode(q, caches, len = positions[b] + 1);
+ *   x = x + a Wo;  h = rmsnorm(x, w_norm2);  [g|u] = h Wgu;  m = swiglu(g, u);  x = x + m Wdown.
+ *
+ * Every step is the operation documented above, so the layer inherits their invariance: row b of
+ * x and sequence b's cache rows do not depend on B or on the other sequences.
+ */
+typedef struct det_layer_cfg {
+    int32_t H;      /* hidden size */
+    int32_t Hq;     /* query heads */
+    int32_t Hkv;    /* KV heads */
+    int32_t D;      /* head dim (128) */
+    int32_t F;      /* MLP inner size */
+    int32_t Lmax;   /* rows per (sequence, KV head) in the caches and in the rope tables */
+    float eps;      /* RMSNorm epsilon */
+    float scale;    /* attention score scale, normally (float)(1/sqrt(D)) */
+} det_layer_cfg;
+
+typedef struct det_layer_weights {
+    const void *w_norm1; /* [H] bf16 */
+    const void *wqkv;    /* packed [K=H, N=(Hq+2Hkv)D]; columns: q heads, k heads, v heads */
+    const void *wo;      /* packed [K=Hq*D, N=H] */
+    const void *w_norm2; /* [H] bf16 */
+    const void *wgu;     /* packed [K=H, N=2F]; columns: gate, up */
+    const void *wdown;   /* packed [K=F, N=H] */
+} det_layer_weights;
+
+size_t det_decoder_layer_workspace_bytes(const det_layer_cfg *cfg /* host */, int B);
+
+/*   w, cfg      host structs holding device pointers / sizes
+ *   x_inout     [B, H] bf16, updated in place
+ *   kcache, vcache [B, Hkv, Lmax, D] bf16, row positions[b] of every KV head of sequence b written
+ *   positions   [B] int32, 0 <= positions[b] < Lmax
+ *   rope_cos, rope_sin [Lmax, D/2] fp32
+ */
+int det_decoder_layer(const det_layer_weights *w, const det_layer_cfg *cfg, void *x_inout,
+                      void *kcache, void *vcache, const int32_t *positions, const float *rope_cos,
+                      const float *rope_sin, void *ws, size_t ws_bytes, int B, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Token bookkeeping of the greedy decode loop, on the device so a step needs no host round trip.
+ * For row b at step t:  tok = t < prompt_lens[b] ? prompts[b][t] : last_sampled[b];
+ * tokens_out[b] = tok;  history[b][t] = tok;  positions_out[b] = t.
+ *   prompts [B, Tp] int32; prompt_lens [B]; last_sampled [B] (the argmax of step t-1);
+ *   history [B, Th] int32 with t < Th.
+ */
+int det_next_token(const int32_t *prompts, int Tp, const int32_t *prompt_lens,
+                   const int32_t *last_sampled, int32_t *tokens_out, int32_t *positions_out,
+                   int32_t *history, int Th, int t, int B, void *stream);
+
+/* Build identification: target architecture, ROCm version the library was built with, and the
+ * kernel-configuration revision (echoes the paper's `system_fingerprint` response field, section
+ * 7.1).  Static storage; host pointer. */
+const char *det_fingerprint(void);
+
+/* hipError_t value of the last failed HIP call on the calling thread (0 if none). */
+int det_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DETINFER_H */

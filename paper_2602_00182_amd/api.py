@@ -1,0 +1,226 @@
+"""Argument marshalling for libdetinfer.  One function per C entry point, same name.
+
+Tensors must live on the GPU and be contiguous where the C call says so; nothing is copied or
+converted here, and no arithmetic of the method happens in Python."""
+from __future__ import annotations
+
+import ctypes as C
+
+import torch
+
+from ._lib import LayerCfg, LayerWeights, lib
+
+__all__ = [
+    "DetError", "det_gemm_bf16", "det_gemm_packed_b_bytes", "det_gemm_pack_b", "det_rmsnorm",
+    "det_attn_decode_workspace_bytes", "det_attn_decode", "det_softmax_f32", "det_argmax", "det_rope",
+    "det_swiglu", "det_residual_add", "det_embed_gather", "det_decoder_layer_workspace_bytes",
+    "det_decoder_layer", "det_next_token", "det_fingerprint", "det_last_hip_error", "layer_cfg",
+    "layer_weights", "pack_weight",
+]
+
+_CODES = {1: "DET_EINVAL", 2: "DET_ESHAPE", 3: "DET_EALIGN", 4: "DET_EWORKSPACE", 5: "DET_EHIP"}
+DET_BF16, DET_F32 = 0, 1
+
+
+class DetError(RuntimeError):
+    def __init__(self, fn: str, code: int):
+        self.code = code
+        extra = f" (hipError {lib().det_last_hip_error()})" if code == 5 else ""
+        super().__init__(f"{fn} failed: {_CODES.get(code, code)}{extra}")
+
+
+def _check(fn: str, code: int) -> None:
+    if code != 0:
+        raise DetError(fn, code)
+
+
+def _ptr(t: torch.Tensor, dtype=None) -> int:
+    if not t.is_cuda:
+        raise ValueError("libdetinfer takes device tensors")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"expected {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _contig(t: torch.Tensor, dtype=None) -> int:
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    return _ptr(t, dtype)
+
+
+def _stream(stream) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+def det_fingerprint() -> str:
+    return lib().det_fingerprint().decode()
+
+
+def det_last_hip_error() -> int:
+    return lib().det_last_hip_error()
+
+
+def det_gemm_packed_b_bytes(N: int, K: int) -> int:
+    return lib().det_gemm_packed_b_bytes(N, K)
+
+
+def det_gemm_pack_b(B_kn: torch.Tensor, B_packed: torch.Tensor, stream=None) -> None:
+    K, N = B_kn.shape
+    if B_packed.numel() * B_packed.element_size() < 2 * N * K:
+        raise ValueError("B_packed too small")
+    _check("det_gemm_pack_b", lib().det_gemm_pack_b(_contig(B_kn, torch.bfloat16), _contig(B_packed), N, K,
+                                                     _stream(stream)))
+
+
+def pack_weight(B_kn: torch.Tensor, stream=None) -> torch.Tensor:
+    """Allocates the packed buffer for a [K, N] bf16 weight and fills it with det_gemm_pack_b."""
+    K, N = B_kn.shape
+    nbytes = det_gemm_packed_b_bytes(N, K)
+    if nbytes == 0:
+        raise DetError("det_gemm_packed_b_bytes", 2)
+    out = torch.empty(nbytes // 2, dtype=torch.bfloat16, device=B_kn.device)
+    det_gemm_pack_b(B_kn, out, stream)
+    return out
+
+
+def det_gemm_bf16(A: torch.Tensor, B_packed: torch.Tensor, C_out: torch.Tensor, N: int, K: int,
+                  stream=None) -> None:
+    """C_out[M, N] = A[M, K] @ B.  A and C_out may be row-strided views (stride(1) == 1)."""
+    M = A.shape[0]
+    if A.shape[1] != K or C_out.shape != (M, N) or A.stride(1) != 1 or C_out.stride(1) != 1:
+        raise ValueError("bad GEMM operand shapes")
+    if B_packed.numel() * B_packed.element_size() < 2 * N * K:
+        raise ValueError("B_packed too small")
+    if C_out.dtype == torch.bfloat16:
+        od = DET_BF16
+    elif C_out.dtype == torch.float32:
+        od = DET_F32
+    else:
+        raise TypeError("C must be bf16 or fp32")
+    lda = A.stride(0) if M > 1 else max(A.stride(0), K)
+    ldc = C_out.stride(0) if M > 1 else max(C_out.stride(0), N)
+    _check("det_gemm_bf16", lib().det_gemm_bf16(_ptr(A, torch.bfloat16), lda, _contig(B_packed), _ptr(C_out),
+                                                 ldc, M, N, K, od, _stream(stream)))
+
+
+def det_rmsnorm(x: torch.Tensor, w: torch.Tensor, y: torch.Tensor, eps: float, stream=None) -> None:
+    M, H = x.shape
+    if w.shape != (H,) or y.shape != x.shape:
+        raise ValueError("bad RMSNorm shapes")
+    _check("det_rmsnorm", lib().det_rmsnorm(_contig(x, torch.bfloat16), _contig(w, torch.bfloat16),
+                                             _contig(y, torch.bfloat16), M, H, eps, _stream(stream)))
+
+
+def det_attn_decode_workspace_bytes(B: int, Hq: int, D: int, Lmax: int) -> int:
+    return lib().det_attn_decode_workspace_bytes(B, Hq, D, Lmax)
+
+
+def det_attn_decode(q, kcache, vcache, seqlens, out, ws, scale: float, stream=None) -> None:
+    B, Hq, D = q.shape
+    B2, Hkv, Lmax, D2 = kcache.shape
+    if (B2, D2) != (B, D) or vcache.shape != kcache.shape or out.shape != q.shape or seqlens.shape != (B,):
+        raise ValueError("bad attention shapes")
+    _check("det_attn_decode", lib().det_attn_decode(
+        _contig(q, torch.bfloat16), _contig(kcache, torch.bfloat16), _contig(vcache, torch.bfloat16),
+        _contig(seqlens, torch.int32), _contig(out, torch.bfloat16), _contig(ws),
+        ws.numel() * ws.element_size(), B, Hq, Hkv, D, Lmax, scale, _stream(stream)))
+
+
+def det_softmax_f32(s, lens, p, m_out, l_out, stream=None) -> None:
+    R, Lmax = s.shape
+    if p.shape != s.shape or lens.shape != (R,) or m_out.shape != (R,) or l_out.shape != (R,):
+        raise ValueError("bad softmax shapes")
+    _check("det_softmax_f32", lib().det_softmax_f32(
+        _contig(s, torch.float32), _contig(lens, torch.int32), _contig(p, torch.float32),
+        _contig(m_out, torch.float32), _contig(l_out, torch.float32), R, Lmax, _stream(stream)))
+
+
+def det_argmax(logits: torch.Tensor, idx: torch.Tensor, stream=None) -> None:
+    B, V = logits.shape
+    if idx.shape != (B,):
+        raise ValueError("bad argmax shapes")
+    if logits.dtype == torch.float32:
+        dt = DET_F32
+    elif logits.dtype == torch.bfloat16:
+        dt = DET_BF16
+    else:
+        raise TypeError("logits must be fp32 or bf16")
+    _check("det_argmax", lib().det_argmax(_contig(logits), _contig(idx, torch.int32), B, V, dt, _stream(stream)))
+
+
+def det_rope(x, y, pos, cos_t, sin_t, stream=None) -> None:
+    R, nh, D = x.shape
+    Lmax = cos_t.shape[0]
+    if y.shape != x.shape or pos.shape != (R,) or cos_t.shape != (Lmax, D // 2) or sin_t.shape != cos_t.shape:
+        raise ValueError("bad rope shapes")
+    _check("det_rope", lib().det_rope(_contig(x, torch.bfloat16), nh * D, _contig(y, torch.bfloat16), nh * D,
+                                       _contig(pos, torch.int32), _contig(cos_t, torch.float32),
+                                       _contig(sin_t, torch.float32), R, nh, D, Lmax, _stream(stream)))
+
+
+def det_swiglu(g, u, y, stream=None) -> None:
+    R, F = g.shape
+    if u.shape != g.shape or y.shape != g.shape or g.stride(1) != 1 or u.stride(1) != 1 or y.stride(1) != 1:
+        raise ValueError("bad swiglu shapes")
+    _check("det_swiglu", lib().det_swiglu(_ptr(g, torch.bfloat16), g.stride(0), _ptr(u, torch.bfloat16),
+                                           u.stride(0), _ptr(y, torch.bfloat16), y.stride(0), R, F,
+                                           _stream(stream)))
+
+
+def det_residual_add(x, y, z, stream=None) -> None:
+    if y.shape != x.shape or z.shape != x.shape:
+        raise ValueError("bad residual shapes")
+    _check("det_residual_add", lib().det_residual_add(_contig(x, torch.bfloat16), _contig(y, torch.bfloat16),
+                                                       _contig(z, torch.bfloat16), x.numel(), _stream(stream)))
+
+
+def det_embed_gather(table, tokens, out, stream=None) -> None:
+    V, H = table.shape
+    B = tokens.shape[0]
+    if out.shape != (B, H):
+        raise ValueError("bad embedding shapes")
+    _check("det_embed_gather", lib().det_embed_gather(_contig(table, torch.bfloat16), _contig(tokens, torch.int32),
+                                                       _contig(out, torch.bfloat16), B, H, V, _stream(stream)))
+
+
+def layer_cfg(H, Hq, Hkv, D, F, Lmax, eps, scale) -> LayerCfg:
+    return LayerCfg(H, Hq, Hkv, D, F, Lmax, eps, scale)
+
+
+def layer_weights(w_norm1, wqkv, wo, w_norm2, wgu, wdown) -> LayerWeights:
+    """Device pointers of one layer's weights (projections already packed).  The returned struct
+    does not keep the tensors alive: the caller does."""
+    return LayerWeights(*[_contig(t) for t in (w_norm1, wqkv, wo, w_norm2, wgu, wdown)])
+
+
+def det_decoder_layer_workspace_bytes(cfg: LayerCfg, B: int) -> int:
+    return lib().det_decoder_layer_workspace_bytes(C.byref(cfg), B)
+
+
+def det_decoder_layer(w: LayerWeights, cfg: LayerCfg, x, kcache, vcache, positions, rope_cos, rope_sin, ws,
+                      stream=None) -> None:
+    B = x.shape[0]
+    if x.shape != (B, cfg.H) or kcache.shape != (B, cfg.Hkv, cfg.Lmax, cfg.D) or vcache.shape != kcache.shape:
+        raise ValueError("bad layer shapes")
+    if positions.shape != (B,) or rope_cos.shape != (cfg.Lmax, cfg.D // 2) or rope_sin.shape != rope_cos.shape:
+        raise ValueError("bad layer shapes")
+    _check("det_decoder_layer", lib().det_decoder_layer(
+        C.byref(w), C.byref(cfg), _contig(x, torch.bfloat16), _contig(kcache, torch.bfloat16),
+        _contig(vcache, torch.bfloat16), _contig(positions, torch.int32), _contig(rope_cos, torch.float32),
+        _contig(rope_sin, torch.float32), _contig(ws), ws.numel() * ws.element_size(), B, _stream(stream)))
+
+
+def det_next_token(prompts, prompt_lens, last_sampled, tokens_out, positions_out, history, t: int,
+                   stream=None) -> None:
+    B, Tp = prompts.shape
+    Th = history.shape[1]
+    for a in (prompt_lens, last_sampled, tokens_out, positions_out):
+        if a.shape != (B,):
+            raise ValueError("bad next_token shapes")
+    if history.shape[0] != B:
+        raise ValueError("bad next_token shapes")
+    _check("det_next_token", lib().det_next_token(
+        _contig(prompts, torch.int32), Tp, _contig(prompt_lens, torch.int32), _contig(last_sampled, torch.int32),
+        _contig(tokens_out, torch.int32), _contig(positions_out, torch.int32), _contig(history, torch.int32),
+        Th, t, B, _stream(stream)))

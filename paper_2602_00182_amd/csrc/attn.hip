@@ -1,0 +1,323 @@
+// Single-query attention over a KV cache in fixed 256-token chunks, and the softmax statistics it
+// is built on.  Every reduction has a written order (the paper's section 6.5, invariants 2 and 3):
+// scores on the matrix cores with one accumulator chain over the head dimension, chunk sums
+// through the 256-leaf tree, chunk partials combined in ascending chunk order.  A chunk's
+// arithmetic depends on nothing but that sequence's own cache rows and length.
+#include <math.h>
+
+#include "internal.h"
+
+namespace det {
+
+constexpr int kChunk = 256;
+constexpr int kD = 128;
+
+// Softmax statistics of one chunk, one token per thread (leaf = threadIdx.x).
+//   m_c = max of the valid scores;  e = det_expf(s - m_c) for a valid token, 0 otherwise;
+//   l_c = canonical tree sum of e.   `scratch`: 4 floats of LDS.
+__device__ __forceinline__ void chunk_stats(float s, bool valid, float* scratch, float& m_c, float& e,
+                                            float& l_c)
+{
+    m_c = block_max(valid ? s : -INFINITY, scratch);
+    e = valid ? det_expf(s - m_c) : 0.0f;
+    l_c = block_tree_sum(e, scratch);
+}
+
+// Combination of chunk statistics in ascending chunk order:
+//   m = max_c m_c;  w_c = det_expf(m_c - m);  L = fold_c (L + w_c*l_c) from +0.
+__device__ __forceinline__ float combine_max(const float* mc, int nc)
+{
+    float m = mc[0];
+    for (int c = 1; c < nc; ++c) m = fmaxf(m, mc[c]);
+    return m;
+}
+
+// ------------------------------------------------------------------ attention, pass 1
+
+// Grid (chunk, kv head, sequence); 256 threads.  G = query heads per KV head.
+//   scores: wave w takes tokens 64w..64w+63 of the chunk as four 16-token blocks; the K rows are
+//           the row operand of v_mfma_f32_16x16x32_bf16 and the G query vectors (zero padded to
+//           16) its column operand; four steps cover the 128 head dimensions in ascending order
+//           (step i takes d = 32g + 8i + e for lane group g).
+//   stats : chunk_stats per head, token = thread.
+//   PV    : lane (p = lane/16, dg = lane%16) of wave w owns d = 8dg..8dg+7 and tokens
+//           64w + 4it + p, it = 0..15, folded in ascending it with fma from +0; the four p are
+//           summed as (p0+p2)+(p1+p3), then the four waves as (w0+w2)+(w1+w3).
+template <int G>
+__global__ __launch_bounds__(256) void attn_chunk_kernel(const uint16_t* __restrict__ q,
+                                                         const uint16_t* __restrict__ kcache,
+                                                         const uint16_t* __restrict__ vcache,
+                                                         const int32_t* __restrict__ seqlens,
+                                                         float* __restrict__ ws_m, float* __restrict__ ws_l,
+                                                         float* __restrict__ ws_o, int Hq, int Hkv, int Lmax,
+                                                         int ncmax, float scale, int len_offset)
+{
+    __shared__ float sc[G][kChunk];       // scores, then e_j
+    __shared__ float po[4][G][kD];        // per-wave partial outputs
+    __shared__ float scratch[4];
+
+    const int c = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+    int len = seqlens[b] + len_offset;
+    len = len > Lmax ? Lmax : len;
+    const int t0 = c * kChunk;
+    if (t0 >= len) return;  // uniform over the workgroup
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int g = lane >> 4, lr = lane & 15;
+    const size_t kv_base = ((size_t)b * Hkv + kvh) * (size_t)Lmax * kD;
+    const uint16_t* kp = kcache + kv_base;
+    const uint16_t* vp = vcache + kv_base;
+
+    // query fragments: head lr (< G) of this KV group, d = 32g + 8i + e
+    uint4 qf[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) qf[i] = make_uint4(0, 0, 0, 0);
+    if (lr < G) {
+        const uint4* qp = reinterpret_cast<const uint4*>(q + ((size_t)b * Hq + (size_t)kvh * G + lr) * kD + 32 * g);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) qf[i] = qp[i];
+    }
+
+#pragma unroll
+    for (int tb = 0; tb < 4; ++tb) {
+        const int tok = t0 + 64 * wave + 16 * tb + lr;
+        uint4 kf[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) kf[i] = make_uint4(0, 0, 0, 0);
+        if (tok < len) {
+            const uint4* kr = reinterpret_cast<const uint4*>(kp + (size_t)tok * kD + 32 * g);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) kf[i] = kr[i];
+        }
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[i]),
+                                                          __builtin_bit_cast(bf16x8, qf[i]), acc, 0, 0, 0);
+        // lane holds S[token = 16tb + 4g + v][head = lr]
+        if (lr < G) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) sc[lr][64 * wave + 16 * tb + 4 * g + v] = acc[v] * scale;
+        }
+    }
+    __syncthreads();
+
+    const bool valid = t0 + tid < len;
+    const size_t part = ((size_t)b * Hq + (size_t)kvh * G) * ncmax + c;  // + h*ncmax
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        float m_c, e, l_c;
+        chunk_stats(sc[h][tid], valid, scratch, m_c, e, l_c);
+        sc[h][tid] = e;  // only this thread reads or writes slot tid until the barrier below
+        if (tid == 0) {
+            ws_m[part + (size_t)h * ncmax] = m_c;
+            ws_l[part + (size_t)h * ncmax] = l_c;
+        }
+    }
+    __syncthreads();
+
+    float o[G][8];
+#pragma unroll
+    for (int h = 0; h < G; ++h)
+#pragma unroll
+        for (int d = 0; d < 8; ++d) o[h][d] = 0.0f;
+#pragma unroll 4
+    for (int it = 0; it < 16; ++it) {
+        const int tl = 64 * wave + 4 * it + g;
+        if (t0 + tl < len) {
+            const uint4 vv = *reinterpret_cast<const uint4*>(vp + (size_t)(t0 + tl) * kD + 8 * lr);
+            const uint32_t pw[4] = {vv.x, vv.y, vv.z, vv.w};
+            float vf[8];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                vf[2 * k] = bf16lo_to_f32(pw[k]);
+                vf[2 * k + 1] = bf16hi_to_f32(pw[k]);
+            }
+#pragma unroll
+            for (int h = 0; h < G; ++h) {
+                const float e = sc[h][tl];
+#pragma unroll
+                for (int d = 0; d < 8; ++d) o[h][d] = __builtin_fmaf(e, vf[d], o[h][d]);
+            }
+        }
+    }
+#pragma unroll
+    for (int h = 0; h < G; ++h)
+#pragma unroll
+        for (int d = 0; d < 8; ++d) {
+            float v = o[h][d];
+            v = v + __shfl_down(v, 32, kWave);
+            v = v + __shfl_down(v, 16, kWave);
+            if (g == 0) po[wave][h][8 * lr + d] = v;
+        }
+    __syncthreads();
+    for (int i = tid; i < G * kD; i += 256) {
+        const int h = i / kD, d = i % kD;
+        const float a = po[0][h][d] + po[2][h][d];
+        const float bb = po[1][h][d] + po[3][h][d];
+        ws_o[(part + (size_t)h * ncmax) * kD + d] = a + bb;
+    }
+}
+
+// ------------------------------------------------------------------ attention, pass 2
+
+// Grid (query head, sequence); 128 threads, thread = d.
+__global__ __launch_bounds__(128) void attn_combine_kernel(const int32_t* __restrict__ seqlens,
+                                                           const float* __restrict__ ws_m,
+                                                           const float* __restrict__ ws_l,
+                                                           const float* __restrict__ ws_o,
+                                                           uint16_t* __restrict__ out, int Hq, int Lmax,
+                                                           int ncmax, int len_offset)
+{
+    const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
+    int len = seqlens[b] + len_offset;
+    len = len > Lmax ? Lmax : len;
+    uint16_t* dst = out + ((size_t)b * Hq + h) * kD;
+    if (len <= 0) {
+        dst[d] = 0;
+        return;
+    }
+    const int nc = (len + kChunk - 1) / kChunk;
+    const size_t part = ((size_t)b * Hq + h) * ncmax;
+    const float m = combine_max(ws_m + part, nc);
+    float L = 0.0f, O = 0.0f;
+    for (int c = 0; c < nc; ++c) {
+        const float w = det_expf(ws_m[part + c] - m);
+        const float wl = w * ws_l[part + c];
+        L = L + wl;
+        const float wo = w * ws_o[(part + c) * kD + d];
+        O = O + wo;
+    }
+    dst[d] = f32_to_bf16_rne(O / L);
+}
+
+// ------------------------------------------------------------------ softmax on given scores
+
+constexpr int kMaxChunksHook = 1024;
+
+// One workgroup per row, chunks in ascending order; p holds e_j until the final rescale.
+__global__ __launch_bounds__(256) void softmax_kernel(const float* __restrict__ s,
+                                                      const int32_t* __restrict__ lens,
+                                                      float* __restrict__ p, float* __restrict__ m_out,
+                                                      float* __restrict__ l_out, int Lmax)
+{
+    __shared__ float mc[kMaxChunksHook];
+    __shared__ float lc[kMaxChunksHook];
+    __shared__ float scratch[4];
+    const int r = blockIdx.x, tid = threadIdx.x;
+    int len = lens[r];
+    len = len > Lmax ? Lmax : len;
+    if (len <= 0) {
+        if (tid == 0) {
+            m_out[r] = -INFINITY;
+            l_out[r] = 0.0f;
+        }
+        return;
+    }
+    const float* sr = s + (size_t)r * Lmax;
+    float* pr = p + (size_t)r * Lmax;
+    const int nc = (len + kChunk - 1) / kChunk;
+    for (int c = 0; c < nc; ++c) {
+        const int j = c * kChunk + tid;
+        const bool valid = j < len;
+        float m_c, e, l_c;
+        chunk_stats(valid ? sr[j] : 0.0f, valid, scratch, m_c, e, l_c);
+        if (valid) pr[j] = e;
+        if (tid == 0) {
+            mc[c] = m_c;
+            lc[c] = l_c;
+        }
+    }
+    __syncthreads();
+    const float m = combine_max(mc, nc);
+    float L = 0.0f;
+    for (int c = 0; c < nc; ++c) {
+        const float w = det_expf(mc[c] - m);
+        const float wl = w * lc[c];
+        L = L + wl;
+    }
+    for (int c = 0; c < nc; ++c) {
+        const int j = c * kChunk + tid;
+        if (j < len) {
+            const float w = det_expf(mc[c] - m);
+            const float we = w * pr[j];
+            pr[j] = we / L;
+        }
+    }
+    if (tid == 0) {
+        m_out[r] = m;
+        l_out[r] = L;
+    }
+}
+
+static size_t attn_ws_floats(int B, int Hq, int Lmax)
+{
+    const size_t nc = (size_t)(Lmax + kChunk - 1) / kChunk;
+    return (size_t)B * Hq * nc * (2 + kD);
+}
+
+}  // namespace det
+
+using namespace det;
+
+extern "C" size_t det_attn_decode_workspace_bytes(int B, int Hq, int D, int Lmax)
+{
+    if (B < 1 || Hq < 1 || D != kD || Lmax < 1) return 0;
+    return attn_ws_floats(B, Hq, Lmax) * sizeof(float);
+}
+
+int det::attn_decode_impl(const void* q, const void* kcache, const void* vcache, const int32_t* seqlens,
+                          int len_offset, void* out, void* ws, size_t ws_bytes, int B, int Hq, int Hkv, int D,
+                          int Lmax, float scale, hipStream_t s)
+{
+    if (!q || !kcache || !vcache || !seqlens || !out || !ws || B < 1 || Hq < 1 || Hkv < 1 || Lmax < 1)
+        return DET_EINVAL;
+    if (D != kD || Hq % Hkv != 0) return DET_ESHAPE;
+    const int G = Hq / Hkv;
+    if (G != 1 && G != 2 && G != 4 && G != 8) return DET_ESHAPE;
+    if (B > 65535 || Hkv > 65535 || Hq > 65535) return DET_ESHAPE;
+    if (!aligned16(q) || !aligned16(kcache) || !aligned16(vcache) || !aligned16(out) || !aligned16(ws))
+        return DET_EALIGN;
+    if (ws_bytes < det_attn_decode_workspace_bytes(B, Hq, D, Lmax)) return DET_EWORKSPACE;
+    const int ncmax = (Lmax + kChunk - 1) / kChunk;
+    const size_t n = (size_t)B * Hq * ncmax;
+    float* ws_m = static_cast<float*>(ws);
+    float* ws_l = ws_m + n;
+    float* ws_o = ws_l + n;
+    const dim3 grid(ncmax, Hkv, B);
+    const uint16_t* qq = static_cast<const uint16_t*>(q);
+    const uint16_t* kk = static_cast<const uint16_t*>(kcache);
+    const uint16_t* vv = static_cast<const uint16_t*>(vcache);
+#define DET_LAUNCH_ATTN(GG)                                                                            \
+    hipLaunchKernelGGL(attn_chunk_kernel<GG>, grid, dim3(256), 0, s, qq, kk, vv, seqlens, ws_m, ws_l, \
+                       ws_o, Hq, Hkv, Lmax, ncmax, scale, len_offset)
+    switch (G) {
+        case 1: DET_LAUNCH_ATTN(1); break;
+        case 2: DET_LAUNCH_ATTN(2); break;
+        case 4: DET_LAUNCH_ATTN(4); break;
+        default: DET_LAUNCH_ATTN(8); break;
+    }
+#undef DET_LAUNCH_ATTN
+    int rc = check_launch();
+    if (rc != DET_OK) return rc;
+    hipLaunchKernelGGL(attn_combine_kernel, dim3(Hq, B), dim3(128), 0, s, seqlens, ws_m, ws_l, ws_o,
+                       static_cast<uint16_t*>(out), Hq, Lmax, ncmax, len_offset);
+    return check_launch();
+}
+
+extern "C" int det_attn_decode(const void* q, const void* kcache, const void* vcache, const int32_t* seqlens,
+                               void* out, void* ws, size_t ws_bytes, int B, int Hq, int Hkv, int D, int Lmax,
+                               float scale, void* stream)
+{
+    return attn_decode_impl(q, kcache, vcache, seqlens, 0, out, ws, ws_bytes, B, Hq, Hkv, D, Lmax, scale,
+                            static_cast<hipStream_t>(stream));
+}
+
+extern "C" int det_softmax_f32(const float* s, const int32_t* lens, float* p, float* m_out, float* l_out,
+                               int R, int Lmax, void* stream)
+{
+    if (!s || !lens || !p || !m_out || !l_out || R < 1 || Lmax < 1) return DET_EINVAL;
+    if ((Lmax + kChunk - 1) / kChunk > kMaxChunksHook) return DET_ESHAPE;
+    hipLaunchKernelGGL(softmax_kernel, dim3(R), dim3(256), 0, static_cast<hipStream_t>(stream), s, lens, p,
+                       m_out, l_out, Lmax);
+    return check_launch();
+}

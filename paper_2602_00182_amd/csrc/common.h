@@ -1,0 +1,120 @@
+// Device-side building blocks shared by the kernels of libdetinfer: bf16 conversion, det_expf,
+// the canonical 256-leaf tree, and the host-side error plumbing.
+//
+// Compile with -ffp-contract=off: every fp32 operation written here is individually rounded, and a
+// fused multiply-add happens only where fmaf() is written.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/detinfer.h"
+
+namespace det {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+constexpr int kWave = 64;
+constexpr int kBlock = 256;  // threads per workgroup in every reduction kernel: 4 wavefronts
+
+// ---------------------------------------------------------------- bf16 <-> fp32
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+__device__ __forceinline__ float bf16lo_to_f32(uint32_t pair) { return __uint_as_float(pair << 16); }
+__device__ __forceinline__ float bf16hi_to_f32(uint32_t pair) { return __uint_as_float(pair & 0xFFFF0000u); }
+
+// Round to nearest, ties to even, on the upper 16 bits; NaN -> 0x7FC0; overflow -> +-inf.
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0;
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    return (uint32_t)f32_to_bf16_rne(lo) | ((uint32_t)f32_to_bf16_rne(hi) << 16);
+}
+
+// ---------------------------------------------------------------- det_expf
+
+// exp(x) built only from an fp32 multiply, round-to-nearest-integer, fused multiply-adds and an
+// integer add on the exponent field, so that it can be reproduced bit for bit anywhere:
+//   n = rint(x*log2e);  r = fma(n,-ln2_hi,x);  r = fma(n,-ln2_lo,r);
+//   p = degree-7 Taylor polynomial of exp(r), Horner form in fma;  result = p * 2^n by adding n to
+//   the exponent bits.   x > 88.72 -> +inf;  x < -87 -> 0 (no subnormal results);  NaN -> 0x7FC00000.
+__device__ __forceinline__ float det_expf(float x)
+{
+    if (x != x) return __uint_as_float(0x7FC00000u);
+    if (x > 88.72f) return __uint_as_float(0x7F800000u);
+    if (x < -87.0f) return 0.0f;
+    const float n = __builtin_rintf(x * 0x1.715476p+0f);
+    float r = __builtin_fmaf(n, -0x1.62e4p-1f, x);
+    r = __builtin_fmaf(n, -0x1.7f7d1cp-20f, r);
+    float p = 0x1.a01a02p-13f;
+    p = __builtin_fmaf(p, r, 0x1.6c16c2p-10f);
+    p = __builtin_fmaf(p, r, 0x1.111112p-7f);
+    p = __builtin_fmaf(p, r, 0x1.555556p-5f);
+    p = __builtin_fmaf(p, r, 0x1.555556p-3f);
+    p = __builtin_fmaf(p, r, 0.5f);
+    p = __builtin_fmaf(p, r, 1.0f);
+    p = __builtin_fmaf(p, r, 1.0f);
+    return __uint_as_float((uint32_t)((int32_t)__float_as_uint(p) + (int32_t)n * (1 << 23)));
+}
+
+// ---------------------------------------------------------------- canonical reductions
+
+// Stride-halving sum inside one wavefront: for off = 32,16,..,1 lane i takes lane i+off.  Lane 0
+// ends with the canonical sum of the 64 leaves; other lanes hold partial sums of no further use.
+__device__ __forceinline__ float wave_tree_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = v + __shfl_down(v, off, kWave);
+    return v;
+}
+
+// Canonical sum of 256 leaves, one per thread of a 256-thread workgroup (leaf = threadIdx.x).
+// Wave sums q0..q3 are combined as (q0+q2)+(q1+q3).  `scratch` is 4 floats of LDS; the function
+// contains the barriers it needs and returns the sum to every thread.
+__device__ __forceinline__ float block_tree_sum(float v, float* scratch)
+{
+    const float w = wave_tree_sum(v);
+    __syncthreads();  // earlier readers of scratch are done
+    if ((threadIdx.x & (kWave - 1)) == 0) scratch[threadIdx.x >> 6] = w;
+    __syncthreads();
+    const float a = scratch[0] + scratch[2];
+    const float b = scratch[1] + scratch[3];
+    return a + b;
+}
+
+// Maximum of one value per thread over a 256-thread workgroup (exact, so order free).  NaN inputs
+// are ignored by fmaxf semantics.  `scratch` is 4 floats of LDS.
+__device__ __forceinline__ float block_max(float v, float* scratch)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+    __syncthreads();
+    if ((threadIdx.x & (kWave - 1)) == 0) scratch[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return fmaxf(fmaxf(scratch[0], scratch[1]), fmaxf(scratch[2], scratch[3]));
+}
+
+// ---------------------------------------------------------------- host side
+
+void set_last_hip_error(int e);
+
+inline int check_launch()
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_last_hip_error((int)e);
+        return DET_EHIP;
+    }
+    return DET_OK;
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace det

@@ -1,0 +1,97 @@
+// One decoder layer as a fixed sequence of the library's own operations on the caller's stream.
+// Nothing here computes: the layer inherits determinism and batch invariance from its steps.
+#include "internal.h"
+
+namespace det {
+
+static size_t up256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+struct LayerWs {
+    size_t h, qkv, qbuf, att, proj, gu, mm, attn, attn_bytes, total;
+};
+
+static LayerWs layer_ws(const det_layer_cfg& c, int B)
+{
+    LayerWs w{};
+    size_t off = 0;
+    const size_t nqkv = (size_t)(c.Hq + 2 * c.Hkv) * c.D;
+    auto take = [&](size_t bytes) {
+        const size_t o = off;
+        off += up256(bytes);
+        return o;
+    };
+    w.h = take(2 * (size_t)B * c.H);
+    w.qkv = take(2 * (size_t)B * nqkv);
+    w.qbuf = take(2 * (size_t)B * c.Hq * c.D);
+    w.att = take(2 * (size_t)B * c.Hq * c.D);
+    w.proj = take(2 * (size_t)B * c.H);
+    w.gu = take(2 * (size_t)B * 2 * c.F);
+    w.mm = take(2 * (size_t)B * c.F);
+    w.attn_bytes = det_attn_decode_workspace_bytes(B, c.Hq, c.D, c.Lmax);
+    w.attn = take(w.attn_bytes);
+    w.total = off;
+    return w;
+}
+
+static bool layer_cfg_ok(const det_layer_cfg* c)
+{
+    return c && c->H > 0 && c->Hq > 0 && c->Hkv > 0 && c->D == 128 && c->F > 0 && c->Lmax > 0 &&
+           c->Hq % c->Hkv == 0 && c->H % 64 == 0 && c->F % 64 == 0;
+}
+
+}  // namespace det
+
+using namespace det;
+
+extern "C" size_t det_decoder_layer_workspace_bytes(const det_layer_cfg* cfg, int B)
+{
+    if (!layer_cfg_ok(cfg) || B < 1) return 0;
+    return layer_ws(*cfg, B).total;
+}
+
+extern "C" int det_decoder_layer(const det_layer_weights* w, const det_layer_cfg* cfg, void* x_inout,
+                                 void* kcache, void* vcache, const int32_t* positions, const float* rope_cos,
+                                 const float* rope_sin, void* ws, size_t ws_bytes, int B, void* stream)
+{
+    if (!w || !cfg || !x_inout || !kcache || !vcache || !positions || !rope_cos || !rope_sin || !ws || B < 1)
+        return DET_EINVAL;
+    if (!w->w_norm1 || !w->wqkv || !w->wo || !w->w_norm2 || !w->wgu || !w->wdown) return DET_EINVAL;
+    if (!layer_cfg_ok(cfg)) return DET_ESHAPE;
+    if (!aligned16(ws) || !aligned16(x_inout)) return DET_EALIGN;
+    const det_layer_cfg c = *cfg;
+    const LayerWs l = layer_ws(c, B);
+    if (ws_bytes < l.total) return DET_EWORKSPACE;
+    char* base = static_cast<char*>(ws);
+    void* h = base + l.h;
+    void* qkv = base + l.qkv;
+    void* qbuf = base + l.qbuf;
+    void* att = base + l.att;
+    void* proj = base + l.proj;
+    uint16_t* gu = reinterpret_cast<uint16_t*>(base + l.gu);
+    void* mm = base + l.mm;
+    void* aws = base + l.attn;
+    const int nqkv = (c.Hq + 2 * c.Hkv) * c.D;
+    const int nq = c.Hq * c.D;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int rc;
+#define DET_TRY(call)                \
+    do {                             \
+        rc = (call);                 \
+        if (rc != DET_OK) return rc; \
+    } while (0)
+    DET_TRY(det_rmsnorm(x_inout, w->w_norm1, h, B, c.H, c.eps, stream));
+    DET_TRY(det_gemm_bf16(h, c.H, w->wqkv, qkv, nqkv, B, nqkv, c.H, DET_BF16, stream));
+    DET_TRY(rope_append(qkv, qbuf, kcache, vcache, positions, rope_cos, rope_sin, B, c.Hq, c.Hkv, c.D, c.Lmax,
+                        s));
+    DET_TRY(attn_decode_impl(qbuf, kcache, vcache, positions, 1, att, aws, l.attn_bytes, B, c.Hq, c.Hkv, c.D,
+                             c.Lmax, c.scale, s));
+    DET_TRY(det_gemm_bf16(att, nq, w->wo, proj, c.H, B, c.H, nq, DET_BF16, stream));
+    DET_TRY(det_residual_add(x_inout, proj, x_inout, (int64_t)B * c.H, stream));
+    DET_TRY(det_rmsnorm(x_inout, w->w_norm2, h, B, c.H, c.eps, stream));
+    DET_TRY(det_gemm_bf16(h, c.H, w->wgu, gu, 2 * c.F, B, 2 * c.F, c.H, DET_BF16, stream));
+    DET_TRY(det_swiglu(gu, 2 * c.F, gu + c.F, 2 * c.F, mm, c.F, B, c.F, stream));
+    DET_TRY(det_gemm_bf16(mm, c.F, w->wdown, proj, c.H, B, c.H, c.F, DET_BF16, stream));
+    DET_TRY(det_residual_add(x_inout, proj, x_inout, (int64_t)B * c.H, stream));
+#undef DET_TRY
+    return DET_OK;
+}

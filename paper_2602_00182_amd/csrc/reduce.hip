@@ -1,0 +1,131 @@
+// RMSNorm and greedy argmax: one 256-thread workgroup per row, canonical tree reductions (the
+// paper's section 6.5, invariant 2, with the shuffle loop written for a 64-wide wavefront).
+#include "common.h"
+
+namespace det {
+
+constexpr int kMaxVecPerThread = 8;  // H <= 8 * 256 * 8 = 16384
+
+// Row i: thread t owns the 8-element vectors t, t+256, ... (element e -> lane (e/8) mod 256) and
+// folds them in ascending e with fma(x,x,acc); then the 256-leaf tree; then
+// y = bf16((x*r)*w) with r = 1/sqrt(ss/H + eps).
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const uint4* __restrict__ x,
+                                                      const uint4* __restrict__ w,
+                                                      uint4* __restrict__ y, int H, float eps)
+{
+    __shared__ float scratch[4];
+    const int nvec = H >> 3;
+    const uint4* xr = x + (size_t)blockIdx.x * nvec;
+    uint4* yr = y + (size_t)blockIdx.x * nvec;
+
+    uint4 xv[kMaxVecPerThread];
+    float acc = 0.0f;
+#pragma unroll
+    for (int i = 0; i < kMaxVecPerThread; ++i) {
+        const int v = threadIdx.x + i * 256;
+        if (v < nvec) {
+            xv[i] = xr[v];
+            const uint32_t p[4] = {xv[i].x, xv[i].y, xv[i].z, xv[i].w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float lo = bf16lo_to_f32(p[k]);
+                const float hi = bf16hi_to_f32(p[k]);
+                acc = __builtin_fmaf(lo, lo, acc);
+                acc = __builtin_fmaf(hi, hi, acc);
+            }
+        }
+    }
+    const float ss = block_tree_sum(acc, scratch);
+    const float mean = ss / (float)H;
+    const float r = 1.0f / __builtin_sqrtf(mean + eps);
+#pragma unroll
+    for (int i = 0; i < kMaxVecPerThread; ++i) {
+        const int v = threadIdx.x + i * 256;
+        if (v < nvec) {
+            const uint4 wv = w[v];
+            const uint32_t p[4] = {xv[i].x, xv[i].y, xv[i].z, xv[i].w};
+            const uint32_t q[4] = {wv.x, wv.y, wv.z, wv.w};
+            uint32_t o[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float lo = (bf16lo_to_f32(p[k]) * r) * bf16lo_to_f32(q[k]);
+                const float hi = (bf16hi_to_f32(p[k]) * r) * bf16hi_to_f32(q[k]);
+                o[k] = pack_bf16x2(lo, hi);
+            }
+            yr[v] = make_uint4(o[0], o[1], o[2], o[3]);
+        }
+    }
+}
+
+// (value, index) pair ordering: larger value wins; on equal values the smaller index wins.
+// The operation is associative and commutative, so the reduction shape does not matter.
+__device__ __forceinline__ void argmax_merge(float& bv, int& bi, float v, int i)
+{
+    if (i >= 0 && (bi < 0 || v > bv || (v == bv && i < bi))) {
+        bv = v;
+        bi = i;
+    }
+}
+
+template <bool F32>
+__global__ __launch_bounds__(256) void argmax_kernel(const void* __restrict__ logits,
+                                                     int32_t* __restrict__ idx, int V)
+{
+    __shared__ float sv[4];
+    __shared__ int si[4];
+    float bv = 0.0f;
+    int bi = -1;  // -1: nothing but NaN seen so far
+    for (int j = threadIdx.x; j < V; j += 256) {
+        float v;
+        if (F32)
+            v = static_cast<const float*>(logits)[(size_t)blockIdx.x * V + j];
+        else
+            v = bf16_to_f32(static_cast<const uint16_t*>(logits)[(size_t)blockIdx.x * V + j]);
+        if (v == v && (bi < 0 || v > bv)) {  // ascending j: strict > keeps the lowest index
+            bv = v;
+            bi = j;
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const float ov = __shfl_xor(bv, off, kWave);
+        const int oi = __shfl_xor(bi, off, kWave);
+        argmax_merge(bv, bi, ov, oi);
+    }
+    if ((threadIdx.x & 63) == 0) {
+        sv[threadIdx.x >> 6] = bv;
+        si[threadIdx.x >> 6] = bi;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int k = 1; k < 4; ++k) argmax_merge(bv, bi, sv[k], si[k]);
+        idx[blockIdx.x] = bi < 0 ? 0 : bi;
+    }
+}
+
+}  // namespace det
+
+using namespace det;
+
+extern "C" int det_rmsnorm(const void* x, const void* w, void* y, int M, int H, float eps, void* stream)
+{
+    if (!x || !w || !y || M < 1 || H < 1) return DET_EINVAL;
+    if (H % 8 != 0 || H > 8 * 256 * kMaxVecPerThread) return DET_ESHAPE;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return DET_EALIGN;
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint4*>(x), static_cast<const uint4*>(w), static_cast<uint4*>(y),
+                       H, eps);
+    return check_launch();
+}
+
+extern "C" int det_argmax(const void* logits, int32_t* idx, int B, int V, int dtype, void* stream)
+{
+    if (!logits || !idx || B < 1 || V < 1) return DET_EINVAL;
+    if (dtype != DET_BF16 && dtype != DET_F32) return DET_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (dtype == DET_F32)
+        hipLaunchKernelGGL(argmax_kernel<true>, dim3(B), dim3(256), 0, s, logits, idx, V);
+    else
+        hipLaunchKernelGGL(argmax_kernel<false>, dim3(B), dim3(256), 0, s, logits, idx, V);
+    return check_launch();
+}

@@ -1,0 +1,124 @@
+"""det_attn_decode against the fp64 oracle (bound: |err| <= 2^-8 |ref| + 2^-20 sum_j p_j |v_jd|),
+its closed forms, and byte equality of a (sequence, head) across batch compositions."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import detsynth as ds
+from gpu_util import DEV, bits_to_f64, down_bf16, step, up, up_bf16, within_bound
+
+pytestmark = pytest.mark.gpu
+
+SCALE = float(np.float32(1.0 / math.sqrt(128.0)))
+
+
+@pytest.fixture(scope="module")
+def d():
+    import paper_2602_00182_amd as d
+    return d
+
+
+def run_attn(d, q, k, v, lens, scale=SCALE, poison_ws=False):
+    B, Hq, D = q.shape
+    Lmax = k.shape[2]
+    ws = torch.empty(d.det_attn_decode_workspace_bytes(B, Hq, D, Lmax), dtype=torch.uint8, device=DEV)
+    if poison_ws:
+        ws.fill_(0xFF)
+    out = torch.empty((B, Hq, D), dtype=torch.bfloat16, device=DEV)
+    d.det_attn_decode(up_bf16(q), up_bf16(k), up_bf16(v), up(np.asarray(lens, dtype=np.int32)), out, ws, scale)
+    torch.cuda.synchronize()
+    return down_bf16(out)
+
+
+def inputs(seed, B, Hq, Hkv, Lmax, D=128):
+    return (ds.normal_bf16(seed, (B, Hq, D)), ds.normal_bf16(seed + 1, (B, Hkv, Lmax, D)),
+            ds.normal_bf16(seed + 2, (B, Hkv, Lmax, D)))
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,Lmax,lens", [
+    (1, 32, 8, 512, [512]),
+    (4, 32, 8, 1024, [1, 255, 257, 1024]),
+    (3, 8, 8, 600, [600, 513, 256]),
+    (2, 16, 8, 300, [300, 2]),
+    (2, 16, 2, 768, [700, 511]),
+    (16, 32, 8, 4096, None),
+])
+def test_attention_vs_oracle(d, orc, B, Hq, Hkv, Lmax, lens):
+    q, k, v = inputs(ds.tensor_seed(3, 10) + Lmax + B, B, Hq, Hkv, Lmax)
+    if lens is None:   # ragged: lengths uniform in [1, Lmax]
+        lens = ds.uniform_int(ds.tensor_seed(3, 13), (B,), 1, Lmax)
+        lens[0] = Lmax
+    step(f"attention B={B} Hq={Hq} Hkv={Hkv} Lmax={Lmax}")
+    got = run_attn(d, q, k, v, lens, poison_ws=True)
+    ref, refabs = orc.attn_decode_f64(q, k, v, lens, SCALE)
+    ok = within_bound(bits_to_f64(got), ref, refabs)
+    assert ok.all(), f"{(~ok).sum()} of {ok.size} outside the bound"
+
+
+def test_attention_closed_forms(d, orc):
+    B, Hq, Hkv, Lmax = 2, 32, 8, 1024
+    q, k, v = inputs(500, B, Hq, Hkv, Lmax)
+    step("attention len=1")
+    got = run_attn(d, q, k, v, [1, 1])
+    for h in range(Hq):
+        assert np.array_equal(got[0, h], v[0, h // 4, 0]) and np.array_equal(got[1, h], v[1, h // 4, 0])
+    step("attention len=0")
+    got = run_attn(d, q, k, v, [0, 5])
+    assert np.all(got[0] == 0)
+    step("attention uniform scores")
+    vi = ds.small_int_bf16(501, (B, Hkv, Lmax, 128), -8, 8)    # integer V: column sums exact in fp32
+    got = run_attn(d, np.zeros_like(q), k, vi, [1024, 512])
+    vf = ds.bf16_bits_to_f32(vi).astype(np.float64)
+    for b, n in [(0, 1024), (1, 512)]:
+        want = orc.bf16_rne((vf[b, :, :n].sum(axis=1) / n).astype(np.float32))   # exact: n is 2^k
+        for h in range(Hq):
+            assert np.array_equal(got[b, h], want[h // 4])
+    step("attention dominant key")
+    k2 = k.copy()
+    qf = ds.bf16_bits_to_f32(q)
+    k2[0, 2, 700] = ds.f32_to_bf16_bits(qf[0, 8] * 64)   # head 8 reads KV head 2
+    got = run_attn(d, q, k2, v, [1024, 1024], scale=1.0)
+    assert np.array_equal(got[0, 8], v[0, 2, 700])
+
+
+def test_cache_past_len_is_ignored_and_batch_invariance(d, orc):
+    B, Hq, Hkv, Lmax = 16, 32, 8, 2048
+    q, k, v = inputs(510, B, Hq, Hkv, Lmax)
+    lens = ds.uniform_int(511, (B,), 1, Lmax)
+    lens[3] = 777
+    step("attention batch 16")
+    base = run_attn(d, q, k, v, lens)
+    k2, v2 = k.copy(), v.copy()
+    for b in range(B):
+        k2[b, :, lens[b]:] = 0x7FC0     # NaN patterns past the length
+        v2[b, :, lens[b]:] = 0xFF80     # -inf
+    step("attention batch 16, poisoned tails")
+    assert np.array_equal(run_attn(d, q, k2, v2, lens), base)
+    step("attention sequence 3 alone")
+    alone = run_attn(d, q[3:4], k[3:4], v[3:4], lens[3:4])
+    assert np.array_equal(alone[0], base[3])
+    step("attention sequence 3 in another slot among other sequences")
+    q3, k3, v3 = inputs(520, 5, Hq, Hkv, Lmax)
+    q3[4], k3[4], v3[4] = q[3], k[3], v[3]
+    other = run_attn(d, q3, k3, v3, [5, 2048, 1, 300, lens[3]])
+    assert np.array_equal(other[4], base[3])
+    step("attention repeat x20")
+    for _ in range(20):
+        assert np.array_equal(run_attn(d, q, k, v, lens, poison_ws=True), base)
+
+
+def test_long_context_sampled(d, orc):
+    """L = 32768 at B = 2 (128 chunks per sequence): the oracle on sampled (sequence, head) pairs."""
+    B, Hq, Hkv, Lmax = 2, 32, 8, 32768
+    q, k, v = inputs(530, B, Hq, Hkv, Lmax)
+    lens = [32768, 30001]
+    step("attention L=32768")
+    got = run_attn(d, q, k, v, lens)
+    for b, heads in [(0, [0, 13, 31]), (1, [5, 22])]:
+        for h in heads:
+            g = h // 4
+            ref, refabs = orc.attn_decode_f64(q[b:b + 1, h:h + 1], k[b:b + 1, g:g + 1], v[b:b + 1, g:g + 1],
+                                              lens[b:b + 1], SCALE)
+            assert within_bound(bits_to_f64(got[b, h]), ref[0, 0], refabs[0, 0]).all()

@@ -1,0 +1,220 @@
+"""det_gemm_bf16 on the GPU against the fp64 oracle, and its determinism / batch-invariance
+contract (byte equality, never allclose).  Bound for floating point, from the benchmark spec:
+|err| <= 2^-8 |ref| + 2^-20 sum_k |a_ik b_kj|."""
+import numpy as np
+import pytest
+import torch
+
+import detsynth as ds
+from gpu_util import DEV, bits_to_f64, down_bf16, step, up_bf16, within_bound
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def d():
+    import paper_2602_00182_amd as d
+    return d
+
+
+def run_gemm(d, A_bits, B_bits, out_f32=False, lda=None):
+    """Packs B, runs the GEMM, returns bf16 bits (or fp32) as numpy."""
+    M, K = A_bits.shape
+    N = B_bits.shape[1]
+    Bp = d.pack_weight(up_bf16(B_bits))
+    if lda is None:
+        A = up_bf16(A_bits)
+    else:
+        buf = torch.zeros((M, lda), dtype=torch.bfloat16, device=DEV)
+        buf[:, :K] = up_bf16(A_bits)
+        A = buf[:, :K]
+    C = torch.empty((M, N), dtype=torch.float32 if out_f32 else torch.bfloat16, device=DEV)
+    d.det_gemm_bf16(A, Bp, C, N, K)
+    torch.cuda.synchronize()
+    return C.cpu().numpy() if out_f32 else down_bf16(C)
+
+
+def test_config1_tolerance_and_row_bytes(d, orc):
+    """A [16,512], B [512,512] ~ N(0,1)/sqrt(512); rerun at M=1 and M=64: shared rows keep their bytes."""
+    K = N = 512
+    s = 1.0 / np.sqrt(K)
+    A = ds.normal_bf16(ds.tensor_seed(1, 0), (16, K), s)
+    Bm = ds.normal_bf16(ds.tensor_seed(1, 1), (K, N), s)
+    step("gemm config 1 M=16")
+    C16 = run_gemm(d, A, Bm)
+    ref, refabs = orc.gemm_f64(A, Bm)
+    assert within_bound(bits_to_f64(C16), ref, refabs).all()
+    step("gemm config 1 M=1")
+    C1 = run_gemm(d, A[:1], Bm)
+    assert np.array_equal(C1[0], C16[0])
+    extra = ds.normal_bf16(ds.tensor_seed(1, 2), (48, K), s)
+    A64 = np.concatenate([A, extra], axis=0)
+    step("gemm config 1 M=64")
+    C64 = run_gemm(d, A64, Bm)
+    assert np.array_equal(C64[:16], C16)
+    ref, refabs = orc.gemm_f64(A64, Bm)
+    assert within_bound(bits_to_f64(C64), ref, refabs).all()
+
+
+@pytest.mark.parametrize("M,N,K", [
+    (1, 16, 64), (5, 48, 64), (16, 512, 512), (17, 4096, 128), (100, 7680, 192), (33, 28672, 64),
+    (257, 64, 1088), (300, 3840 * 2, 64), (64, 32000, 128), (256, 4096, 2048 + 64),
+    (20, 11520, 64), (20, 16000, 128), (35, 20000, 64), (70, 24000, 192),
+])
+def test_integer_matrices_are_exact(d, orc, M, N, K):
+    """Entries in -4..4: every summation order gives the exact integer (|sum| < 2^24), so the GPU
+    bytes must equal bf16_rne(exact).  Pins layout, packing, K coverage, masking of ragged M and
+    round-to-nearest-even of the output."""
+    A = ds.small_int_bf16(100 + M, (M, K))
+    Bm = ds.small_int_bf16(200 + N, (K, N))
+    exact = ds.bf16_bits_to_f32(A).astype(np.int64) @ ds.bf16_bits_to_f32(Bm).astype(np.int64)
+    want = orc.bf16_rne(exact.astype(np.float32))
+    step(f"gemm integer exact M={M} N={N} K={K}")
+    got = run_gemm(d, A, Bm)
+    assert np.array_equal(got, want)
+    got32 = run_gemm(d, A, Bm, out_f32=True)
+    assert np.array_equal(got32, exact.astype(np.float32))
+
+
+def test_rne_ties_and_identity(d, orc):
+    """Identity weights copy A; a product of 257 must round to 256 (tie to even)."""
+    K = N = 256
+    A = ds.normal_bf16(301, (40, K))
+    eye = ds.f32_to_bf16_bits(np.eye(K, dtype=np.float32))
+    step("gemm identity")
+    assert np.array_equal(run_gemm(d, A, eye), A)
+    a = np.zeros((1, K), dtype=np.float32)
+    a[0, :257 - 1] = 1.0  # 256 ones ...
+    b = np.zeros((K, N), dtype=np.float32)
+    b[:, 0] = 1.0
+    b[0, 0] = 2.0        # ... one of them weighted 2 -> sum 257
+    b[:, 1] = 1.0
+    b[0, 1] = 4.0        # 259 -> tie between 258 and 260 -> 260
+    got = run_gemm(d, ds.f32_to_bf16_bits(a), ds.f32_to_bf16_bits(b))
+    assert ds.bf16_bits_to_f32(got[0, :2]).tolist() == [256.0, 260.0]
+
+
+def test_strided_a_and_lda(d, orc):
+    K, N, M = 512, 4096, 37
+    A = ds.normal_bf16(311, (M, K))
+    Bm = ds.normal_bf16(312, (K, N), 0.02)
+    step("gemm strided A")
+    assert np.array_equal(run_gemm(d, A, Bm), run_gemm(d, A, Bm, lda=K + 64))
+
+
+def _llama_case(K, N, Mmax=256):
+    W = ds.normal_bf16(ds.tensor_seed(2, K // 64 + N), (K, N), 0.02)
+    X = ds.normal_bf16(ds.tensor_seed(2, 7), (Mmax, K))
+    return X, W
+
+
+@pytest.mark.parametrize("K,N", [(4096, 4096), (4096, 6144), (4096, 28672), (14336, 4096)])
+def test_llama_shapes_sampled_vs_oracle_and_batch_invariance(d, orc, K, N):
+    """Full-size projection GEMMs: M swept over 1..256 with the first M rows of one X, every row's
+    bytes identical at every M; a seeded sample of outputs against the fp64 oracle."""
+    X, W = _llama_case(K, N)
+    Wp = d.pack_weight(up_bf16(W))
+    Xd = up_bf16(X)
+    outs = {}
+    for M in [1, 2, 4, 8, 16, 32, 64, 128, 256]:
+        step(f"gemm llama K={K} N={N} M={M}")
+        C = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+        d.det_gemm_bf16(Xd[:M], Wp, C, N, K)
+        torch.cuda.synchronize()
+        outs[M] = down_bf16(C)
+    full = outs[256]
+    for M, c in outs.items():
+        assert np.array_equal(c, full[:M]), f"rows changed between M={M} and M=256"
+    rng = np.random.default_rng(K + N)
+    rows = rng.integers(0, 256, 4096).astype(np.int32)
+    cols = rng.integers(0, N, 4096).astype(np.int32)
+    rows[:64] = np.arange(64) * 4
+    cols[:64] = N - 1 - np.arange(64)
+    ref, refabs = orc.gemm_f64_sample(X, W, rows, cols)
+    got = bits_to_f64(full[rows, cols])
+    assert within_bound(got, ref, refabs).all()
+
+
+def test_rows_do_not_see_each_other(d, orc):
+    """Row i's bytes are unchanged when the other rows are replaced, when row i moves to another
+    slot, and when M is not a multiple of the row block."""
+    K, N = 4096, 4096
+    X, W = _llama_case(K, N)
+    Wp = d.pack_weight(up_bf16(W))
+
+    def gemm(Xb):
+        C = torch.empty((Xb.shape[0], N), dtype=torch.bfloat16, device=DEV)
+        d.det_gemm_bf16(up_bf16(Xb), Wp, C, N, K)
+        torch.cuda.synchronize()
+        return down_bf16(C)
+
+    step("gemm row isolation")
+    base = gemm(X[:200])
+    other = ds.normal_bf16(999, (200, K), 3.0)
+    other[57] = X[57]
+    assert np.array_equal(gemm(other)[57], base[57])
+    nanrows = X[:200].copy()
+    nanrows[:] = 0x7FC0
+    nanrows[130] = X[130]
+    assert np.array_equal(gemm(nanrows)[130], base[130])
+    perm = np.random.default_rng(5).permutation(200)
+    assert np.array_equal(gemm(X[:200][perm]), base[perm])
+    assert np.array_equal(gemm(X[:93]), base[:93])
+    big = np.concatenate([X, X[:77]], axis=0)  # M = 333 > 256: second row tile
+    out = gemm(big)
+    assert np.array_equal(out[:200], base) and np.array_equal(out[256:], base[:77])
+
+
+def test_repeat_streams_launch_order_and_background_load(d, orc):
+    """100 repeats, three streams, shuffled launch order and a bandwidth hog on another stream:
+    every result byte-identical (the paper's same-host, batch and stress conditions, section 6.7,
+    10.1 and 10.2)."""
+    K, N = 4096, 6144
+    X, W = _llama_case(K, N)
+    Wp = d.pack_weight(up_bf16(W))
+    Xd = up_bf16(X)
+    Ms = [1, 8, 64, 256]
+    want = {}
+    for M in Ms:
+        C = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+        d.det_gemm_bf16(Xd[:M], Wp, C, N, K)
+        want[M] = C.clone()
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(device=DEV) for _ in range(3)]
+    hog_stream = torch.cuda.Stream(device=DEV)
+    hog = torch.empty(256 << 20, dtype=torch.uint8, device=DEV)
+    rng = np.random.default_rng(9)
+    mismatches = 0
+    step("gemm 100 repeats over 3 streams with background copies")
+    for rep in range(100):
+        with torch.cuda.stream(hog_stream):
+            hog.copy_(hog.flip(0) if rep % 10 == 0 else hog)
+        order = rng.permutation(len(Ms))
+        outs = []
+        for j in order:
+            M = Ms[j]
+            st = streams[(rep + j) % 3]
+            C = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+            with torch.cuda.stream(st):
+                d.det_gemm_bf16(Xd[:M], Wp, C, N, K)
+            outs.append((M, C))
+        torch.cuda.synchronize()
+        for M, C in outs:
+            mismatches += int(not torch.equal(C.view(torch.int16), want[M].view(torch.int16)))
+    assert mismatches == 0
+
+
+def test_error_codes(d):
+    A = torch.zeros((4, 64), dtype=torch.bfloat16, device=DEV)
+    Bp = torch.zeros(64 * 16, dtype=torch.bfloat16, device=DEV)
+    C = torch.zeros((4, 16), dtype=torch.bfloat16, device=DEV)
+    lib = d.api.lib()
+    s = torch.cuda.current_stream().cuda_stream
+    assert lib.det_gemm_bf16(A.data_ptr(), 64, Bp.data_ptr(), C.data_ptr(), 16, 4, 16, 64, 0, s) == 0
+    assert lib.det_gemm_bf16(A.data_ptr(), 64, Bp.data_ptr(), C.data_ptr(), 16, 4, 24, 64, 0, s) == 2
+    assert lib.det_gemm_bf16(A.data_ptr(), 64, Bp.data_ptr(), C.data_ptr(), 16, 4, 16, 96, 0, s) == 2
+    assert lib.det_gemm_bf16(A.data_ptr() + 2, 64, Bp.data_ptr(), C.data_ptr(), 16, 4, 16, 64, 0, s) == 3
+    assert lib.det_gemm_bf16(None, 64, Bp.data_ptr(), C.data_ptr(), 16, 4, 16, 64, 0, s) == 1
+    assert lib.det_gemm_bf16(A.data_ptr(), 64, Bp.data_ptr(), C.data_ptr(), 16, 0, 16, 64, 0, s) == 1
+    assert lib.det_gemm_bf16(A.data_ptr(), 64, Bp.data_ptr(), C.data_ptr(), 16, 4, 16, 64, 7, s) == 1
+    torch.cuda.synchronize()
