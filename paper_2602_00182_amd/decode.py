@@ -1,0 +1,115 @@
+"""Greedy decode loop over libdetinfer (host orchestration only: every step runs in the library's
+kernels, on one stream, with no host round trip inside the loop).
+
+One step, for B sequences at step t (the paper's section 6.6: greedy decoding in a fixed order):
+    token select -> embedding gather -> L x decoder layer -> final RMSNorm -> lm_head GEMM (fp32
+    logits) -> argmax.
+Prompts are fed through the same step one token at a time, so a sequence's bytes are those of the
+single-sequence run whatever batch it sits in."""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import torch
+
+from . import api
+
+
+@dataclass
+class ModelCfg:
+    H: int
+    Hq: int
+    Hkv: int
+    D: int
+    F: int
+    V: int
+    n_layers: int
+    eps: float = 1e-5
+    scale: float = 0.08838834764831845  # 1/sqrt(128)
+
+
+class DecodeModel:
+    """Weights of a Llama-style decoder, packed for det_gemm_bf16.
+
+    `weights` holds logical row-major bf16 tensors on the GPU:
+        embed [V,H], lm_head [H,V], final_norm [H], and per layer i:
+        layers[i] = dict(norm1 [H], wqkv [H,(Hq+2Hkv)D], wo [Hq*D,H], norm2 [H], wgu [H,2F], wdown [F,H])
+    """
+
+    def __init__(self, cfg: ModelCfg, weights: dict):
+        self.cfg = cfg
+        self.embed = weights["embed"].contiguous()
+        self.final_norm = weights["final_norm"].contiguous()
+        self.lm_head = api.pack_weight(weights["lm_head"])
+        self.layers = []
+        for lw in weights["layers"]:
+            packed = dict(norm1=lw["norm1"].contiguous(), wqkv=api.pack_weight(lw["wqkv"]),
+                          wo=api.pack_weight(lw["wo"]), norm2=lw["norm2"].contiguous(),
+                          wgu=api.pack_weight(lw["wgu"]), wdown=api.pack_weight(lw["wdown"]))
+            struct = api.layer_weights(packed["norm1"], packed["wqkv"], packed["wo"], packed["norm2"],
+                                       packed["wgu"], packed["wdown"])
+            self.layers.append((packed, struct))
+
+    def new_state(self, B: int, Lmax: int, rope_cos: torch.Tensor, rope_sin: torch.Tensor):
+        return DecodeState(self, B, Lmax, rope_cos, rope_sin)
+
+
+class DecodeState:
+    """KV caches, workspace and step buffers for B sequences of up to Lmax tokens."""
+
+    def __init__(self, model: DecodeModel, B: int, Lmax: int, rope_cos, rope_sin):
+        c = model.cfg
+        dev = model.embed.device
+        self.model, self.B, self.Lmax = model, B, Lmax
+        self.lcfg = api.layer_cfg(c.H, c.Hq, c.Hkv, c.D, c.F, Lmax, c.eps, c.scale)
+        if rope_cos.shape != (Lmax, c.D // 2):
+            raise ValueError("rope tables must be [Lmax, D/2]")
+        self.rope_cos, self.rope_sin = rope_cos, rope_sin
+        self.kcache = [torch.zeros((B, c.Hkv, Lmax, c.D), dtype=torch.bfloat16, device=dev)
+                       for _ in range(c.n_layers)]
+        self.vcache = [torch.zeros_like(k) for k in self.kcache]
+        self.ws = torch.empty(api.det_decoder_layer_workspace_bytes(self.lcfg, B), dtype=torch.uint8, device=dev)
+        self.x = torch.empty((B, c.H), dtype=torch.bfloat16, device=dev)
+        self.xn = torch.empty((B, c.H), dtype=torch.bfloat16, device=dev)
+        self.logits = torch.empty((B, c.V), dtype=torch.float32, device=dev)
+        self.tokens = torch.empty(B, dtype=torch.int32, device=dev)
+        self.positions = torch.empty(B, dtype=torch.int32, device=dev)
+
+    def forward(self, stream=None):
+        """One decode step on self.tokens / self.positions; leaves fp32 logits in self.logits."""
+        m, c = self.model, self.model.cfg
+        api.det_embed_gather(m.embed, self.tokens, self.x, stream)
+        for i, (_, struct) in enumerate(m.layers):
+            api.det_decoder_layer(struct, self.lcfg, self.x, self.kcache[i], self.vcache[i], self.positions,
+                                  self.rope_cos, self.rope_sin, self.ws, stream)
+        api.det_rmsnorm(self.x, m.final_norm, self.xn, c.eps, stream)
+        api.det_gemm_bf16(self.xn, m.lm_head, self.logits, c.V, c.H, stream)
+
+
+def greedy_decode(model: DecodeModel, prompts: torch.Tensor, prompt_lens: torch.Tensor, n_new: int,
+                  rope_cos: torch.Tensor, rope_sin: torch.Tensor, keep_logits_at=(), stream=None):
+    """Runs B sequences together.  prompts [B, Tp] int32 (padded), prompt_lens [B] int32.
+
+    Returns (generated [B, n_new] int32 on the device, {step: logits [B, V] fp32 clone}).
+    Step t feeds prompt token t while t < len, else the token sampled at step t-1; sequence b's
+    generated tokens are the samples of steps len_b-1 .. len_b+n_new-2."""
+    B, Tp = prompts.shape
+    lens_host = prompt_lens.cpu()
+    T = int(lens_host.max()) + n_new - 1
+    if rope_cos.shape[0] < T:
+        raise ValueError("rope tables shorter than the run")
+    st = model.new_state(B, T, rope_cos[:T].contiguous(), rope_sin[:T].contiguous())
+    dev = prompts.device
+    sampled = torch.zeros((T, B), dtype=torch.int32, device=dev)
+    history = torch.zeros((B, T), dtype=torch.int32, device=dev)
+    kept = {}
+    for t in range(T):
+        last = sampled[t - 1] if t > 0 else sampled[0]
+        api.det_next_token(prompts, prompt_lens, last, st.tokens, st.positions, history, t, stream)
+        st.forward(stream)
+        api.det_argmax(st.logits, sampled[t], stream)
+        if t in keep_logits_at:
+            kept[t] = st.logits.clone()
+    idx = (lens_host.to(torch.int64) - 1)[:, None] + torch.arange(n_new)[None, :]
+    gen = sampled.t().contiguous().gather(1, idx.to(dev))
+    return gen, kept

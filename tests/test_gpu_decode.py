@@ -1,0 +1,83 @@
+"""Greedy decode of a random-init 8-layer Llama-style model: token streams (and logits bytes) of a
+prompt are identical whether it runs alone or batched at 8 / 32 / 64 (the paper's end-to-end
+determinism experiments, section 6.7, with batch composition as the perturbation)."""
+import numpy as np
+import pytest
+import torch
+
+import detsynth as ds
+from gpu_util import DEV, step, up
+
+pytestmark = pytest.mark.gpu
+
+H, HQ, HKV, D, F, V, NL = 2048, 16, 4, 128, 5632, 32000, 8
+N_PROMPTS, N_NEW = 64, 128
+
+
+@pytest.fixture(scope="module")
+def model():
+    from paper_2602_00182_amd.decode import DecodeModel, ModelCfg
+
+    s = ds.tensor_seed(5, 0)
+    g = lambda i, shape, std=0.02, mean=0.0: ds.normal_bf16_torch(s + i, shape, std, mean, DEV)
+    layers = []
+    for l in range(NL):
+        o = 10 + 10 * l
+        layers.append(dict(norm1=g(o, (H,), 0.0, 1.0), wqkv=g(o + 1, (H, (HQ + 2 * HKV) * D)),
+                           wo=g(o + 2, (HQ * D, H)), norm2=g(o + 3, (H,), 0.0, 1.0), wgu=g(o + 4, (H, 2 * F)),
+                           wdown=g(o + 5, (F, H))))
+    weights = dict(embed=g(1, (V, H), 1.0), lm_head=g(2, (H, V)), final_norm=g(3, (H,), 0.0, 1.0), layers=layers)
+    return DecodeModel(ModelCfg(H, HQ, HKV, D, F, V, NL), weights)
+
+
+@pytest.fixture(scope="module")
+def prompts():
+    lens = ds.uniform_int(ds.tensor_seed(5, 500), (N_PROMPTS,), 16, 512)
+    toks = ds.uniform_int(ds.tensor_seed(5, 501), (N_PROMPTS, 512), 0, V - 1)
+    return toks, lens
+
+
+def test_token_streams_identical_across_batchings(model, prompts):
+    from paper_2602_00182_amd.decode import greedy_decode
+
+    toks, lens = prompts
+    cos_t, sin_t = ds.rope_tables(512 + N_NEW, D, 5.0e5)
+    cos_d, sin_d = up(cos_t), up(sin_t)
+
+    def run(ids, keep=()):
+        ids = list(ids)
+        gen, kept = greedy_decode(model, up(toks[ids]), up(lens[ids]), N_NEW, cos_d, sin_d, keep_logits_at=keep)
+        torch.cuda.synchronize()
+        return gen.cpu().numpy(), {t: l.cpu().numpy() for t, l in kept.items()}
+
+    keep = (15, 100, 300, 500, 600)
+    step("greedy decode, all 64 prompts in one batch")
+    full, full_logits = run(range(64), keep)
+    assert full.shape == (64, N_NEW)
+    assert len({tuple(r) for r in full}) > 32, "streams should differ between prompts"
+    step("greedy decode, same batch again")
+    again, again_logits = run(range(64), keep)
+    assert np.array_equal(full, again)
+    for t in keep:
+        if t in full_logits:
+            assert np.array_equal(full_logits[t].view(np.uint32), again_logits[t].view(np.uint32))
+    for bs in (32, 8):
+        for start in (0, 64 - bs):
+            ids = list(range(start, start + bs))
+            step(f"greedy decode, batch of {bs} starting at prompt {start}")
+            part, part_logits = run(ids, keep)
+            assert np.array_equal(part, full[ids]), f"token streams differ at batch size {bs}"
+            for t, lg in part_logits.items():
+                # rows still inside their own run at step t carry the same logits bytes
+                live = [j for j, i in enumerate(ids) if t < lens[i] + N_NEW - 1]
+                assert np.array_equal(lg[live].view(np.uint32), full_logits[t][[ids[j] for j in live]].view(np.uint32))
+    step("greedy decode, shuffled batch of 32 drawn from all prompts")
+    ids = np.random.default_rng(3).permutation(64)[:32].tolist()
+    part, _ = run(ids)
+    assert np.array_equal(part, full[ids])
+    for i in (0, 17, 40, 63):
+        step(f"greedy decode, prompt {i} alone")
+        alone, alone_logits = run([i], keep)
+        assert np.array_equal(alone[0], full[i]), f"prompt {i}: alone differs from batched"
+        for t, lg in alone_logits.items():
+            assert np.array_equal(lg[0].view(np.uint32), full_logits[t][i].view(np.uint32))

@@ -1,0 +1,133 @@
+"""det_decoder_layer: the Llama-3-8B-shaped layer against the oracle layer, and byte equality of a
+sequence's outputs across batch compositions (the real gate: the paper's batch-variance condition,
+section 10.1, strengthened to any batch size and any content of the other rows)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import detsynth as ds
+from gpu_util import DEV, bits_to_f64, down_bf16, step, up, up_bf16
+
+pytestmark = pytest.mark.gpu
+
+CFG = dict(H=4096, Hq=32, Hkv=8, D=128, F=14336, Lmax=2048, eps=1e-5,
+           scale=float(np.float32(1.0 / math.sqrt(128.0))))
+
+
+@pytest.fixture(scope="module")
+def d():
+    import paper_2602_00182_amd as d
+    return d
+
+
+@pytest.fixture(scope="module")
+def layer(d):
+    """Random-init layer (weights N(0, 0.02^2), norm weights 1.0) generated on the device."""
+    H, Hq, Hkv, D, F = (CFG[k] for k in ("H", "Hq", "Hkv", "D", "F"))
+    s = ds.tensor_seed(4, 0)
+    logical = dict(
+        norm1=ds.normal_bf16_torch(s, (H,), 0.0, 1.0, DEV),
+        wqkv=ds.normal_bf16_torch(s + 1, (H, (Hq + 2 * Hkv) * D), 0.02, 0.0, DEV),
+        wo=ds.normal_bf16_torch(s + 2, (Hq * D, H), 0.02, 0.0, DEV),
+        norm2=ds.normal_bf16_torch(s + 3, (H,), 0.0, 1.0, DEV),
+        wgu=ds.normal_bf16_torch(s + 4, (H, 2 * F), 0.02, 0.0, DEV),
+        wdown=ds.normal_bf16_torch(s + 5, (F, H), 0.02, 0.0, DEV),
+    )
+    packed = {k: (d.pack_weight(v) if v.dim() == 2 else v) for k, v in logical.items()}
+    struct = d.layer_weights(packed["norm1"], packed["wqkv"], packed["wo"], packed["norm2"], packed["wgu"],
+                             packed["wdown"])
+    cos_t, sin_t = ds.rope_tables(CFG["Lmax"], CFG["D"], 5.0e5)
+    cfg = d.layer_cfg(CFG["H"], CFG["Hq"], CFG["Hkv"], CFG["D"], CFG["F"], CFG["Lmax"], CFG["eps"], CFG["scale"])
+    return dict(logical=logical, packed=packed, struct=struct, cfg=cfg, cos=up(cos_t), sin=up(sin_t),
+                cos_h=cos_t, sin_h=sin_t)
+
+
+def seq_inputs(b):
+    """x row, K and V cache of synthetic sequence number b (device tensors)."""
+    s = ds.tensor_seed(4, 100) + 10 * b
+    x = ds.normal_bf16_torch(s, (CFG["H"],), 1.0, 0.0, DEV)
+    k = ds.normal_bf16_torch(s + 1, (CFG["Hkv"], CFG["Lmax"], CFG["D"]), 1.0, 0.0, DEV)
+    v = ds.normal_bf16_torch(s + 2, (CFG["Hkv"], CFG["Lmax"], CFG["D"]), 1.0, 0.0, DEV)
+    return x, k, v
+
+
+def run_layer(d, layer, seq_ids, positions):
+    B = len(seq_ids)
+    xs, ks, vs = zip(*[seq_inputs(b) for b in seq_ids])
+    x = torch.stack(xs).contiguous()
+    kc = torch.stack(ks).contiguous()
+    vc = torch.stack(vs).contiguous()
+    ws = torch.empty(d.det_decoder_layer_workspace_bytes(layer["cfg"], B), dtype=torch.uint8, device=DEV)
+    ws.fill_(0xFF)
+    pos = up(np.asarray(positions, dtype=np.int32))
+    d.det_decoder_layer(layer["struct"], layer["cfg"], x, kc, vc, pos, layer["cos"], layer["sin"], ws)
+    torch.cuda.synchronize()
+    return x, kc, vc
+
+
+def test_layer_vs_oracle(d, orc, layer):
+    """B = 3 sequences at positions 2047, 1000, 0.  The oracle's contractions are fp64 references
+    rounded once to bf16, so intermediate activations can differ from the GPU's by one bf16 ulp;
+    those flips pass through the following GEMMs as noise of relative size ~2^-8/sqrt(K) each.
+    Bound used: |err| <= 2^-6 |ref| + 2^-7 rms(ref)."""
+    seq_ids, positions = [0, 1, 2], [2047, 1000, 0]
+    step("decoder layer B=3 vs oracle")
+    x, kc, vc = run_layer(d, layer, seq_ids, positions)
+    xs, ks, vs = zip(*[seq_inputs(b) for b in seq_ids])
+    x0 = down_bf16(torch.stack(xs))
+    kc0 = down_bf16(torch.stack(ks))
+    vc0 = down_bf16(torch.stack(vs))
+    w = {k: down_bf16(v) for k, v in layer["logical"].items()}
+    ref = orc.decoder_layer(x0, w, kc0, vc0, np.asarray(positions, dtype=np.int32), layer["cos_h"],
+                            layer["sin_h"], CFG)
+    got = bits_to_f64(down_bf16(x))
+    reff = bits_to_f64(ref)
+    rms = np.sqrt((reff ** 2).mean())
+    err = np.abs(got - reff)
+    assert (err <= 2.0 ** -6 * np.abs(reff) + 2.0 ** -7 * rms).all(), (err.max(), rms)
+    # the caches: K rows are rope(bf16(projection)), V rows bf16(projection): one-ulp flips allowed
+    gk, gv = bits_to_f64(down_bf16(kc)), bits_to_f64(down_bf16(vc))
+    rk, rv = bits_to_f64(kc0), bits_to_f64(vc0)   # oracle updated these in place
+    for b, p in enumerate(positions):
+        for g_, r_ in ((gk, rk), (gv, rv)):
+            e = np.abs(g_[b, :, p] - r_[b, :, p])
+            assert (e <= 2.0 ** -6 * np.abs(r_[b, :, p]) + 2.0 ** -9).all()
+        # every other cache row is untouched
+        mask = np.ones(CFG["Lmax"], dtype=bool)
+        mask[p] = False
+        assert np.array_equal(down_bf16(kc)[b][:, mask], down_bf16(torch.stack(ks))[b][:, mask])
+
+
+@pytest.mark.parametrize("B", [32, 128])
+def test_layer_bytes_across_batch_compositions(d, layer, B):
+    """Sequence 0 at position 2047: alone, inside B at slot 0, inside B at another slot, with the
+    other rows re-seeded and at other positions.  Its x row and its new cache rows never change."""
+    step("decoder layer alone")
+    x1, k1, v1 = run_layer(d, layer, [0], [2047])
+    want_x = x1[0].clone()
+    want_k = k1[0, :, 2047].clone()
+    want_v = v1[0, :, 2047].clone()
+
+    def check(xb, kb, vb, slot):
+        assert torch.equal(xb[slot].view(torch.int16), want_x.view(torch.int16))
+        assert torch.equal(kb[slot, :, 2047].view(torch.int16), want_k.view(torch.int16))
+        assert torch.equal(vb[slot, :, 2047].view(torch.int16), want_v.view(torch.int16))
+
+    step(f"decoder layer inside B={B}, slot 0")
+    ids = list(range(B))
+    check(*run_layer(d, layer, ids, [2047] * B), 0)
+    step(f"decoder layer inside B={B}, slot {B - 3}, other rows re-seeded, ragged positions")
+    ids = [1000 + i for i in range(B)]
+    slot = B - 3
+    ids[slot] = 0
+    pos = ds.uniform_int(77 + B, (B,), 0, 2047).tolist()
+    pos[slot] = 2047
+    xb, kb, vb = run_layer(d, layer, ids, pos)
+    check(xb, kb, vb, slot)
+    step("decoder layer repeat x5")
+    for _ in range(5):
+        xr, kr, vr = run_layer(d, layer, ids, pos)
+        assert torch.equal(xr.view(torch.int16), xb.view(torch.int16))
+        assert torch.equal(kr.view(torch.int16), kb.view(torch.int16))
