@@ -189,9 +189,12 @@ def layer_cfg(H, Hq, Hkv, D, F, Lmax, eps, scale) -> LayerCfg:
 
 
 def layer_weights(w_norm1, wqkv, wo, w_norm2, wgu, wdown) -> LayerWeights:
-    """Device pointers of one layer's weights (projections already packed).  The returned struct
-    does not keep the tensors alive: the caller does."""
-    return LayerWeights(*[_contig(t) for t in (w_norm1, wqkv, wo, w_norm2, wgu, wdown)])
+    """Device pointers of one layer's weights (projections already packed).  The struct keeps a
+    reference to the six tensors, so they live as long as it does."""
+    tensors = (w_norm1, wqkv, wo, w_norm2, wgu, wdown)
+    s = LayerWeights(*[_contig(t) for t in tensors])
+    s._keep = tensors
+    return s
 
 
 def det_decoder_layer_workspace_bytes(cfg: LayerCfg, B: int) -> int:
