@@ -5,27 +5,30 @@
 //
 // Shape of the kernel
 //   * A workgroup (4 wavefronts) owns BN = 16*CB output columns and up to 256 rows; grid.x = N/BN,
-//     grid.y = ceil(M/256).  CB is a function of N alone (gemm_cols_per_block), so the
+//     grid.y = ceil(M/256).  CB and the LDS chunk size are functions of N alone, so the
 //     configuration never depends on M.
-//   * The weight slab of the workgroup is one contiguous run of the packed matrix.  It is streamed
-//     through a double-buffered LDS ring in chunks of CS 64-deep K stages: all 256 threads issue
-//     the 16-byte global loads of chunk c+1 before computing on chunk c.
-//   * Weights are the ROW operand of v_mfma_f32_16x16x32_bf16 (16 output columns of C), the
-//     activations are its COLUMN operand (16 rows of C): a lane then holds 4 consecutive columns of
-//     one row of C, which makes the store one 8- or 16-byte write.
-//   * 16-row blocks of the tile are dealt round-robin to the 4 waves (block rb -> wave rb % 4).
-//     M only decides how many blocks exist; a block's arithmetic is identical wherever it sits.
-//     Activation fragments go straight from global memory (L2) to registers: each is needed by
-//     exactly one wave of the workgroup.
+//   * K is cut into 64-deep stages.  A stage is a run of 1 KB blocks, each already in the
+//     operand order of v_mfma_f32_16x16x32_bf16 (lane l holds 8 consecutive k of row/column l%16,
+//     k group l/16): 2*CB weight blocks followed by 2*RB activation blocks, RB = number of 16-row
+//     blocks of the tile that hold data.  M decides RB and nothing else.
+//   * Stages are streamed through two LDS chunk buffers with the LDS-DMA form of the global load
+//     (global_load_lds_dwordx4: no staging registers, a wave instruction fills one 1 KB block):
+//     while the waves compute on one buffer, the loads of the next chunk are in flight into the
+//     other.  The weight slab of a workgroup is one contiguous run of the packed matrix.
+//   * Weights are the ROW operand of the MFMA (16 output columns of C), activations its COLUMN
+//     operand (16 rows of C): a lane then holds 4 consecutive columns of one row of C and the
+//     store is one 8- or 16-byte write.  Rows of the operand are independent in the matrix core,
+//     so rows past M may hold anything: their loads are clamped to row M-1 and never stored.
+//   * 16-row blocks are dealt round-robin to the 4 waves (block rb -> wave rb % 4).
 //
-// K order inside a 64-deep stage s: matrix-core step 2s takes k = 64s + 16g + e, step 2s+1 takes
-// k = 64s + 16g + 8 + e (g = lane/16 in 0..3, e in 0..7), so that a lane's two activation
-// fragments are 32 contiguous bytes of a row of A.
+// K order: matrix-core step t (t = 0 .. K/32-1, ascending) takes k in [32t, 32t+32); inside a step
+// lane group g supplies k = 32t + 8g + e, e = 0..7.
 #include "common.h"
 
 namespace det {
 
-__host__ __device__ constexpr int gemm_stage_u4(int cb) { return cb * 2 * 64; }  // uint4 per stage
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void global_void_t;
 
 // Columns-per-workgroup factor: the largest CB in 1..8 that divides N/16 and still leaves at least
 // 240 workgroups across N (one per compute unit, roughly); 1 if there is none.
@@ -38,47 +41,43 @@ int gemm_cols_per_block(int N)
     return best;
 }
 
-// K stages per LDS chunk for a given CB: at most 32 KB per chunk (two chunks fit the 64 KB of
-// statically declared LDS), even so that the chunk is a whole number of 16-byte loads per thread.
-__host__ __device__ constexpr int gemm_chunk_stages(int cb)
+// 1 KB blocks per LDS chunk buffer (there are two buffers).  A stage of the largest tile needs
+// 2*(CB+16) blocks.  When N yields at least 1.5 workgroups per compute unit and CB is small, the
+// buffers are kept small enough for two workgroups to share a compute unit's 160 KB of LDS.
+__host__ __device__ constexpr int gemm_small_chunk_blocks(int cb) { return 2 * (cb + 16) + 2; }
+int gemm_chunk_blocks(int N)
 {
-    return cb == 1 ? 16 : cb == 2 ? 8 : cb <= 4 ? 4 : 2;
+    const int cb = gemm_cols_per_block(N);
+    if (cb <= 3 && N / (16 * cb) >= 384) return gemm_small_chunk_blocks(cb);
+    return 64;
 }
 
-template <int CB>
+template <int CB, int CHB>
 __global__ __launch_bounds__(256) void gemm_kernel(const uint16_t* __restrict__ A, int lda,
                                                    const uint4* __restrict__ Bp, void* __restrict__ C,
                                                    int ldc, int M, int K, int out_f32)
 {
-    constexpr int CS = gemm_chunk_stages(CB);
-    constexpr int STAGE_U4 = gemm_stage_u4(CB);
-    constexpr int CHUNK_U4 = CS * STAGE_U4;
-    constexpr int LOADS = CHUNK_U4 / 256;
-    static_assert(CHUNK_U4 % 256 == 0, "chunk must be a whole number of loads per thread");
-    __shared__ uint4 lds[2][CHUNK_U4];
+    static_assert(CHB >= 2 * (CB + 16), "a chunk buffer must hold one stage of the largest tile");
+    __shared__ uint4 buf0[CHB * 64];
+    __shared__ uint4 buf1[CHB * 64];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int g = lane >> 4;      // k group of the lane
-    const int lr = lane & 15;     // row of A / column-in-block of the weights
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4;   // k group of the lane
+    const int lr = lane & 15;  // row of A / column-in-block of the weights
     const int m0 = blockIdx.y * 256;
+    const int mrem = min(M - m0, 256);
+    const int RB = (mrem + 15) >> 4;          // 16-row blocks holding data
+    const int nb = 2 * (CB + RB);             // 1 KB blocks per stage
+    const int SPC = CHB / nb;                 // stages per chunk (>= 1)
     const int nstages = K >> 6;
-    const int total_u4 = nstages * STAGE_U4;
-    const uint4* __restrict__ bsrc = Bp + (size_t)blockIdx.x * total_u4;
+    const int nchunks = (nstages + SPC - 1) / SPC;
+    const uint4* __restrict__ bsrc = Bp + (size_t)blockIdx.x * nstages * (2 * CB * 64);
+    const uint16_t* __restrict__ abase = A + (size_t)m0 * lda;
 
-    // Row blocks of this wave: rb = wave + 4r.  Block r is active when its first row exists.
-    const int mrem = M - m0;
-    const uint16_t* arow[4];
-    bool rvalid[4];
-    int nrb = 0;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int row = 16 * (wave + 4 * r) + lr;
-        if (16 * (wave + 4 * r) < mrem) nrb = r + 1;
-        rvalid[r] = row < mrem;
-        arow[r] = A + (size_t)(m0 + (rvalid[r] ? row : 0)) * lda + 16 * g;
-    }
+    // Row blocks of this wave: rb = wave + 4r, active while rb < RB.
+    const int nrb = RB > wave ? (RB - wave + 3) >> 2 : 0;
 
     f32x4 acc[4][CB];
 #pragma unroll
@@ -86,57 +85,73 @@ __global__ __launch_bounds__(256) void gemm_kernel(const uint16_t* __restrict__ 
 #pragma unroll
         for (int j = 0; j < CB; ++j) acc[r][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    uint4 pre[LOADS];
-    const uint4 zero4 = make_uint4(0, 0, 0, 0);
-#pragma unroll
-    for (int i = 0; i < LOADS; ++i) {
-        const int idx = i * 256 + tid;
-        pre[i] = idx < total_u4 ? bsrc[idx] : zero4;
-    }
-
-    const int nchunks = (nstages + CS - 1) / CS;
-    for (int ch = 0; ch < nchunks; ++ch) {
-        uint4* buf = lds[ch & 1];
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i) buf[i * 256 + tid] = pre[i];
-        __syncthreads();
-        if (ch + 1 < nchunks) {
-            const int base = (ch + 1) * CHUNK_U4;
-#pragma unroll
-            for (int i = 0; i < LOADS; ++i) {
-                const int idx = base + i * 256 + tid;
-                pre[i] = idx < total_u4 ? bsrc[idx] : zero4;
+    // Issues the LDS-DMA loads of chunk c into `buf`: block F of the chunk (stage F / nb, block
+    // F % nb of that stage) is loaded by wave F % 4.
+    auto load_chunk = [&](uint4* buf, int c) {
+        const int s_begin = c * SPC;
+        const int s_cnt = min(SPC, nstages - s_begin);
+        const int total = s_cnt * nb;
+        int s = s_begin, f = wave;
+        for (int F = wave; F < total; F += 4) {
+            const void* src;
+            if (f < 2 * CB) {
+                src = bsrc + ((size_t)s * (2 * CB) + f) * 64 + lane;
+            } else {
+                const int a = f - 2 * CB;
+                int row = 16 * (a >> 1) + lr;
+                row = row < mrem ? row : mrem - 1;
+                src = abase + (size_t)row * lda + (s << 6) + 32 * (a & 1) + 8 * g;
+            }
+            __builtin_amdgcn_global_load_lds((global_void_t*)src, (lds_void_t*)(buf + F * 64), 16, 0, 0);
+            f += 4;
+            if (f >= nb) {
+                f -= nb;
+                ++s;
             }
         }
-        const int st_n = min(CS, nstages - ch * CS);
-        if (nrb > 0) {
-            for (int st = 0; st < st_n; ++st) {
-                const int kbase = (ch * CS + st) << 6;
-                bf16x8 wf[CB][2];
+    };
+
+    auto compute_chunk = [&](const uint4* buf, int c) {
+        if (nrb == 0) return;
+        const int s_cnt = min(SPC, nstages - c * SPC);
+        for (int s = 0; s < s_cnt; ++s) {
+            const uint4* st = buf + s * nb * 64 + lane;
+            bf16x8 wf[CB][2];
 #pragma unroll
-                for (int j = 0; j < CB; ++j) {
-                    wf[j][0] = __builtin_bit_cast(bf16x8, buf[st * STAGE_U4 + (2 * j) * 64 + lane]);
-                    wf[j][1] = __builtin_bit_cast(bf16x8, buf[st * STAGE_U4 + (2 * j + 1) * 64 + lane]);
-                }
+            for (int j = 0; j < CB; ++j) {
+                wf[j][0] = __builtin_bit_cast(bf16x8, st[(2 * j) * 64]);
+                wf[j][1] = __builtin_bit_cast(bf16x8, st[(2 * j + 1) * 64]);
+            }
+            bf16x8 xf[4][2];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    if (r < nrb) {
-                        uint4 a0 = zero4, a1 = zero4;
-                        if (rvalid[r]) {
-                            const uint4* ap = reinterpret_cast<const uint4*>(arow[r] + kbase);
-                            a0 = ap[0];
-                            a1 = ap[1];
-                        }
-                        const bf16x8 x0 = __builtin_bit_cast(bf16x8, a0);
-                        const bf16x8 x1 = __builtin_bit_cast(bf16x8, a1);
-#pragma unroll
-                        for (int j = 0; j < CB; ++j) {
-                            acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[j][0], x0, acc[r][j], 0, 0, 0);
-                            acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[j][1], x1, acc[r][j], 0, 0, 0);
-                        }
-                    }
+            for (int r = 0; r < 4; ++r) {
+                if (r < nrb) {
+                    const uint4* ap = st + (2 * CB + 2 * (wave + 4 * r)) * 64;
+                    xf[r][0] = __builtin_bit_cast(bf16x8, ap[0]);
+                    xf[r][1] = __builtin_bit_cast(bf16x8, ap[64]);
                 }
             }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (r < nrb) {
+#pragma unroll
+                        for (int j = 0; j < CB; ++j)
+                            acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[j][i], xf[r][i], acc[r][j], 0, 0, 0);
+                    }
+        }
+    };
+
+    load_chunk(buf0, 0);
+    for (int c = 0; c < nchunks; c += 2) {
+        __syncthreads();  // chunk c has landed in buf0; every wave is done with buf1
+        if (c + 1 < nchunks) load_chunk(buf1, c + 1);
+        compute_chunk(buf0, c);
+        if (c + 1 < nchunks) {
+            __syncthreads();  // chunk c+1 has landed in buf1; every wave is done with buf0
+            if (c + 2 < nchunks) load_chunk(buf0, c + 2);
+            compute_chunk(buf1, c + 1);
         }
     }
 
@@ -144,8 +159,9 @@ __global__ __launch_bounds__(256) void gemm_kernel(const uint16_t* __restrict__ 
     const int n0 = blockIdx.x * (16 * CB);
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-        if (r < nrb && rvalid[r]) {
-            const size_t row = (size_t)(m0 + 16 * (wave + 4 * r) + lr);
+        const int rowl = 16 * (wave + 4 * r) + lr;
+        if (r < nrb && rowl < mrem) {
+            const size_t row = (size_t)(m0 + rowl);
 #pragma unroll
             for (int j = 0; j < CB; ++j) {
                 const int n = n0 + 16 * j + 4 * g;
@@ -167,7 +183,7 @@ __global__ __launch_bounds__(256) void gemm_pack_kernel(const uint16_t* __restri
                                                         uint4* __restrict__ Bp, int N, int K, int cb)
 {
     const size_t total = (size_t)N * K / 8;
-    const int stage_u4 = gemm_stage_u4(cb);
+    const int stage_u4 = cb * 2 * 64;
     const int nstages = K >> 6;
     for (size_t u = (size_t)blockIdx.x * 256 + threadIdx.x; u < total; u += (size_t)gridDim.x * 256) {
         const size_t per_tile = (size_t)nstages * stage_u4;
@@ -179,7 +195,7 @@ __global__ __launch_bounds__(256) void gemm_pack_kernel(const uint16_t* __restri
         const int i = (f >> 6) & 1;
         const int lane = f & 63;
         const int n = tile * 16 * cb + 16 * j + (lane & 15);
-        const int k0 = 64 * st + 16 * (lane >> 4) + 8 * i;
+        const int k0 = 64 * st + 32 * i + 8 * (lane >> 4);
         uint16_t e[8];
 #pragma unroll
         for (int t = 0; t < 8; ++t) e[t] = Bkn[(size_t)(k0 + t) * N + n];
@@ -192,12 +208,12 @@ __global__ __launch_bounds__(256) void gemm_pack_kernel(const uint16_t* __restri
     }
 }
 
-template <int CB>
+template <int CB, int CHB>
 static void launch_gemm(const void* A, int lda, const void* Bp, void* C, int ldc, int M, int N, int K,
                         int out_f32, hipStream_t s)
 {
     dim3 grid(N / (16 * CB), (M + 255) / 256);
-    hipLaunchKernelGGL(gemm_kernel<CB>, grid, dim3(256), 0, s, static_cast<const uint16_t*>(A), lda,
+    hipLaunchKernelGGL((gemm_kernel<CB, CHB>), grid, dim3(256), 0, s, static_cast<const uint16_t*>(A), lda,
                        static_cast<const uint4*>(Bp), C, ldc, M, K, out_f32);
 }
 
@@ -237,15 +253,31 @@ extern "C" int det_gemm_bf16(const void* A, int lda, const void* B_packed, void*
         return DET_EALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int f32 = out_dtype == DET_F32;
-    switch (gemm_cols_per_block(N)) {
-        case 1: launch_gemm<1>(A, lda, B_packed, C, ldc, M, N, K, f32, s); break;
-        case 2: launch_gemm<2>(A, lda, B_packed, C, ldc, M, N, K, f32, s); break;
-        case 3: launch_gemm<3>(A, lda, B_packed, C, ldc, M, N, K, f32, s); break;
-        case 4: launch_gemm<4>(A, lda, B_packed, C, ldc, M, N, K, f32, s); break;
-        case 5: launch_gemm<5>(A, lda, B_packed, C, ldc, M, N, K, f32, s); break;
-        case 6: launch_gemm<6>(A, lda, B_packed, C, ldc, M, N, K, f32, s); break;
-        case 7: launch_gemm<7>(A, lda, B_packed, C, ldc, M, N, K, f32, s); break;
-        default: launch_gemm<8>(A, lda, B_packed, C, ldc, M, N, K, f32, s); break;
+    const int cb = gemm_cols_per_block(N);
+    const bool small = gemm_chunk_blocks(N) != 64;
+#define DET_GEMM_CASE(CBV)                                                                          \
+    case CBV:                                                                                       \
+        if constexpr (CBV <= 3) {                                                                   \
+            if (small) {                                                                            \
+                launch_gemm<CBV, gemm_small_chunk_blocks(CBV <= 3 ? CBV : 1)>(A, lda, B_packed, C, ldc, M, N, \
+                                                                             K, f32, s);            \
+                break;                                                                              \
+            }                                                                                       \
+        }                                                                                           \
+        launch_gemm<CBV, 64>(A, lda, B_packed, C, ldc, M, N, K, f32, s);                            \
+        break;
+    switch (cb) {
+        DET_GEMM_CASE(1)
+        DET_GEMM_CASE(2)
+        DET_GEMM_CASE(3)
+        DET_GEMM_CASE(4)
+        DET_GEMM_CASE(5)
+        DET_GEMM_CASE(6)
+        DET_GEMM_CASE(7)
+        default:
+            launch_gemm<8, 64>(A, lda, B_packed, C, ldc, M, N, K, f32, s);
+            break;
     }
+#undef DET_GEMM_CASE
     return check_launch();
 }
