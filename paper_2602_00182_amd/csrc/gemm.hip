@@ -5,30 +5,34 @@
 //
 // Shape of the kernel
 //   * A workgroup (4 wavefronts) owns BN = 16*CB output columns and up to 256 rows; grid.x = N/BN,
-//     grid.y = ceil(M/256).  CB and the LDS chunk size are functions of N alone, so the
+//     grid.y = ceil(M/256).  CB and the LDS ring size are functions of N alone, so the
 //     configuration never depends on M.
-//   * K is cut into 64-deep stages.  A stage is a run of 1 KB blocks, each already in the
-//     operand order of v_mfma_f32_16x16x32_bf16 (lane l holds 8 consecutive k of row/column l%16,
-//     k group l/16): 2*CB weight blocks followed by 2*RB activation blocks, RB = number of 16-row
+//   * K is cut into 64-deep stages.  Operands travel as 1 KB blocks, each already in the operand
+//     order of v_mfma_f32_16x16x32_bf16 (lane l holds 8 consecutive k of row/column l%16, k group
+//     l/16): a stage has 2*CB weight blocks and 2*RB activation blocks, RB = number of 16-row
 //     blocks of the tile that hold data.  M decides RB and nothing else.
-//   * Stages are streamed through two LDS chunk buffers with the LDS-DMA form of the global load
-//     (global_load_lds_dwordx4: no staging registers, a wave instruction fills one 1 KB block):
-//     while the waves compute on one buffer, the loads of the next chunk are in flight into the
-//     other.  The weight slab of a workgroup is one contiguous run of the packed matrix.
+//   * Stages are grouped into chunks and streamed through a ring of up to 4 LDS slots with the
+//     LDS-DMA form of the global load (global_load_lds_dwordx4: no staging registers, one wave
+//     instruction fills one 1 KB block).  Up to 3 chunks are in flight while the waves compute on
+//     a fourth; a wave waits only for its own loads of the oldest chunk (s_waitcnt vmcnt(n) with n
+//     = its loads of the younger chunks), then the workgroup barrier makes the chunk visible.
+//     The weight slab of a workgroup is one contiguous run of the packed matrix.
 //   * Weights are the ROW operand of the MFMA (16 output columns of C), activations its COLUMN
 //     operand (16 rows of C): a lane then holds 4 consecutive columns of one row of C and the
 //     store is one 8- or 16-byte write.  Rows of the operand are independent in the matrix core,
-//     so rows past M may hold anything: their loads are clamped to row M-1 and never stored.
+//     so rows past M may hold anything: their lanes load nothing and their outputs are never
+//     stored.
 //   * 16-row blocks are dealt round-robin to the 4 waves (block rb -> wave rb % 4).
 //
 // K order: matrix-core step t (t = 0 .. K/32-1, ascending) takes k in [32t, 32t+32); inside a step
 // lane group g supplies k = 32t + 8g + e, e = 0..7.
+#include <type_traits>
+
 #include "common.h"
 
 namespace det {
 
-typedef __attribute__((address_space(3))) void lds_void_t;
-typedef __attribute__((address_space(1))) const void global_void_t;
+typedef __attribute__((address_space(3))) char lds_char_t;
 
 // Columns-per-workgroup factor: the largest CB in 1..8 that divides N/16 and still leaves at least
 // 240 workgroups across N (one per compute unit, roughly); 1 if there is none.
@@ -41,25 +45,57 @@ int gemm_cols_per_block(int N)
     return best;
 }
 
-// 1 KB blocks per LDS chunk buffer (there are two buffers).  A stage of the largest tile needs
-// 2*(CB+16) blocks.  When N yields at least 1.5 workgroups per compute unit and CB is small, the
-// buffers are kept small enough for two workgroups to share a compute unit's 160 KB of LDS.
-__host__ __device__ constexpr int gemm_small_chunk_blocks(int cb) { return 2 * (cb + 16) + 2; }
-int gemm_chunk_blocks(int N)
+// LDS ring size in 1 KB blocks.  144 KB by default (one workgroup per compute unit).  When N
+// yields at least 1.5 workgroups per compute unit and CB is small, the ring is two stages of the
+// largest tile, so that two workgroups share a compute unit's 160 KB of LDS.
+constexpr int kRingBig = 144;
+__host__ __device__ constexpr int gemm_small_ring_blocks(int cb) { return 4 * (cb + 16); }
+bool gemm_small_ring(int N)
 {
     const int cb = gemm_cols_per_block(N);
-    if (cb <= 3 && N / (16 * cb) >= 384) return gemm_small_chunk_blocks(cb);
-    return 64;
+    return cb <= 3 && N / (16 * cb) >= 384;
 }
 
-template <int CB, int CHB>
+// One wave instruction: 64 lanes x 16 bytes from global memory straight into the 1 KB LDS block at
+// byte address lds_addr (wave-uniform); lane l lands at lds_addr + 16 l.  Written as assembly so
+// that the completion wait below can name a count instead of draining every load in flight.
+__device__ __forceinline__ void dma_block(const void* gsrc, uint32_t lds_addr)
+{
+    uint32_t saved_m0;
+    asm volatile(
+        "s_mov_b32 %0, m0\n\t"
+        "s_mov_b32 m0, %1\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %2, off\n\t"
+        "s_mov_b32 m0, %0"
+        : "=&s"(saved_m0)
+        : "s"(lds_addr), "v"(gsrc)
+        : "memory");
+}
+
+// Waits until at most n of this wave's loads are outstanding, then the workgroup barrier.
+#define DET_WB(n) \
+    case n: asm volatile("s_waitcnt vmcnt(" #n ")\n\ts_barrier" ::: "memory"); break;
+__device__ __forceinline__ void wait_loads_then_barrier(int n)
+{
+    switch (n) {
+        DET_WB(1) DET_WB(2) DET_WB(3) DET_WB(4) DET_WB(5) DET_WB(6) DET_WB(7) DET_WB(8)
+        DET_WB(9) DET_WB(10) DET_WB(11) DET_WB(12) DET_WB(13) DET_WB(14) DET_WB(15) DET_WB(16)
+        DET_WB(17) DET_WB(18) DET_WB(19) DET_WB(20) DET_WB(21) DET_WB(22) DET_WB(23) DET_WB(24)
+        DET_WB(25) DET_WB(26) DET_WB(27) DET_WB(28) DET_WB(29) DET_WB(30) DET_WB(31) DET_WB(32)
+        DET_WB(33) DET_WB(34) DET_WB(35) DET_WB(36) DET_WB(37) DET_WB(38) DET_WB(39) DET_WB(40)
+        default: asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory"); break;
+    }
+}
+#undef DET_WB
+
+template <int CB, int RINGB>
 __global__ __launch_bounds__(256) void gemm_kernel(const uint16_t* __restrict__ A, int lda,
                                                    const uint4* __restrict__ Bp, void* __restrict__ C,
                                                    int ldc, int M, int K, int out_f32)
 {
-    static_assert(CHB >= 2 * (CB + 16), "a chunk buffer must hold one stage of the largest tile");
-    __shared__ uint4 buf0[CHB * 64];
-    __shared__ uint4 buf1[CHB * 64];
+    static_assert(RINGB >= 4 * (CB + 16), "the ring must hold two stages of the largest tile");
+    __shared__ uint4 ring[RINGB * 64];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -68,113 +104,189 @@ __global__ __launch_bounds__(256) void gemm_kernel(const uint16_t* __restrict__ 
     const int lr = lane & 15;  // row of A / column-in-block of the weights
     const int m0 = blockIdx.y * 256;
     const int mrem = min(M - m0, 256);
-    const int RB = (mrem + 15) >> 4;          // 16-row blocks holding data
-    const int nb = 2 * (CB + RB);             // 1 KB blocks per stage
-    const int SPC = CHB / nb;                 // stages per chunk (>= 1)
+    const int RB = (mrem + 15) >> 4;                 // 16-row blocks holding data
+    const int nA = 2 * RB;                           // activation blocks per stage
+    const int nb = 2 * CB + nA;                      // 1 KB blocks per stage
+    const int SPC = max(1, (RINGB / 4) / nb);        // stages per chunk
+    const int slot_blocks = SPC * nb;                // blocks per ring slot
+    const int nslots = min(4, RINGB / slot_blocks);  // >= 2 by the static_assert
+    const int P = nslots - 1;                        // chunks in flight
     const int nstages = K >> 6;
     const int nchunks = (nstages + SPC - 1) / SPC;
     const uint4* __restrict__ bsrc = Bp + (size_t)blockIdx.x * nstages * (2 * CB * 64);
     const uint16_t* __restrict__ abase = A + (size_t)m0 * lda;
+    const uint32_t ring_addr = (uint32_t)(uintptr_t)(lds_char_t*)ring;
 
     // Row blocks of this wave: rb = wave + 4r, active while rb < RB.
     const int nrb = RB > wave ? (RB - wave + 3) >> 2 : 0;
 
-    f32x4 acc[4][CB];
-#pragma unroll
-    for (int r = 0; r < 4; ++r)
-#pragma unroll
-        for (int j = 0; j < CB; ++j) acc[r][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // Which waves issue loads: while fewer than 4 row blocks hold data, the waves without a row block
+    // (waves RB..3) do all the loading and the computing waves only compute; from 4 row blocks on,
+    // every wave does both.  lrank < 0: this wave issues no loads.
+    const int nload = RB >= 4 ? 4 : 4 - RB;
+    const int lrank = RB >= 4 ? wave : wave - RB;
 
-    // Issues the LDS-DMA loads of chunk c into `buf`: block F of the chunk (stage F / nb, block
-    // F % nb of that stage) is loaded by wave F % 4.
-    auto load_chunk = [&](uint4* buf, int c) {
-        const int s_begin = c * SPC;
-        const int s_cnt = min(SPC, nstages - s_begin);
-        const int total = s_cnt * nb;
-        int s = s_begin, f = wave;
-        for (int F = wave; F < total; F += 4) {
-            const void* src;
-            if (f < 2 * CB) {
-                src = bsrc + ((size_t)s * (2 * CB) + f) * 64 + lane;
-            } else {
-                const int a = f - 2 * CB;
-                int row = 16 * (a >> 1) + lr;
-                row = row < mrem ? row : mrem - 1;
-                src = abase + (size_t)row * lda + (s << 6) + 32 * (a & 1) + 8 * g;
+    auto chunk_stages = [&](int c) { return c < nchunks ? min(SPC, nstages - c * SPC) : 0; };
+    // Loads this wave issues for a chunk of s_cnt stages: weight blocks q = lrank, lrank+nload, ...
+    // below s_cnt*2*CB, one load each; activation pairs pp = lrank, lrank+nload, ... below s_cnt*RB,
+    // two loads each (a pair always has a live lane: row 16*rb exists for rb < RB).
+    auto strided = [&](int n) { return n > lrank ? (n - lrank + nload - 1) / nload : 0; };
+    auto loads_for = [&](int s_cnt) { return lrank < 0 ? 0 : strided(s_cnt * 2 * CB) + 2 * strided(s_cnt * RB); };
+    // every chunk but the last has SPC stages, so two values cover all chunks
+    const int loads_full = loads_for(SPC);
+    const int loads_last = loads_for(nstages - (nchunks - 1) * SPC);
+    auto wave_loads = [&](int c) { return c < nchunks - 1 ? loads_full : (c == nchunks - 1 ? loads_last : 0); };
+
+    // LDS layout of a chunk of s_cnt stages inside its slot: first the s_cnt*2*CB weight blocks in
+    // the order they lie in the packed matrix (stage, column block, step), then the s_cnt*2*RB
+    // activation blocks (stage, row block, step).
+    const uint4* wsrc = bsrc + lane;                          // this lane's slot in weight block 0
+    const uint16_t* asrc = abase + (size_t)lr * lda + 8 * g;  // row lr, k group g of stage 0
+    auto load_chunk = [&](int c, int slot_idx) {
+        const int s_cnt = chunk_stages(c);
+        if (s_cnt == 0 || lrank < 0) return;
+        const int s0 = c * SPC;
+        const int nw = s_cnt * 2 * CB;
+        const uint32_t slot_addr = ring_addr + (uint32_t)(slot_idx * slot_blocks) * 1024u;
+        const uint4* src = wsrc + ((size_t)s0 * (2 * CB) + lrank) * 64;
+        uint32_t dst = slot_addr + (uint32_t)lrank * 1024u;
+        for (int q = lrank; q < nw; q += nload) {
+            dma_block(src, dst);
+            src += nload * 64;
+            dst += (uint32_t)nload * 1024u;
+        }
+        // activation blocks in pairs (both steps of one row block), pair pp = sl*RB + rb, so that the
+        // two 64-byte halves of each 128-byte line of A are fetched back to back
+        uint32_t adst = slot_addr + (uint32_t)nw * 1024u + (uint32_t)lrank * 2048u;
+        int sl = 0, rb = lrank;
+        while (rb >= RB) {
+            rb -= RB;
+            ++sl;
+        }
+        const int npair = s_cnt * RB;
+        for (int pp = lrank; pp < npair; pp += nload) {
+            if (16 * rb + lr < mrem) {  // lanes of rows past M load nothing: their LDS bytes are never used
+                const uint16_t* src_a = asrc + (size_t)(16 * rb) * lda + ((s0 + sl) << 6);
+                dma_block(src_a, adst);
+                dma_block(src_a + 32, adst + 1024u);
             }
-            __builtin_amdgcn_global_load_lds((global_void_t*)src, (lds_void_t*)(buf + F * 64), 16, 0, 0);
-            f += 4;
-            if (f >= nb) {
-                f -= nb;
-                ++s;
+            adst += (uint32_t)nload * 2048u;
+            rb += nload;
+            while (rb >= RB) {
+                rb -= RB;
+                ++sl;
             }
         }
     };
 
-    auto compute_chunk = [&](const uint4* buf, int c) {
-        if (nrb == 0) return;
-        const int s_cnt = min(SPC, nstages - c * SPC);
-        for (int s = 0; s < s_cnt; ++s) {
-            const uint4* st = buf + s * nb * 64 + lane;
+    // The whole K loop and the store, for a wave with NRB row blocks (0: a wave that only loads).
+    // NRB is a compile-time constant inside so that the loop bodies have no branches.
+    auto run = [&](auto nrb_tag) {
+        constexpr int NRB = decltype(nrb_tag)::value;
+        constexpr int NR = NRB > 0 ? NRB : 1;
+        struct Frags {
             bf16x8 wf[CB][2];
+            bf16x8 xf[NR][2];
+        };
+        f32x4 acc[NR][CB];
 #pragma unroll
-            for (int j = 0; j < CB; ++j) {
-                wf[j][0] = __builtin_bit_cast(bf16x8, st[(2 * j) * 64]);
-                wf[j][1] = __builtin_bit_cast(bf16x8, st[(2 * j + 1) * 64]);
-            }
-            bf16x8 xf[4][2];
+        for (int r = 0; r < NR; ++r)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                if (r < nrb) {
-                    const uint4* ap = st + (2 * CB + 2 * (wave + 4 * r)) * 64;
-                    xf[r][0] = __builtin_bit_cast(bf16x8, ap[0]);
-                    xf[r][1] = __builtin_bit_cast(bf16x8, ap[64]);
+            for (int j = 0; j < CB; ++j) acc[r][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+        auto compute_chunk = [&](int c, int slot_idx) {
+            const int s_cnt = chunk_stages(c);
+            const uint4* slot = ring + (size_t)(slot_idx * slot_blocks) * 64;
+            const uint4* wbase = slot + lane;
+            const uint4* abuf = slot + s_cnt * (2 * CB * 64) + 2 * wave * 64 + lane;
+            auto read_stage = [&](Frags& fr, int sl) {
+                const uint4* wp = wbase + sl * (2 * CB * 64);
+#pragma unroll
+                for (int j = 0; j < CB; ++j) {
+                    fr.wf[j][0] = __builtin_bit_cast(bf16x8, wp[(2 * j) * 64]);
+                    fr.wf[j][1] = __builtin_bit_cast(bf16x8, wp[(2 * j + 1) * 64]);
                 }
-            }
+                const uint4* ap = abuf + sl * nA * 64;
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+                for (int r = 0; r < NRB; ++r) {
+                    fr.xf[r][0] = __builtin_bit_cast(bf16x8, ap[(8 * r) * 64]);
+                    fr.xf[r][1] = __builtin_bit_cast(bf16x8, ap[(8 * r + 1) * 64]);
+                }
+                __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the steps they feed
+            };
+            auto mfma_stage = [&](const Frags& fr) {
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    if (r < nrb) {
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int r = 0; r < NRB; ++r)
 #pragma unroll
                         for (int j = 0; j < CB; ++j)
-                            acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[j][i], xf[r][i], acc[r][j], 0, 0, 0);
+                            acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fr.wf[j][i], fr.xf[r][i], acc[r][j], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            // Stages in ascending order, software pipelined: the LDS reads of stage s+D-1 are issued
+            // before the steps of stage s (D = 4 for small tiles, whose steps are too few to cover the
+            // LDS latency, else 2).  Reads past the last stage are redirected to the last stage: in
+            // bounds and unused, which keeps the loop body free of branches.
+            constexpr int D = (CB * NRB >= 4) ? 2 : 4;
+            Frags f[D];
+            const int last = s_cnt - 1;
+#pragma unroll
+            for (int d = 0; d < D - 1; ++d) read_stage(f[d], min(d, last));
+            for (int sl = 0; sl < s_cnt; sl += D) {
+#pragma unroll
+                for (int u = 0; u < D; ++u) {
+                    if (sl + u >= s_cnt) return;
+                    read_stage(f[(u + D - 1) % D], min(sl + u + D - 1, last));
+                    mfma_stage(f[u]);
+                }
+            }
+        };
+
+        for (int c = 0; c < P; ++c) load_chunk(c, c);
+        int slot_c = 0;    // slot of chunk c
+        int slot_new = P;  // slot of chunk c+P (the slot chunk c-1 used: nslots = P+1)
+        for (int c = 0; c < nchunks; ++c) {
+            // Loads issued after chunk c's: chunks c+1 .. c+P-1.  Once chunk c has landed here and
+            // the barrier is passed, it has landed for every wave, and every wave is done with chunk
+            // c-1, whose slot is the one chunk c+P goes into.
+            int younger = 0;
+            for (int d = 1; d < P; ++d) younger += wave_loads(c + d);
+            wait_loads_then_barrier(younger);
+            load_chunk(c + P, slot_new);
+            if constexpr (NRB > 0) compute_chunk(c, slot_c);
+            slot_new = slot_c;
+            slot_c = slot_c + 1 == nslots ? 0 : slot_c + 1;
+        }
+
+        // Lane holds C[row = 16*rb + lr][n0 + 16j + 4g + v], v = 0..3.
+        const int n0 = blockIdx.x * (16 * CB);
+#pragma unroll
+        for (int r = 0; r < NRB; ++r) {
+            const int rowl = 16 * (wave + 4 * r) + lr;
+            if (rowl < mrem) {
+                const size_t row = (size_t)(m0 + rowl);
+#pragma unroll
+                for (int j = 0; j < CB; ++j) {
+                    const int n = n0 + 16 * j + 4 * g;
+                    const f32x4 v = acc[r][j];
+                    if (out_f32) {
+                        float4* dst = reinterpret_cast<float4*>(static_cast<float*>(C) + row * ldc + n);
+                        *dst = make_float4(v[0], v[1], v[2], v[3]);
+                    } else {
+                        uint2* dst = reinterpret_cast<uint2*>(static_cast<uint16_t*>(C) + row * ldc + n);
+                        *dst = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
                     }
-        }
-    };
-
-    load_chunk(buf0, 0);
-    for (int c = 0; c < nchunks; c += 2) {
-        __syncthreads();  // chunk c has landed in buf0; every wave is done with buf1
-        if (c + 1 < nchunks) load_chunk(buf1, c + 1);
-        compute_chunk(buf0, c);
-        if (c + 1 < nchunks) {
-            __syncthreads();  // chunk c+1 has landed in buf1; every wave is done with buf0
-            if (c + 2 < nchunks) load_chunk(buf0, c + 2);
-            compute_chunk(buf1, c + 1);
-        }
-    }
-
-    // Lane holds C[row = 16*rb + lr][n0 + 16j + 4g + v], v = 0..3.
-    const int n0 = blockIdx.x * (16 * CB);
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int rowl = 16 * (wave + 4 * r) + lr;
-        if (r < nrb && rowl < mrem) {
-            const size_t row = (size_t)(m0 + rowl);
-#pragma unroll
-            for (int j = 0; j < CB; ++j) {
-                const int n = n0 + 16 * j + 4 * g;
-                const f32x4 v = acc[r][j];
-                if (out_f32) {
-                    float4* dst = reinterpret_cast<float4*>(static_cast<float*>(C) + row * ldc + n);
-                    *dst = make_float4(v[0], v[1], v[2], v[3]);
-                } else {
-                    uint2* dst = reinterpret_cast<uint2*>(static_cast<uint16_t*>(C) + row * ldc + n);
-                    *dst = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
                 }
             }
         }
+    };
+    switch (nrb) {
+        case 0: run(std::integral_constant<int, 0>{}); break;
+        case 1: run(std::integral_constant<int, 1>{}); break;
+        case 2: run(std::integral_constant<int, 2>{}); break;
+        case 3: run(std::integral_constant<int, 3>{}); break;
+        default: run(std::integral_constant<int, 4>{}); break;
     }
 }
 
@@ -208,12 +320,12 @@ __global__ __launch_bounds__(256) void gemm_pack_kernel(const uint16_t* __restri
     }
 }
 
-template <int CB, int CHB>
+template <int CB, int RINGB>
 static void launch_gemm(const void* A, int lda, const void* Bp, void* C, int ldc, int M, int N, int K,
                         int out_f32, hipStream_t s)
 {
     dim3 grid(N / (16 * CB), (M + 255) / 256);
-    hipLaunchKernelGGL((gemm_kernel<CB, CHB>), grid, dim3(256), 0, s, static_cast<const uint16_t*>(A), lda,
+    hipLaunchKernelGGL((gemm_kernel<CB, RINGB>), grid, dim3(256), 0, s, static_cast<const uint16_t*>(A), lda,
                        static_cast<const uint4*>(Bp), C, ldc, M, K, out_f32);
 }
 
@@ -254,17 +366,16 @@ extern "C" int det_gemm_bf16(const void* A, int lda, const void* B_packed, void*
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int f32 = out_dtype == DET_F32;
     const int cb = gemm_cols_per_block(N);
-    const bool small = gemm_chunk_blocks(N) != 64;
-#define DET_GEMM_CASE(CBV)                                                                          \
-    case CBV:                                                                                       \
-        if constexpr (CBV <= 3) {                                                                   \
-            if (small) {                                                                            \
-                launch_gemm<CBV, gemm_small_chunk_blocks(CBV <= 3 ? CBV : 1)>(A, lda, B_packed, C, ldc, M, N, \
-                                                                             K, f32, s);            \
-                break;                                                                              \
-            }                                                                                       \
-        }                                                                                           \
-        launch_gemm<CBV, 64>(A, lda, B_packed, C, ldc, M, N, K, f32, s);                            \
+    const bool small = gemm_small_ring(N);
+#define DET_GEMM_CASE(CBV)                                                                              \
+    case CBV:                                                                                           \
+        if constexpr (CBV <= 3) {                                                                       \
+            if (small) {                                                                                \
+                launch_gemm<CBV, gemm_small_ring_blocks(CBV)>(A, lda, B_packed, C, ldc, M, N, K, f32, s); \
+                break;                                                                                  \
+            }                                                                                           \
+        }                                                                                               \
+        launch_gemm<CBV, kRingBig>(A, lda, B_packed, C, ldc, M, N, K, f32, s);                          \
         break;
     switch (cb) {
         DET_GEMM_CASE(1)
@@ -275,7 +386,7 @@ extern "C" int det_gemm_bf16(const void* A, int lda, const void* B_packed, void*
         DET_GEMM_CASE(6)
         DET_GEMM_CASE(7)
         default:
-            launch_gemm<8, 64>(A, lda, B_packed, C, ldc, M, N, K, f32, s);
+            launch_gemm<8, kRingBig>(A, lda, B_packed, C, ldc, M, N, K, f32, s);
             break;
     }
 #undef DET_GEMM_CASE
