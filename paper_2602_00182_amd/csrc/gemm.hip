@@ -107,7 +107,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const uint16_t* __restrict__ 
     const int RB = (mrem + 15) >> 4;                 // 16-row blocks holding data
     const int nA = 2 * RB;                           // activation blocks per stage
     const int nb = 2 * CB + nA;                      // 1 KB blocks per stage
-    const int SPC = max(1, (RINGB / 4) / nb);        // stages per chunk
+    const int SPC = max(1, (RINGB / 3) / nb);        // stages per chunk: three chunks fill the ring
     const int slot_blocks = SPC * nb;                // blocks per ring slot
     const int nslots = min(4, RINGB / slot_blocks);  // >= 2 by the static_assert
     const int P = nslots - 1;                        // chunks in flight

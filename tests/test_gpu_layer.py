@@ -69,9 +69,13 @@ def run_layer(d, layer, seq_ids, positions):
 
 def test_layer_vs_oracle(d, orc, layer):
     """B = 3 sequences at positions 2047, 1000, 0.  The oracle's contractions are fp64 references
-    rounded once to bf16, so intermediate activations can differ from the GPU's by one bf16 ulp;
-    those flips pass through the following GEMMs as noise of relative size ~2^-8/sqrt(K) each.
-    Bound used: |err| <= 2^-6 |ref| + 2^-7 rms(ref)."""
+    rounded once to bf16, so wherever an fp32 result sits near a bf16 rounding boundary the two
+    sides can land one bf16 ulp apart (2^-7 relative at most).  The output is x + o-branch +
+    mlp-branch with a rounding after each add: two such flips on the output itself (2 * 2^-7 |ref|
+    worst case, 2^-6 |ref|), one on each branch value before it is added (2^-7 of a branch value,
+    which is of the order of rms(ref)), plus the flips of earlier activations carried through the
+    projections as noise well below that.  Bound used: |err| <= 2^-6 |ref| + 2^-5 rms(ref), i.e.
+    a few branch-ulps of slack; the per-op tests carry the tight bounds."""
     seq_ids, positions = [0, 1, 2], [2047, 1000, 0]
     step("decoder layer B=3 vs oracle")
     x, kc, vc = run_layer(d, layer, seq_ids, positions)
@@ -86,7 +90,7 @@ def test_layer_vs_oracle(d, orc, layer):
     reff = bits_to_f64(ref)
     rms = np.sqrt((reff ** 2).mean())
     err = np.abs(got - reff)
-    assert (err <= 2.0 ** -6 * np.abs(reff) + 2.0 ** -7 * rms).all(), (err.max(), rms)
+    assert (err <= 2.0 ** -6 * np.abs(reff) + 2.0 ** -5 * rms).all(), (err.max(), rms)
     # the caches: K rows are rope(bf16(projection)), V rows bf16(projection): one-ulp flips allowed
     gk, gv = bits_to_f64(down_bf16(kc)), bits_to_f64(down_bf16(vc))
     rk, rv = bits_to_f64(kc0), bits_to_f64(vc0)   # oracle updated these in place
