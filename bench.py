@@ -35,6 +35,10 @@ N_SETS = 3
 PEAK_MFMA_TFLOPS = 2500.0   # MI355X dense bf16
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 DOMINANT = (4096, 28672)    # the launch that moves most of the step's bytes (gemm_kernel<7>)
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a
+# plain copy kernel (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000): 238.78 MB read + 3.26 MB written, averaged
+# over the nine M of the sweep (summary under profiles/, kernel gemm_kernel<7,144>).
+DOMINANT_TRAFFIC_BYTES = 242.04e6
 
 
 def gemm_flops(M, N, K):
@@ -52,6 +56,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--skip-extras", action="store_true", help="only the timed GEMM workload")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run a plain device-to-device copy of known size (for scaling rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE readings) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -68,6 +75,17 @@ def main():
         sys.exit(2)
     dev = "cuda:0"
     torch.cuda.set_device(0)
+
+    if args.calibrate_copy:
+        nbytes = 256 << 20
+        a = torch.full((nbytes,), 7, dtype=torch.uint8, device=dev)
+        b = torch.empty_like(a)
+        for _ in range(5):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": nbytes, "calibrate_copy_bytes_written": nbytes,
+                          "launches": 5}))
+        return
 
     # ------------------------------------------------------------------ resident inputs
     weights = {}   # (K, N, set) -> packed weight
@@ -132,7 +150,7 @@ def main():
     achieved = dom_bytes / dom_avg_ms / 1e6
     roofline = {"bound": "hbm", "kernel": "det::gemm_kernel<7> (K=4096, N=28672, M=1..256)",
                 "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None,
+                "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": DOMINANT_TRAFFIC_BYTES,
                 "avg_launch_us": round(dom_avg_ms * 1e3, 2), "bytes_per_launch": int(dom_bytes)}
 
     result = {
