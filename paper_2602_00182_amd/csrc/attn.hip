@@ -160,7 +160,11 @@ __global__ __launch_bounds__(256) void attn_chunk_kernel(const uint16_t* __restr
 
 // ------------------------------------------------------------------ attention, pass 2
 
-// Grid (query head, sequence); 128 threads, thread = d.
+// Grid (query head, sequence); 128 threads, thread = d.  The arithmetic is the ascending-chunk fold
+// of the canonical order; only the data movement is parallel: the chunk maxima are reduced across
+// the threads (max is exact, so order free), the weights w_c = det_expf(m_c - m) are computed one
+// chunk per thread into LDS, and each thread then folds L and its own O[d] over the chunks in
+// ascending order with the loads of 8 chunks in flight at a time.
 __global__ __launch_bounds__(128) void attn_combine_kernel(const int32_t* __restrict__ seqlens,
                                                            const float* __restrict__ ws_m,
                                                            const float* __restrict__ ws_l,
@@ -168,6 +172,9 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const int32_t* __rest
                                                            uint16_t* __restrict__ out, int Hq, int Lmax,
                                                            int ncmax, int len_offset)
 {
+    __shared__ float s_w[128];
+    __shared__ float s_l[128];
+    __shared__ float s_red[2];
     const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
     int len = seqlens[b] + len_offset;
     len = len > Lmax ? Lmax : len;
@@ -178,14 +185,45 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const int32_t* __rest
     }
     const int nc = (len + kChunk - 1) / kChunk;
     const size_t part = ((size_t)b * Hq + h) * ncmax;
-    const float m = combine_max(ws_m + part, nc);
+    float m = -INFINITY;
+    for (int c = d; c < nc; c += 128) m = fmaxf(m, ws_m[part + c]);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, kWave));
+    if ((d & 63) == 0) s_red[d >> 6] = m;
+    __syncthreads();
+    m = fmaxf(s_red[0], s_red[1]);
+
     float L = 0.0f, O = 0.0f;
-    for (int c = 0; c < nc; ++c) {
-        const float w = det_expf(ws_m[part + c] - m);
-        const float wl = w * ws_l[part + c];
-        L = L + wl;
-        const float wo = w * ws_o[(part + c) * kD + d];
-        O = O + wo;
+    for (int c0 = 0; c0 < nc; c0 += 128) {
+        const int n = min(128, nc - c0);
+        __syncthreads();  // the previous tile's s_w / s_l are no longer read
+        if (d < n) {
+            s_w[d] = det_expf(ws_m[part + c0 + d] - m);
+            s_l[d] = ws_l[part + c0 + d];
+        }
+        __syncthreads();
+        const float* op = ws_o + (part + c0) * kD + d;
+        int c = 0;
+        for (; c + 8 <= n; c += 8) {
+            float o[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) o[u] = op[(size_t)(c + u) * kD];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float w = s_w[c + u];
+                const float wl = w * s_l[c + u];
+                L = L + wl;
+                const float wo = w * o[u];
+                O = O + wo;
+            }
+        }
+        for (; c < n; ++c) {
+            const float w = s_w[c];
+            const float wl = w * s_l[c];
+            L = L + wl;
+            const float wo = w * op[(size_t)c * kD];
+            O = O + wo;
+        }
     }
     dst[d] = f32_to_bf16_rne(O / L);
 }
