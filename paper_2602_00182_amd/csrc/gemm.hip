@@ -130,8 +130,16 @@ __global__ __launch_bounds__(256) void gemm_kernel(const uint16_t* __restrict__ 
     // Loads this wave issues for a chunk of s_cnt stages: weight blocks q = lrank, lrank+nload, ...
     // below s_cnt*2*CB, one load each; activation pairs pp = lrank, lrank+nload, ... below s_cnt*RB,
     // two loads each (a pair always has a live lane: row 16*rb exists for rb < RB).
+    // From 4 row blocks on (every wave loads and computes) the split is per stage instead: wave w
+    // takes the weight blocks f = w, w+4, ... below 2*CB of each stage and the pairs of its own row
+    // blocks, and issues them between the matrix-core steps of the stage it is computing.
+    const bool interleaved = CB <= 3 && RB >= 4;  // wide tiles measured faster with burst issue
+    const int nbw = 2 * CB > wave ? (2 * CB - wave + 3) >> 2 : 0;  // weight blocks per stage, this wave
     auto strided = [&](int n) { return n > lrank ? (n - lrank + nload - 1) / nload : 0; };
-    auto loads_for = [&](int s_cnt) { return lrank < 0 ? 0 : strided(s_cnt * 2 * CB) + 2 * strided(s_cnt * RB); };
+    auto loads_for = [&](int s_cnt) {
+        if (interleaved) return s_cnt * (nbw + 2 * nrb);
+        return lrank < 0 ? 0 : strided(s_cnt * 2 * CB) + 2 * strided(s_cnt * RB);
+    };
     // every chunk but the last has SPC stages, so two values cover all chunks
     const int loads_full = loads_for(SPC);
     const int loads_last = loads_for(nstages - (nchunks - 1) * SPC);
@@ -142,12 +150,35 @@ __global__ __launch_bounds__(256) void gemm_kernel(const uint16_t* __restrict__ 
     // activation blocks (stage, row block, step).
     const uint4* wsrc = bsrc + lane;                          // this lane's slot in weight block 0
     const uint16_t* asrc = abase + (size_t)lr * lda + 8 * g;  // row lr, k group g of stage 0
+    // One stage's loads of this wave under the per-stage split (stage sl of a chunk starting at
+    // global stage s0 whose slot starts at slot_addr and holds nw weight blocks).
+    auto issue_weight = [&](int s0, int sl, int t, uint32_t slot_addr) {
+        const int f = wave + 4 * t;
+        if (f < 2 * CB)
+            dma_block(wsrc + ((size_t)(s0 + sl) * (2 * CB) + f) * 64, slot_addr + (uint32_t)(sl * 2 * CB + f) * 1024u);
+    };
+    auto issue_pair = [&](int s0, int sl, int r, uint32_t slot_addr, int nw) {
+        const int rb = wave + 4 * r;
+        if (16 * rb + lr < mrem) {  // lanes of rows past M load nothing: their LDS bytes are never used
+            const uint16_t* src_a = asrc + (size_t)(16 * rb) * lda + ((s0 + sl) << 6);
+            const uint32_t d = slot_addr + (uint32_t)nw * 1024u + (uint32_t)(sl * RB + rb) * 2048u;
+            dma_block(src_a, d);
+            dma_block(src_a + 32, d + 1024u);
+        }
+    };
     auto load_chunk = [&](int c, int slot_idx) {
         const int s_cnt = chunk_stages(c);
         if (s_cnt == 0 || lrank < 0) return;
         const int s0 = c * SPC;
         const int nw = s_cnt * 2 * CB;
         const uint32_t slot_addr = ring_addr + (uint32_t)(slot_idx * slot_blocks) * 1024u;
+        if (interleaved) {  // burst form of the per-stage split (used to prime the ring)
+            for (int sl = 0; sl < s_cnt; ++sl) {
+                for (int t = 0; t < nbw; ++t) issue_weight(s0, sl, t, slot_addr);
+                for (int r = 0; r < nrb; ++r) issue_pair(s0, sl, r, slot_addr, nw);
+            }
+            return;
+        }
         const uint4* src = wsrc + ((size_t)s0 * (2 * CB) + lrank) * 64;
         uint32_t dst = slot_addr + (uint32_t)lrank * 1024u;
         for (int q = lrank; q < nw; q += nload) {
@@ -194,8 +225,13 @@ __global__ __launch_bounds__(256) void gemm_kernel(const uint16_t* __restrict__ 
 #pragma unroll
             for (int j = 0; j < CB; ++j) acc[r][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-        auto compute_chunk = [&](int c, int slot_idx) {
+        // cn / slot_n: the chunk whose loads are issued between the steps (interleaved regime), -1: none
+        auto compute_chunk = [&](int c, int slot_idx, int cn, int slot_n) {
             const int s_cnt = chunk_stages(c);
+            const int sn_cnt = cn >= 0 ? chunk_stages(cn) : 0;
+            const int sn0 = cn * SPC;
+            const int nwn = sn_cnt * 2 * CB;
+            const uint32_t slot_n_addr = ring_addr + (uint32_t)(slot_n * slot_blocks) * 1024u;
             const uint4* slot = ring + (size_t)(slot_idx * slot_blocks) * 64;
             const uint4* wbase = slot + lane;
             const uint4* abuf = slot + s_cnt * (2 * CB * 64) + 2 * wave * 64 + lane;
@@ -214,14 +250,32 @@ __global__ __launch_bounds__(256) void gemm_kernel(const uint16_t* __restrict__ 
                 }
                 __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the steps they feed
             };
-            auto mfma_stage = [&](const Frags& fr) {
+            // Steps of stage sl.  In the interleaved regime the loads of stage sl of chunk cn go out
+            // between the groups of steps (pairs after the i = 0 groups, weight blocks after the i = 1
+            // groups), so that address generation overlaps the matrix-core pipe.
+            constexpr int NBW = (2 * CB + 3) / 4;  // most weight blocks per stage any wave takes
+            auto mfma_stage = [&](const Frags& fr, int sl) {
+                const bool ld = sl < sn_cnt;
 #pragma unroll
                 for (int i = 0; i < 2; ++i)
 #pragma unroll
-                    for (int r = 0; r < NRB; ++r)
+                    for (int r = 0; r < NRB; ++r) {
 #pragma unroll
                         for (int j = 0; j < CB; ++j)
                             acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fr.wf[j][i], fr.xf[r][i], acc[r][j], 0, 0, 0);
+                        if (ld) {
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (i == 0) {
+                                issue_pair(sn0, sl, r, slot_n_addr, nwn);
+                            } else {
+                                issue_weight(sn0, sl, r, slot_n_addr);
+                                if (r == NRB - 1) {
+#pragma unroll
+                                    for (int t = NRB; t < NBW; ++t) issue_weight(sn0, sl, t, slot_n_addr);
+                                }
+                            }
+                        }
+                    }
                 __builtin_amdgcn_sched_barrier(0);
             };
             // Stages in ascending order, software pipelined: the LDS reads of stage s+D-1 are issued
@@ -238,7 +292,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const uint16_t* __restrict__ 
                 for (int u = 0; u < D; ++u) {
                     if (sl + u >= s_cnt) return;
                     read_stage(f[(u + D - 1) % D], min(sl + u + D - 1, last));
-                    mfma_stage(f[u]);
+                    mfma_stage(f[u], sl + u);
                 }
             }
         };
@@ -253,8 +307,16 @@ __global__ __launch_bounds__(256) void gemm_kernel(const uint16_t* __restrict__ 
             int younger = 0;
             for (int d = 1; d < P; ++d) younger += wave_loads(c + d);
             wait_loads_then_barrier(younger);
-            load_chunk(c + P, slot_new);
-            if constexpr (NRB > 0) compute_chunk(c, slot_c);
+            if constexpr (NRB > 0) {
+                if (interleaved) {
+                    compute_chunk(c, slot_c, c + P, slot_new);
+                } else {
+                    load_chunk(c + P, slot_new);
+                    compute_chunk(c, slot_c, -1, 0);
+                }
+            } else {
+                load_chunk(c + P, slot_new);
+            }
             slot_new = slot_c;
             slot_c = slot_c + 1 == nslots ? 0 : slot_c + 1;
         }
