@@ -173,6 +173,7 @@ def main():
         result["bit_identical"] = bit_identical(torch, det, weights, X)
         del weights, C
         torch.cuda.empty_cache()
+        result["attention"] = attention_numbers(torch, det, ds, dev)
         result["decode"] = decode_numbers(torch, det, ds, dev)
     print(json.dumps(result))
 
@@ -197,23 +198,28 @@ def warm_sweep(torch, det, weights, X, C, table):
 
 def cpu_baseline(ds):
     """The oracle as it stands, timed on this host: fp64 reference GEMM of the four shapes at
-    M = 32 rows (a bounded sample of the workload), all host threads."""
+    M = 256 rows (the largest M of the workload; a bounded sample of it: one M of nine), all host
+    threads, repeated until about ten seconds of CPU work have been timed."""
     import oracle
 
     oracle.lib()
-    M = 32
+    M = 256
     flops = 0.0
     t = 0.0
+    reps = 0
+    mats = []
     for j, (K, N) in enumerate(SHAPES):
-        A = ds.normal_bf16(ds.tensor_seed(2, 7) + K, (M, K))
-        B = ds.normal_bf16(ds.tensor_seed(2, j), (K, N), 0.02)
-        t0 = time.perf_counter()
-        oracle.gemm_f64(A, B, want_abs=False)
-        t += time.perf_counter() - t0
-        flops += gemm_flops(M, N, K)
+        mats.append((ds.normal_bf16(ds.tensor_seed(2, 7) + K, (M, K)), ds.normal_bf16(ds.tensor_seed(2, j), (K, N), 0.02), K, N))
+    while t < 10.0 and reps < 4:
+        for A, B, K, N in mats:
+            t0 = time.perf_counter()
+            oracle.gemm_f64(A, B, want_abs=False)
+            t += time.perf_counter() - t0
+            flops += gemm_flops(M, N, K)
+        reps += 1
     return {"value": round(flops / t / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
-            "kind": "oracle", "sample": f"fp64 reference GEMM, the four shapes at M={M} ({flops / 1e9:.1f} GFLOP, "
-                                        f"{t:.1f} s)", "cpu": _cpu_model()}
+            "kind": "oracle", "sample": f"fp64 reference GEMM, the four shapes at M={M}, {reps} pass(es) "
+                                        f"({flops / 1e9:.0f} GFLOP in {t:.1f} s)", "cpu": _cpu_model()}
 
 
 def _cpu_model():
@@ -241,6 +247,40 @@ def bit_identical(torch, det, weights, X):
                 same += int(torch.equal(out.view(torch.int16), ref[:M].view(torch.int16)))
     return {"rate": same / total, "comparisons": total,
             "what": "each (shape, M) output vs rows 0..M-1 of the M=256 output, 5 repeats, bytes"}
+
+
+def attention_numbers(torch, det, ds, dev):
+    """det_attn_decode on the config-3 grid: 32 query heads, 8 KV heads, head_dim 128, full-length
+    sequences.  Algorithmic bytes = B*Hkv*L*D*2*2 (K and V once)."""
+    Hq, Hkv, D = 32, 8, 128
+    scale = float(np.float32(1.0 / math.sqrt(128.0)))
+    rows = []
+    for L in (512, 4096, 32768):
+        for B in (1, 16, 64):
+            base = min(B, 2)   # two distinct sequences of synthetic cache, tiled to B (all addresses distinct)
+            k = ds.normal_bf16_torch(ds.tensor_seed(3, 11), (base, Hkv, L, D), 1.0, 0.0, dev).repeat(B // base, 1, 1, 1)
+            v = ds.normal_bf16_torch(ds.tensor_seed(3, 12), (base, Hkv, L, D), 1.0, 0.0, dev).repeat(B // base, 1, 1, 1)
+            q = ds.normal_bf16_torch(ds.tensor_seed(3, 10), (B, Hq, D), 1.0, 0.0, dev)
+            lens = torch.full((B,), L, dtype=torch.int32, device=dev)
+            ws = torch.empty(det.det_attn_decode_workspace_bytes(B, Hq, D, L), dtype=torch.uint8, device=dev)
+            out = torch.empty((B, Hq, D), dtype=torch.bfloat16, device=dev)
+            for _ in range(2):
+                det.det_attn_decode(q, k, v, lens, out, ws, scale)
+            torch.cuda.synchronize()
+            n = 20 if B * L <= 64 * 4096 else 5
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                det.det_attn_decode(q, k, v, lens, out, ws, scale)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) / n * 1e3
+            by = B * Hkv * L * D * 2 * 2
+            rows.append({"B": B, "L": L, "us": round(us, 1), "gbs": round(by / us / 1e3, 1),
+                         "frac_hbm": round(by / us / 1e3 / PEAK_HBM_GBS, 4), "kv_mb": round(by / 1e6, 1)})
+            del k, v, ws
+            torch.cuda.empty_cache()
+    return rows
 
 
 def decode_numbers(torch, det, ds, dev):
