@@ -122,3 +122,34 @@ def test_long_context_sampled(d, orc):
             ref, refabs = orc.attn_decode_f64(q[b:b + 1, h:h + 1], k[b:b + 1, g:g + 1], v[b:b + 1, g:g + 1],
                                               lens[b:b + 1], SCALE)
             assert within_bound(bits_to_f64(got[b, h]), ref[0, 0], refabs[0, 0]).all()
+
+
+def test_full_size_batch64_context32768_sampled(d, orc):
+    """The largest configuration bench.py times (B = 64, L = 32768: 8.6 GB of KV cache), generated
+    on the device; the oracle recomputes sampled (sequence, head) pairs from the same counter-based
+    generator on the host, so no input or expected value comes from the GPU."""
+    B, Hq, Hkv, Lmax, D = 64, 32, 8, 32768, 128
+    sq, sk, sv = ds.tensor_seed(3, 20), ds.tensor_seed(3, 21), ds.tensor_seed(3, 22)
+    step("attention B=64 L=32768: generating 8.6 GB of cache on the device")
+    q = ds.normal_bf16_torch(sq, (B, Hq, D), 1.0, 0.0, DEV)
+    k = ds.normal_bf16_torch(sk, (B, Hkv, Lmax, D), 1.0, 0.0, DEV)
+    v = ds.normal_bf16_torch(sv, (B, Hkv, Lmax, D), 1.0, 0.0, DEV)
+    lens_h = ds.uniform_int(ds.tensor_seed(3, 23), (B,), Lmax // 2, Lmax)
+    lens_h[0] = Lmax
+    lens = up(lens_h)
+    ws = torch.empty(d.det_attn_decode_workspace_bytes(B, Hq, D, Lmax), dtype=torch.uint8, device=DEV)
+    out = torch.empty((B, Hq, D), dtype=torch.bfloat16, device=DEV)
+    step("attention B=64 L=32768: launch")
+    d.det_attn_decode(q, k, v, lens, out, ws, SCALE)
+    torch.cuda.synchronize()
+    got = down_bf16(out)
+    del k, v, ws
+    torch.cuda.empty_cache()
+    per_head = Lmax * D
+    for b, h in [(0, 0), (17, 13), (63, 31), (40, 6)]:
+        g = h // 4
+        qh = ds.normal_bf16_slice(sq, (b * Hq + h) * D, D).reshape(1, 1, D)
+        kh = ds.normal_bf16_slice(sk, (b * Hkv + g) * per_head, per_head).reshape(1, 1, Lmax, D)
+        vh = ds.normal_bf16_slice(sv, (b * Hkv + g) * per_head, per_head).reshape(1, 1, Lmax, D)
+        ref, refabs = orc.attn_decode_f64(qh, kh, vh, lens_h[b:b + 1], SCALE)
+        assert within_bound(bits_to_f64(got[b, h]), ref[0, 0], refabs[0, 0]).all(), (b, h)
