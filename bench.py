@@ -293,7 +293,7 @@ def decode_numbers(torch, det, ds, dev):
     s = ds.tensor_seed(4, 0)
     g = lambda i, shape, std=0.02, mean=0.0: ds.normal_bf16_torch(s + i, shape, std, mean, dev)
     packed = [g(0, (H,), 0.0, 1.0), det.pack_weight(g(1, (H, (Hq + 2 * Hkv) * D))), det.pack_weight(g(2, (Hq * D, H))),
-              g(3, (H,), 0.0, 1.0), det.pack_weight(g(4, (H, 2 * F))), det.pack_weight(g(5, (F, H)))]
+              g(3, (H,), 0.0, 1.0), det.pack_gate_up(g(4, (H, 2 * F))), det.pack_weight(g(5, (F, H)))]
     struct = det.layer_weights(*packed)
     cfg = det.layer_cfg(H, Hq, Hkv, D, F, Lmax, 1e-5, scale)
     cos_t, sin_t = ds.rope_tables(Lmax, D, 5.0e5)

@@ -71,6 +71,21 @@ size_t det_gemm_packed_b_bytes(int N, int K);
  * overlap. */
 int det_gemm_pack_b(const void *B_kn, void *B_packed, int N, int K, void *stream);
 
+/* Fused epilogues of the same kernel; each produces exactly the bytes of the unfused sequence.
+ *
+ * det_gemm_bf16_residual: C = bf16( fp32(bf16(A B)) + fp32(R) ), i.e. det_gemm_bf16 (bf16 out)
+ *   followed by det_residual_add.  R [M, N] bf16 with row stride ldr (ldr % 4 == 0); C may be R.
+ * det_gemm_pack_gate_up: packs a [K, 2F] bf16 matrix whose columns are F gate columns followed by
+ *   F up columns, with gate_j and up_j made neighbours, for det_gemm_swiglu_bf16.  F % 8 == 0.
+ * det_gemm_swiglu_bf16: Y[M, F] = det_swiglu( g, u ) with [g | u] = det_gemm_bf16(A, [Wgate | Wup])
+ *   rounded to bf16 first.  B_gate_up is the output of det_gemm_pack_gate_up; ldy >= F, ldy % 4 == 0.
+ */
+int det_gemm_bf16_residual(const void *A, int lda, const void *B_packed, const void *R, int ldr,
+                           void *C, int ldc, int M, int N, int K, void *stream);
+int det_gemm_pack_gate_up(const void *B_kn, void *B_packed, int F, int K, void *stream);
+int det_gemm_swiglu_bf16(const void *A, int lda, const void *B_gate_up, void *Y, int ldy, int M,
+                         int F, int K, void *stream);
+
 /* ---------------------------------------------------------------------------------------------
  * RMSNorm (section 6.5, invariant 2: canonical tree reduction; tree of Fig. "kernel_tree").
  *
@@ -152,8 +167,9 @@ int det_embed_gather(const void *table, const int32_t *tokens, void *out, int B,
  *   a = attn_decode(q, caches, len = positions[b] + 1);
  *   x = x + a Wo;  h = rmsnorm(x, w_norm2);  [g|u] = h Wgu;  m = swiglu(g, u);  x = x + m Wdown.
  *
- * Every step is the operation documented above, so the layer inherits their invariance: row b of
- * x and sequence b's cache rows do not depend on B or on the other sequences.
+ * Every step is the operation documented above (the residual adds and the SwiGLU run as fused GEMM
+ * epilogues with the bytes of the unfused steps), so the layer inherits their invariance: row b
+ * of x and sequence b's cache rows do not depend on B or on the other sequences.
  */
 typedef struct det_layer_cfg {
     int32_t H;      /* hidden size */
@@ -171,7 +187,7 @@ typedef struct det_layer_weights {
     const void *wqkv;    /* packed [K=H, N=(Hq+2Hkv)D]; columns: q heads, k heads, v heads */
     const void *wo;      /* packed [K=Hq*D, N=H] */
     const void *w_norm2; /* [H] bf16 */
-    const void *wgu;     /* packed [K=H, N=2F]; columns: gate, up */
+    const void *wgu;     /* [K=H, N=2F] (columns: gate, up) packed by det_gemm_pack_gate_up */
     const void *wdown;   /* packed [K=F, N=H] */
 } det_layer_weights;
 

@@ -11,7 +11,8 @@ import torch
 from ._lib import LayerCfg, LayerWeights, lib
 
 __all__ = [
-    "DetError", "det_gemm_bf16", "det_gemm_packed_b_bytes", "det_gemm_pack_b", "det_rmsnorm",
+    "DetError", "det_gemm_bf16", "det_gemm_packed_b_bytes", "det_gemm_pack_b", "det_gemm_bf16_residual",
+    "det_gemm_pack_gate_up", "det_gemm_swiglu_bf16", "pack_gate_up", "det_rmsnorm",
     "det_attn_decode_workspace_bytes", "det_attn_decode", "det_softmax_f32", "det_argmax", "det_rope",
     "det_swiglu", "det_residual_add", "det_embed_gather", "det_decoder_layer_workspace_bytes",
     "det_decoder_layer", "det_next_token", "det_fingerprint", "det_last_hip_error", "layer_cfg",
@@ -104,6 +105,50 @@ def det_gemm_bf16(A: torch.Tensor, B_packed: torch.Tensor, C_out: torch.Tensor, 
                                                  ldc, M, N, K, od, _stream(stream)))
 
 
+def det_gemm_pack_gate_up(B_kn: torch.Tensor, B_packed: torch.Tensor, stream=None) -> None:
+    K, N2 = B_kn.shape
+    if N2 % 2 or B_packed.numel() * B_packed.element_size() < 2 * N2 * K:
+        raise ValueError("bad gate/up weight")
+    _check("det_gemm_pack_gate_up", lib().det_gemm_pack_gate_up(_contig(B_kn, torch.bfloat16), _contig(B_packed),
+                                                                 N2 // 2, K, _stream(stream)))
+
+
+def pack_gate_up(B_kn: torch.Tensor, stream=None) -> torch.Tensor:
+    """Allocates and fills the packed form of a [K, 2F] (gate | up) weight for det_gemm_swiglu_bf16."""
+    K, N2 = B_kn.shape
+    if det_gemm_packed_b_bytes(N2, K) == 0:
+        raise DetError("det_gemm_packed_b_bytes", 2)
+    out = torch.empty(N2 * K, dtype=torch.bfloat16, device=B_kn.device)
+    det_gemm_pack_gate_up(B_kn, out, stream)
+    return out
+
+
+def _ld(t: torch.Tensor, cols: int) -> int:
+    return t.stride(0) if t.shape[0] > 1 else max(t.stride(0), cols)
+
+
+def det_gemm_bf16_residual(A, B_packed, R, C_out, N: int, K: int, stream=None) -> None:
+    """C_out = bf16(fp32(bf16(A @ B)) + fp32(R)); C_out may be R."""
+    M = A.shape[0]
+    if A.shape[1] != K or C_out.shape != (M, N) or R.shape != (M, N):
+        raise ValueError("bad GEMM operand shapes")
+    if A.stride(1) != 1 or C_out.stride(1) != 1 or R.stride(1) != 1:
+        raise ValueError("rows must be contiguous")
+    _check("det_gemm_bf16_residual", lib().det_gemm_bf16_residual(
+        _ptr(A, torch.bfloat16), _ld(A, K), _contig(B_packed), _ptr(R, torch.bfloat16), _ld(R, N),
+        _ptr(C_out, torch.bfloat16), _ld(C_out, N), M, N, K, _stream(stream)))
+
+
+def det_gemm_swiglu_bf16(A, B_gate_up, Y, F: int, K: int, stream=None) -> None:
+    """Y[M, F] = swiglu(bf16(A @ Wgate), bf16(A @ Wup)) with the weight packed by pack_gate_up."""
+    M = A.shape[0]
+    if A.shape[1] != K or Y.shape != (M, F) or A.stride(1) != 1 or Y.stride(1) != 1:
+        raise ValueError("bad GEMM operand shapes")
+    _check("det_gemm_swiglu_bf16", lib().det_gemm_swiglu_bf16(
+        _ptr(A, torch.bfloat16), _ld(A, K), _contig(B_gate_up), _ptr(Y, torch.bfloat16), _ld(Y, F), M, F, K,
+        _stream(stream)))
+
+
 def det_rmsnorm(x: torch.Tensor, w: torch.Tensor, y: torch.Tensor, eps: float, stream=None) -> None:
     M, H = x.shape
     if w.shape != (H,) or y.shape != x.shape:
@@ -189,8 +234,9 @@ def layer_cfg(H, Hq, Hkv, D, F, Lmax, eps, scale) -> LayerCfg:
 
 
 def layer_weights(w_norm1, wqkv, wo, w_norm2, wgu, wdown) -> LayerWeights:
-    """Device pointers of one layer's weights (projections already packed).  The struct keeps a
-    reference to the six tensors, so they live as long as it does."""
+    """Device pointers of one layer's weights (projections already packed: wqkv, wo, wdown with
+    pack_weight, wgu with pack_gate_up).  The struct keeps a reference to the six tensors, so they
+    live as long as it does."""
     tensors = (w_norm1, wqkv, wo, w_norm2, wgu, wdown)
     s = LayerWeights(*[_contig(t) for t in tensors])
     s._keep = tensors

@@ -89,10 +89,24 @@ __device__ __forceinline__ void wait_loads_then_barrier(int n)
 }
 #undef DET_WB
 
-template <int CB, int RINGB>
+// Epilogues.  kEpiStore: C = bf16(acc) or fp32 acc.  kEpiResidual: C = bf16(fp32(bf16(acc)) + fp32(R)),
+// the bytes of the plain GEMM followed by the residual add.  kEpiSwiglu: the weight columns are packed
+// gate_j, up_j interleaved, and Y[j] = bf16( silu(bf16(acc_gate_j)) * bf16(acc_up_j) ), the bytes of the
+// plain GEMM followed by the SwiGLU step.  C (and R) may alias nothing the kernel reads except that C
+// may be R itself: an output element is read and written by the same lane only.
+constexpr int kEpiStore = 0, kEpiResidual = 1, kEpiSwiglu = 2;
+
+__device__ __forceinline__ float silu_mul(float gate, float up)
+{
+    const float den = 1.0f + det_expf(-gate);
+    const float sg = gate / den;
+    return sg * up;
+}
+
+template <int CB, int RINGB, int EPI>
 __global__ __launch_bounds__(256) void gemm_kernel(const uint16_t* __restrict__ A, int lda,
-                                                   const uint4* __restrict__ Bp, void* __restrict__ C,
-                                                   int ldc, int M, int K, int out_f32)
+                                                   const uint4* __restrict__ Bp, void* C, int ldc,
+                                                   const uint16_t* R, int ldr, int M, int K, int out_f32)
 {
     static_assert(RINGB >= 4 * (CB + 16), "the ring must hold two stages of the largest tile");
     __shared__ uint4 ring[RINGB * 64];
@@ -332,7 +346,23 @@ __global__ __launch_bounds__(256) void gemm_kernel(const uint16_t* __restrict__ 
                 for (int j = 0; j < CB; ++j) {
                     const int n = n0 + 16 * j + 4 * g;
                     const f32x4 v = acc[r][j];
-                    if (out_f32) {
+                    if constexpr (EPI == kEpiSwiglu) {
+                        const float g0 = bf16_to_f32(f32_to_bf16_rne(v[0])), u0 = bf16_to_f32(f32_to_bf16_rne(v[1]));
+                        const float g1 = bf16_to_f32(f32_to_bf16_rne(v[2])), u1 = bf16_to_f32(f32_to_bf16_rne(v[3]));
+                        uint32_t* dst = reinterpret_cast<uint32_t*>(static_cast<uint16_t*>(C) + row * ldc + (n >> 1));
+                        *dst = pack_bf16x2(silu_mul(g0, u0), silu_mul(g1, u1));
+                    } else if constexpr (EPI == kEpiResidual) {
+                        const uint2 rv = *reinterpret_cast<const uint2*>(R + row * ldr + n);
+                        float y[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) y[e] = bf16_to_f32(f32_to_bf16_rne(v[e]));
+                        y[0] = y[0] + bf16lo_to_f32(rv.x);
+                        y[1] = y[1] + bf16hi_to_f32(rv.x);
+                        y[2] = y[2] + bf16lo_to_f32(rv.y);
+                        y[3] = y[3] + bf16hi_to_f32(rv.y);
+                        uint2* dst = reinterpret_cast<uint2*>(static_cast<uint16_t*>(C) + row * ldc + n);
+                        *dst = make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
+                    } else if (out_f32) {
                         float4* dst = reinterpret_cast<float4*>(static_cast<float*>(C) + row * ldc + n);
                         *dst = make_float4(v[0], v[1], v[2], v[3]);
                     } else {
@@ -353,8 +383,10 @@ __global__ __launch_bounds__(256) void gemm_kernel(const uint16_t* __restrict__ 
 }
 
 // One thread per 16 bytes of the packed matrix: gathers 8 K-consecutive elements of one column.
+// gate_up_f > 0: packed column 2j is logical column j (gate) and 2j+1 is gate_up_f + j (up).
 __global__ __launch_bounds__(256) void gemm_pack_kernel(const uint16_t* __restrict__ Bkn,
-                                                        uint4* __restrict__ Bp, int N, int K, int cb)
+                                                        uint4* __restrict__ Bp, int N, int K, int cb,
+                                                        int gate_up_f)
 {
     const size_t total = (size_t)N * K / 8;
     const int stage_u4 = cb * 2 * 64;
@@ -368,7 +400,8 @@ __global__ __launch_bounds__(256) void gemm_pack_kernel(const uint16_t* __restri
         const int j = f >> 7;
         const int i = (f >> 6) & 1;
         const int lane = f & 63;
-        const int n = tile * 16 * cb + 16 * j + (lane & 15);
+        int n = tile * 16 * cb + 16 * j + (lane & 15);
+        if (gate_up_f > 0) n = (n & 1) ? gate_up_f + (n >> 1) : (n >> 1);
         const int k0 = 64 * st + 32 * i + 8 * (lane >> 4);
         uint16_t e[8];
 #pragma unroll
@@ -382,13 +415,47 @@ __global__ __launch_bounds__(256) void gemm_pack_kernel(const uint16_t* __restri
     }
 }
 
-template <int CB, int RINGB>
-static void launch_gemm(const void* A, int lda, const void* Bp, void* C, int ldc, int M, int N, int K,
-                        int out_f32, hipStream_t s)
+template <int CB, int RINGB, int EPI>
+static void launch_gemm(const void* A, int lda, const void* Bp, void* C, int ldc, const void* R, int ldr, int M,
+                        int N, int K, int out_f32, hipStream_t s)
 {
     dim3 grid(N / (16 * CB), (M + 255) / 256);
-    hipLaunchKernelGGL((gemm_kernel<CB, RINGB>), grid, dim3(256), 0, s, static_cast<const uint16_t*>(A), lda,
-                       static_cast<const uint4*>(Bp), C, ldc, M, K, out_f32);
+    hipLaunchKernelGGL((gemm_kernel<CB, RINGB, EPI>), grid, dim3(256), 0, s, static_cast<const uint16_t*>(A), lda,
+                       static_cast<const uint4*>(Bp), C, ldc, static_cast<const uint16_t*>(R), ldr, M, K,
+                       out_f32);
+}
+
+// Picks the kernel configuration from N alone and launches it.
+template <int EPI>
+static int gemm_dispatch(const void* A, int lda, const void* Bp, void* C, int ldc, const void* R, int ldr, int M,
+                         int N, int K, int f32, hipStream_t s)
+{
+    const int cb = gemm_cols_per_block(N);
+    const bool small = gemm_small_ring(N);
+#define DET_GEMM_CASE(CBV)                                                                                  \
+    case CBV:                                                                                               \
+        if constexpr (CBV <= 3) {                                                                           \
+            if (small) {                                                                                    \
+                launch_gemm<CBV, gemm_small_ring_blocks(CBV), EPI>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s); \
+                break;                                                                                      \
+            }                                                                                               \
+        }                                                                                                   \
+        launch_gemm<CBV, kRingBig, EPI>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s);                       \
+        break;
+    switch (cb) {
+        DET_GEMM_CASE(1)
+        DET_GEMM_CASE(2)
+        DET_GEMM_CASE(3)
+        DET_GEMM_CASE(4)
+        DET_GEMM_CASE(5)
+        DET_GEMM_CASE(6)
+        DET_GEMM_CASE(7)
+        default:
+            launch_gemm<8, kRingBig, EPI>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s);
+            break;
+    }
+#undef DET_GEMM_CASE
+    return check_launch();
 }
 
 static bool gemm_shape_ok(int N, int K) { return N > 0 && K > 0 && N % 16 == 0 && K % 64 == 0; }
@@ -403,7 +470,7 @@ extern "C" size_t det_gemm_packed_b_bytes(int N, int K)
     return (size_t)2 * N * K;
 }
 
-extern "C" int det_gemm_pack_b(const void* B_kn, void* B_packed, int N, int K, void* stream)
+static int pack_impl(const void* B_kn, void* B_packed, int N, int K, int gate_up_f, void* stream)
 {
     if (!B_kn || !B_packed) return DET_EINVAL;
     if (!gemm_shape_ok(N, K)) return DET_ESHAPE;
@@ -412,45 +479,59 @@ extern "C" int det_gemm_pack_b(const void* B_kn, void* B_packed, int N, int K, v
     const int blocks = (int)((total + 255) / 256 < 65536 ? (total + 255) / 256 : 65536);
     hipLaunchKernelGGL(gemm_pack_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<const uint16_t*>(B_kn), static_cast<uint4*>(B_packed), N, K,
-                       gemm_cols_per_block(N));
+                       gemm_cols_per_block(N), gate_up_f);
     return check_launch();
+}
+
+extern "C" int det_gemm_pack_b(const void* B_kn, void* B_packed, int N, int K, void* stream)
+{
+    return pack_impl(B_kn, B_packed, N, K, 0, stream);
+}
+
+extern "C" int det_gemm_pack_gate_up(const void* B_kn, void* B_packed, int F, int K, void* stream)
+{
+    if (F < 1 || F % 8 != 0) return DET_ESHAPE;
+    return pack_impl(B_kn, B_packed, 2 * F, K, F, stream);
+}
+
+static int gemm_args_ok(const void* A, int lda, const void* Bp, const void* C, int ldc, int M, int N, int K)
+{
+    if (!A || !Bp || !C || M < 1) return DET_EINVAL;
+    if (!gemm_shape_ok(N, K)) return DET_ESHAPE;
+    if (lda < K) return DET_EINVAL;
+    if (!aligned16(A) || !aligned16(Bp) || !aligned16(C) || lda % 8 != 0 || ldc % 4 != 0) return DET_EALIGN;
+    return DET_OK;
 }
 
 extern "C" int det_gemm_bf16(const void* A, int lda, const void* B_packed, void* C, int ldc, int M, int N,
                              int K, int out_dtype, void* stream)
 {
-    if (!A || !B_packed || !C || M < 1) return DET_EINVAL;
     if (out_dtype != DET_BF16 && out_dtype != DET_F32) return DET_EINVAL;
-    if (!gemm_shape_ok(N, K)) return DET_ESHAPE;
-    if (lda < K || ldc < N) return DET_EINVAL;
-    if (!aligned16(A) || !aligned16(B_packed) || !aligned16(C) || lda % 8 != 0 || ldc % 4 != 0)
-        return DET_EALIGN;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const int f32 = out_dtype == DET_F32;
-    const int cb = gemm_cols_per_block(N);
-    const bool small = gemm_small_ring(N);
-#define DET_GEMM_CASE(CBV)                                                                              \
-    case CBV:                                                                                           \
-        if constexpr (CBV <= 3) {                                                                       \
-            if (small) {                                                                                \
-                launch_gemm<CBV, gemm_small_ring_blocks(CBV)>(A, lda, B_packed, C, ldc, M, N, K, f32, s); \
-                break;                                                                                  \
-            }                                                                                           \
-        }                                                                                               \
-        launch_gemm<CBV, kRingBig>(A, lda, B_packed, C, ldc, M, N, K, f32, s);                          \
-        break;
-    switch (cb) {
-        DET_GEMM_CASE(1)
-        DET_GEMM_CASE(2)
-        DET_GEMM_CASE(3)
-        DET_GEMM_CASE(4)
-        DET_GEMM_CASE(5)
-        DET_GEMM_CASE(6)
-        DET_GEMM_CASE(7)
-        default:
-            launch_gemm<8, kRingBig>(A, lda, B_packed, C, ldc, M, N, K, f32, s);
-            break;
-    }
-#undef DET_GEMM_CASE
-    return check_launch();
+    const int rc = gemm_args_ok(A, lda, B_packed, C, ldc, M, N, K);
+    if (rc != DET_OK) return rc;
+    if (ldc < N) return DET_EINVAL;
+    return gemm_dispatch<kEpiStore>(A, lda, B_packed, C, ldc, nullptr, 0, M, N, K, out_dtype == DET_F32,
+                                    static_cast<hipStream_t>(stream));
+}
+
+extern "C" int det_gemm_bf16_residual(const void* A, int lda, const void* B_packed, const void* R, int ldr,
+                                      void* C, int ldc, int M, int N, int K, void* stream)
+{
+    const int rc = gemm_args_ok(A, lda, B_packed, C, ldc, M, N, K);
+    if (rc != DET_OK) return rc;
+    if (!R || ldc < N || ldr < N) return DET_EINVAL;
+    if (!aligned16(R) || ldr % 4 != 0) return DET_EALIGN;
+    return gemm_dispatch<kEpiResidual>(A, lda, B_packed, C, ldc, R, ldr, M, N, K, 0,
+                                       static_cast<hipStream_t>(stream));
+}
+
+extern "C" int det_gemm_swiglu_bf16(const void* A, int lda, const void* B_gate_up, void* Y, int ldy, int M,
+                                    int F, int K, void* stream)
+{
+    if (F < 1 || F % 8 != 0) return DET_ESHAPE;
+    const int rc = gemm_args_ok(A, lda, B_gate_up, Y, ldy, M, 2 * F, K);
+    if (rc != DET_OK) return rc;
+    if (ldy < F) return DET_EINVAL;
+    return gemm_dispatch<kEpiSwiglu>(A, lda, B_gate_up, Y, ldy, nullptr, 0, M, 2 * F, K, 0,
+                                     static_cast<hipStream_t>(stream));
 }

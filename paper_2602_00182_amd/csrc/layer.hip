@@ -7,7 +7,7 @@ namespace det {
 static size_t up256(size_t n) { return (n + 255) & ~(size_t)255; }
 
 struct LayerWs {
-    size_t h, qkv, qbuf, att, proj, gu, mm, attn, attn_bytes, total;
+    size_t h, qkv, qbuf, att, mm, attn, attn_bytes, total;
 };
 
 static LayerWs layer_ws(const det_layer_cfg& c, int B)
@@ -24,8 +24,6 @@ static LayerWs layer_ws(const det_layer_cfg& c, int B)
     w.qkv = take(2 * (size_t)B * nqkv);
     w.qbuf = take(2 * (size_t)B * c.Hq * c.D);
     w.att = take(2 * (size_t)B * c.Hq * c.D);
-    w.proj = take(2 * (size_t)B * c.H);
-    w.gu = take(2 * (size_t)B * 2 * c.F);
     w.mm = take(2 * (size_t)B * c.F);
     w.attn_bytes = det_attn_decode_workspace_bytes(B, c.Hq, c.D, c.Lmax);
     w.attn = take(w.attn_bytes);
@@ -36,7 +34,7 @@ static LayerWs layer_ws(const det_layer_cfg& c, int B)
 static bool layer_cfg_ok(const det_layer_cfg* c)
 {
     return c && c->H > 0 && c->Hq > 0 && c->Hkv > 0 && c->D == 128 && c->F > 0 && c->Lmax > 0 &&
-           c->Hq % c->Hkv == 0 && c->H % 64 == 0 && c->F % 64 == 0;
+           c->Hq % c->Hkv == 0 && c->H % 64 == 0 && c->F % 64 == 0;  // F % 64: K of the down projection
 }
 
 }  // namespace det
@@ -66,8 +64,6 @@ extern "C" int det_decoder_layer(const det_layer_weights* w, const det_layer_cfg
     void* qkv = base + l.qkv;
     void* qbuf = base + l.qbuf;
     void* att = base + l.att;
-    void* proj = base + l.proj;
-    uint16_t* gu = reinterpret_cast<uint16_t*>(base + l.gu);
     void* mm = base + l.mm;
     void* aws = base + l.attn;
     const int nqkv = (c.Hq + 2 * c.Hkv) * c.D;
@@ -85,13 +81,10 @@ extern "C" int det_decoder_layer(const det_layer_weights* w, const det_layer_cfg
                         s));
     DET_TRY(attn_decode_impl(qbuf, kcache, vcache, positions, 1, att, aws, l.attn_bytes, B, c.Hq, c.Hkv, c.D,
                              c.Lmax, c.scale, s));
-    DET_TRY(det_gemm_bf16(att, nq, w->wo, proj, c.H, B, c.H, nq, DET_BF16, stream));
-    DET_TRY(det_residual_add(x_inout, proj, x_inout, (int64_t)B * c.H, stream));
+    DET_TRY(det_gemm_bf16_residual(att, nq, w->wo, x_inout, c.H, x_inout, c.H, B, c.H, nq, stream));
     DET_TRY(det_rmsnorm(x_inout, w->w_norm2, h, B, c.H, c.eps, stream));
-    DET_TRY(det_gemm_bf16(h, c.H, w->wgu, gu, 2 * c.F, B, 2 * c.F, c.H, DET_BF16, stream));
-    DET_TRY(det_swiglu(gu, 2 * c.F, gu + c.F, 2 * c.F, mm, c.F, B, c.F, stream));
-    DET_TRY(det_gemm_bf16(mm, c.F, w->wdown, proj, c.H, B, c.H, c.F, DET_BF16, stream));
-    DET_TRY(det_residual_add(x_inout, proj, x_inout, (int64_t)B * c.H, stream));
+    DET_TRY(det_gemm_swiglu_bf16(h, c.H, w->wgu, mm, c.F, B, c.F, c.H, stream));
+    DET_TRY(det_gemm_bf16_residual(mm, c.F, w->wdown, x_inout, c.H, x_inout, c.H, B, c.H, c.F, stream));
 #undef DET_TRY
     return DET_OK;
 }

@@ -45,7 +45,7 @@ class DecodeModel:
         for lw in weights["layers"]:
             packed = dict(norm1=lw["norm1"].contiguous(), wqkv=api.pack_weight(lw["wqkv"]),
                           wo=api.pack_weight(lw["wo"]), norm2=lw["norm2"].contiguous(),
-                          wgu=api.pack_weight(lw["wgu"]), wdown=api.pack_weight(lw["wdown"]))
+                          wgu=api.pack_gate_up(lw["wgu"]), wdown=api.pack_weight(lw["wdown"]))
             struct = api.layer_weights(packed["norm1"], packed["wqkv"], packed["wo"], packed["norm2"],
                                        packed["wgu"], packed["wdown"])
             self.layers.append((packed, struct))

@@ -218,3 +218,47 @@ def test_error_codes(d):
     assert lib.det_gemm_bf16(A.data_ptr(), 64, Bp.data_ptr(), C.data_ptr(), 16, 0, 16, 64, 0, s) == 1
     assert lib.det_gemm_bf16(A.data_ptr(), 64, Bp.data_ptr(), C.data_ptr(), 16, 4, 16, 64, 7, s) == 1
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("M,K,N", [(1, 512, 4096), (19, 4096, 4096), (130, 1024, 28672), (64, 5632, 2048)])
+def test_fused_residual_epilogue_equals_unfused_bytes(d, orc, M, K, N):
+    """det_gemm_bf16_residual = det_gemm_bf16 then det_residual_add, byte for byte (and the oracle's
+    residual of the GPU's own GEMM output), also in place (C is R)."""
+    A = ds.normal_bf16(700 + M, (M, K))
+    W = ds.normal_bf16(701 + N, (K, N), 0.02)
+    R = ds.normal_bf16(702 + M, (M, N))
+    Wp = d.pack_weight(up_bf16(W))
+    Ad, Rd = up_bf16(A), up_bf16(R)
+    plain = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+    step(f"gemm residual epilogue M={M} K={K} N={N}")
+    d.det_gemm_bf16(Ad, Wp, plain, N, K)
+    unfused = torch.empty_like(plain)
+    d.det_residual_add(Rd, plain, unfused)
+    fused = torch.empty_like(plain)
+    d.det_gemm_bf16_residual(Ad, Wp, Rd, fused, N, K)
+    inplace = Rd.clone()
+    d.det_gemm_bf16_residual(Ad, Wp, inplace, inplace, N, K)
+    torch.cuda.synchronize()
+    assert torch.equal(fused.view(torch.int16), unfused.view(torch.int16))
+    assert torch.equal(inplace.view(torch.int16), unfused.view(torch.int16))
+    assert np.array_equal(down_bf16(fused), orc.residual(R, down_bf16(plain)))
+
+
+@pytest.mark.parametrize("M,K,F", [(1, 512, 2048), (33, 4096, 14336), (7, 2048, 5632), (200, 256, 1000 * 8)])
+def test_fused_swiglu_epilogue_equals_unfused_bytes(d, orc, M, K, F):
+    """det_gemm_swiglu_bf16 on the gate/up-interleaved packing = det_gemm_bf16 on the plain packing
+    then det_swiglu, byte for byte."""
+    A = ds.normal_bf16(710 + M, (M, K))
+    W = ds.normal_bf16(711 + F, (K, 2 * F), 0.03)
+    Ad, Wd = up_bf16(A), up_bf16(W)
+    gu = torch.empty((M, 2 * F), dtype=torch.bfloat16, device=DEV)
+    step(f"gemm swiglu epilogue M={M} K={K} F={F}")
+    d.det_gemm_bf16(Ad, d.pack_weight(Wd), gu, 2 * F, K)
+    unfused = torch.empty((M, F), dtype=torch.bfloat16, device=DEV)
+    d.det_swiglu(gu[:, :F], gu[:, F:], unfused)
+    fused = torch.empty((M, F), dtype=torch.bfloat16, device=DEV)
+    d.det_gemm_swiglu_bf16(Ad, d.pack_gate_up(Wd), fused, F, K)
+    torch.cuda.synchronize()
+    assert torch.equal(fused.view(torch.int16), unfused.view(torch.int16))
+    guh = down_bf16(gu)
+    assert np.array_equal(down_bf16(fused), orc.swiglu(np.ascontiguousarray(guh[:, :F]), np.ascontiguousarray(guh[:, F:])))
