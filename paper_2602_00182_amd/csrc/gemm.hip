@@ -4,7 +4,7 @@
 // no atomics).
 //
 // Shape of the kernel
-//   * A workgroup (4 wavefronts) owns BN = 16*CB output columns and up to 256 rows; grid.x = N/BN,
+//   * A workgroup (NW = 4 or 8 wavefronts) owns BN = 16*CB output columns and up to 256 rows; grid.x = N/BN,
 //     grid.y = ceil(M/256).  CB and the LDS ring size are functions of N alone, so the
 //     configuration never depends on M.
 //   * K is cut into 64-deep stages.  Operands travel as 1 KB blocks, each already in the operand
@@ -22,7 +22,7 @@
 //     store is one 8- or 16-byte write.  Rows of the operand are independent in the matrix core,
 //     so rows past M may hold anything: their lanes load nothing and their outputs are never
 //     stored.
-//   * 16-row blocks are dealt round-robin to the 4 waves (block rb -> wave rb % 4).
+//   * 16-row blocks are dealt round-robin to the waves (block rb -> wave rb % NW).
 //
 // K order: matrix-core step t (t = 0 .. K/32-1, ascending) takes k in [32t, 32t+32); inside a step
 // lane group g supplies k = 32t + 8g + e, e = 0..7.
@@ -48,6 +48,10 @@ int gemm_cols_per_block(int N)
 // LDS ring size in 1 KB blocks.  144 KB by default (one workgroup per compute unit).  When N
 // yields at least 1.5 workgroups per compute unit and CB is small, the ring is two stages of the
 // largest tile, so that two workgroups share a compute unit's 160 KB of LDS.
+// Wavefronts per workgroup: 4 for narrow tiles, 8 (two per SIMD, so that one can issue loads while
+// the other feeds the matrix core) for wide ones, which measured faster from 64 rows up.
+__host__ __device__ constexpr int gemm_waves(int cb) { return cb >= 4 ? 8 : 4; }
+
 constexpr int kRingBig = 144;
 __host__ __device__ constexpr int gemm_small_ring_blocks(int cb) { return 4 * (cb + 16); }
 bool gemm_small_ring(int N)
@@ -103,8 +107,8 @@ __device__ __forceinline__ float silu_mul(float gate, float up)
     return sg * up;
 }
 
-template <int CB, int RINGB, int EPI>
-__global__ __launch_bounds__(256) void gemm_kernel(const uint16_t* __restrict__ A, int lda,
+template <int CB, int RINGB, int EPI, int NW>
+__global__ __launch_bounds__(64 * NW) void gemm_kernel(const uint16_t* __restrict__ A, int lda,
                                                    const uint4* __restrict__ Bp, void* C, int ldc,
                                                    const uint16_t* R, int ldr, int M, int K, int out_f32)
 {
@@ -132,23 +136,23 @@ __global__ __launch_bounds__(256) void gemm_kernel(const uint16_t* __restrict__ 
     const uint32_t ring_addr = (uint32_t)(uintptr_t)(lds_char_t*)ring;
 
     // Row blocks of this wave: rb = wave + 4r, active while rb < RB.
-    const int nrb = RB > wave ? (RB - wave + 3) >> 2 : 0;
+    const int nrb = RB > wave ? (RB - wave + NW - 1) / NW : 0;
 
-    // Which waves issue loads: while fewer than 4 row blocks hold data, the waves without a row block
-    // (waves RB..3) do all the loading and the computing waves only compute; from 4 row blocks on,
+    // Which waves issue loads: while fewer than NW row blocks hold data, the waves without a row block
+    // (waves RB..NW-1) do all the loading and the computing waves only compute; from NW row blocks on,
     // every wave does both.  lrank < 0: this wave issues no loads.
-    const int nload = RB >= 4 ? 4 : 4 - RB;
-    const int lrank = RB >= 4 ? wave : wave - RB;
+    const int nload = RB >= NW ? NW : NW - RB;
+    const int lrank = RB >= NW ? wave : wave - RB;
 
     auto chunk_stages = [&](int c) { return c < nchunks ? min(SPC, nstages - c * SPC) : 0; };
     // Loads this wave issues for a chunk of s_cnt stages: weight blocks q = lrank, lrank+nload, ...
     // below s_cnt*2*CB, one load each; activation pairs pp = lrank, lrank+nload, ... below s_cnt*RB,
     // two loads each (a pair always has a live lane: row 16*rb exists for rb < RB).
-    // From 4 row blocks on (every wave loads and computes) the split is per stage instead: wave w
-    // takes the weight blocks f = w, w+4, ... below 2*CB of each stage and the pairs of its own row
+    // For narrow tiles, from NW row blocks on (every wave loads and computes) the split is per stage
+    // instead: wave w takes the weight blocks f = w, w+NW, ... below 2*CB of each stage and the pairs of its own row
     // blocks, and issues them between the matrix-core steps of the stage it is computing.
-    const bool interleaved = CB <= 3 && RB >= 4;  // wide tiles measured faster with burst issue
-    const int nbw = 2 * CB > wave ? (2 * CB - wave + 3) >> 2 : 0;  // weight blocks per stage, this wave
+    const bool interleaved = CB <= 3 && RB >= NW;  // wide tiles measured faster with burst issue
+    const int nbw = 2 * CB > wave ? (2 * CB - wave + NW - 1) / NW : 0;  // weight blocks per stage, this wave
     auto strided = [&](int n) { return n > lrank ? (n - lrank + nload - 1) / nload : 0; };
     auto loads_for = [&](int s_cnt) {
         if (interleaved) return s_cnt * (nbw + 2 * nrb);
@@ -167,12 +171,12 @@ __global__ __launch_bounds__(256) void gemm_kernel(const uint16_t* __restrict__ 
     // One stage's loads of this wave under the per-stage split (stage sl of a chunk starting at
     // global stage s0 whose slot starts at slot_addr and holds nw weight blocks).
     auto issue_weight = [&](int s0, int sl, int t, uint32_t slot_addr) {
-        const int f = wave + 4 * t;
+        const int f = wave + NW * t;
         if (f < 2 * CB)
             dma_block(wsrc + ((size_t)(s0 + sl) * (2 * CB) + f) * 64, slot_addr + (uint32_t)(sl * 2 * CB + f) * 1024u);
     };
     auto issue_pair = [&](int s0, int sl, int r, uint32_t slot_addr, int nw) {
-        const int rb = wave + 4 * r;
+        const int rb = wave + NW * r;
         if (16 * rb + lr < mrem) {  // lanes of rows past M load nothing: their LDS bytes are never used
             const uint16_t* src_a = asrc + (size_t)(16 * rb) * lda + ((s0 + sl) << 6);
             const uint32_t d = slot_addr + (uint32_t)nw * 1024u + (uint32_t)(sl * RB + rb) * 2048u;
@@ -259,15 +263,15 @@ __global__ __launch_bounds__(256) void gemm_kernel(const uint16_t* __restrict__ 
                 const uint4* ap = abuf + sl * nA * 64;
 #pragma unroll
                 for (int r = 0; r < NRB; ++r) {
-                    fr.xf[r][0] = __builtin_bit_cast(bf16x8, ap[(8 * r) * 64]);
-                    fr.xf[r][1] = __builtin_bit_cast(bf16x8, ap[(8 * r + 1) * 64]);
+                    fr.xf[r][0] = __builtin_bit_cast(bf16x8, ap[(2 * NW * r) * 64]);
+                    fr.xf[r][1] = __builtin_bit_cast(bf16x8, ap[(2 * NW * r + 1) * 64]);
                 }
                 __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the steps they feed
             };
             // Steps of stage sl.  In the interleaved regime the loads of stage sl of chunk cn go out
             // between the groups of steps (pairs after the i = 0 groups, weight blocks after the i = 1
             // groups), so that address generation overlaps the matrix-core pipe.
-            constexpr int NBW = (2 * CB + 3) / 4;  // most weight blocks per stage any wave takes
+            constexpr int NBW = (2 * CB + NW - 1) / NW;  // most weight blocks per stage any wave takes
             auto mfma_stage = [&](const Frags& fr, int sl) {
                 const bool ld = sl < sn_cnt;
 #pragma unroll
@@ -339,7 +343,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const uint16_t* __restrict__ 
         const int n0 = blockIdx.x * (16 * CB);
 #pragma unroll
         for (int r = 0; r < NRB; ++r) {
-            const int rowl = 16 * (wave + 4 * r) + lr;
+            const int rowl = 16 * (wave + NW * r) + lr;
             if (rowl < mrem) {
                 const size_t row = (size_t)(m0 + rowl);
 #pragma unroll
@@ -373,12 +377,20 @@ __global__ __launch_bounds__(256) void gemm_kernel(const uint16_t* __restrict__ 
             }
         }
     };
-    switch (nrb) {
-        case 0: run(std::integral_constant<int, 0>{}); break;
-        case 1: run(std::integral_constant<int, 1>{}); break;
-        case 2: run(std::integral_constant<int, 2>{}); break;
-        case 3: run(std::integral_constant<int, 3>{}); break;
-        default: run(std::integral_constant<int, 4>{}); break;
+    if constexpr (NW == 8) {
+        switch (nrb) {
+            case 0: run(std::integral_constant<int, 0>{}); break;
+            case 1: run(std::integral_constant<int, 1>{}); break;
+            default: run(std::integral_constant<int, 2>{}); break;
+        }
+    } else {
+        switch (nrb) {
+            case 0: run(std::integral_constant<int, 0>{}); break;
+            case 1: run(std::integral_constant<int, 1>{}); break;
+            case 2: run(std::integral_constant<int, 2>{}); break;
+            case 3: run(std::integral_constant<int, 3>{}); break;
+            default: run(std::integral_constant<int, 4>{}); break;
+        }
     }
 }
 
@@ -415,12 +427,12 @@ __global__ __launch_bounds__(256) void gemm_pack_kernel(const uint16_t* __restri
     }
 }
 
-template <int CB, int RINGB, int EPI>
+template <int CB, int RINGB, int EPI, int NW>
 static void launch_gemm(const void* A, int lda, const void* Bp, void* C, int ldc, const void* R, int ldr, int M,
                         int N, int K, int out_f32, hipStream_t s)
 {
     dim3 grid(N / (16 * CB), (M + 255) / 256);
-    hipLaunchKernelGGL((gemm_kernel<CB, RINGB, EPI>), grid, dim3(256), 0, s, static_cast<const uint16_t*>(A), lda,
+    hipLaunchKernelGGL((gemm_kernel<CB, RINGB, EPI, NW>), grid, dim3(64 * NW), 0, s, static_cast<const uint16_t*>(A), lda,
                        static_cast<const uint4*>(Bp), C, ldc, static_cast<const uint16_t*>(R), ldr, M, K,
                        out_f32);
 }
@@ -436,11 +448,11 @@ static int gemm_dispatch(const void* A, int lda, const void* Bp, void* C, int ld
     case CBV:                                                                                               \
         if constexpr (CBV <= 3) {                                                                           \
             if (small) {                                                                                    \
-                launch_gemm<CBV, gemm_small_ring_blocks(CBV), EPI>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s); \
+                launch_gemm<CBV, gemm_small_ring_blocks(CBV), EPI, gemm_waves(CBV)>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s); \
                 break;                                                                                      \
             }                                                                                               \
         }                                                                                                   \
-        launch_gemm<CBV, kRingBig, EPI>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s);                       \
+        launch_gemm<CBV, kRingBig, EPI, gemm_waves(CBV)>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s);                       \
         break;
     switch (cb) {
         DET_GEMM_CASE(1)
@@ -451,7 +463,7 @@ static int gemm_dispatch(const void* A, int lda, const void* Bp, void* C, int ld
         DET_GEMM_CASE(6)
         DET_GEMM_CASE(7)
         default:
-            launch_gemm<8, kRingBig, EPI>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s);
+            launch_gemm<8, kRingBig, EPI, gemm_waves(8)>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s);
             break;
     }
 #undef DET_GEMM_CASE
