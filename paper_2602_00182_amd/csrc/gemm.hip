@@ -35,13 +35,13 @@ namespace det {
 typedef __attribute__((address_space(3))) char lds_char_t;
 
 // Columns-per-workgroup factor: the largest CB in 1..8 that divides N/16 and still leaves at least
-// 240 workgroups across N (one per compute unit, roughly); 1 if there is none.
+// 192 workgroups across N (three quarters of the 256 compute units); 1 if there is none.
 int gemm_cols_per_block(int N)
 {
     const int nb = N / 16;
     int best = 1;
     for (int cb = 1; cb <= 8; ++cb)
-        if (nb % cb == 0 && nb / cb >= 240) best = cb;
+        if (nb % cb == 0 && nb / cb >= 192) best = cb;
     return best;
 }
 
