@@ -77,7 +77,8 @@ __device__ __forceinline__ void dma_block(const void* gsrc, uint32_t lds_addr)
         : "memory");
 }
 
-// Waits until at most n of this wave's loads are outstanding, then the workgroup barrier.
+// Waits until at most n of this wave's loads are outstanding (the counter holds 0..63; anything
+// above falls back to waiting for all of them), then the workgroup barrier.
 #define DET_WB(n) \
     case n: asm volatile("s_waitcnt vmcnt(" #n ")\n\ts_barrier" ::: "memory"); break;
 __device__ __forceinline__ void wait_loads_then_barrier(int n)
@@ -88,6 +89,9 @@ __device__ __forceinline__ void wait_loads_then_barrier(int n)
         DET_WB(17) DET_WB(18) DET_WB(19) DET_WB(20) DET_WB(21) DET_WB(22) DET_WB(23) DET_WB(24)
         DET_WB(25) DET_WB(26) DET_WB(27) DET_WB(28) DET_WB(29) DET_WB(30) DET_WB(31) DET_WB(32)
         DET_WB(33) DET_WB(34) DET_WB(35) DET_WB(36) DET_WB(37) DET_WB(38) DET_WB(39) DET_WB(40)
+        DET_WB(41) DET_WB(42) DET_WB(43) DET_WB(44) DET_WB(45) DET_WB(46) DET_WB(47) DET_WB(48)
+        DET_WB(49) DET_WB(50) DET_WB(51) DET_WB(52) DET_WB(53) DET_WB(54) DET_WB(55) DET_WB(56)
+        DET_WB(57) DET_WB(58) DET_WB(59) DET_WB(60) DET_WB(61) DET_WB(62) DET_WB(63)
         default: asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory"); break;
     }
 }
