@@ -568,3 +568,20 @@ def test_generator_host_and_torch_paths_agree():
     assert abs(f.mean()) < 0.01 and abs(f.std() - 1) < 0.01
     ids = ds.uniform_int(7, (10000,), 16, 512)
     assert ids.min() == 16 and ids.max() == 512
+
+
+# ------------------------------------------------------------------ stored digests of the oracle
+
+def test_oracle_matches_stored_digests(orc):
+    """tests/golden/oracle_golden.txt was written by a committed script that calls only the oracle;
+    the oracle must keep producing those bytes unless a commit says why they changed."""
+    import importlib.util
+    import os
+
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_oracle_golden", os.path.join(here, "make_oracle_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    stored = dict(line.split() for line in open(os.path.join(here, "oracle_golden.txt")) if not line.startswith("#"))
+    got = dict(mod.digests())
+    assert got == stored
