@@ -69,21 +69,69 @@ __device__ __forceinline__ void argmax_merge(float& bv, int& bi, float v, int i)
 
 template <bool F32>
 __global__ __launch_bounds__(256) void argmax_kernel(const void* __restrict__ logits,
-                                                     int32_t* __restrict__ idx, int V)
+                                                     int32_t* __restrict__ idx, int V, int vec)
 {
     __shared__ float sv[4];
     __shared__ int si[4];
     float bv = 0.0f;
     int bi = -1;  // -1: nothing but NaN seen so far
-    for (int j = threadIdx.x; j < V; j += 256) {
-        float v;
-        if (F32)
-            v = static_cast<const float*>(logits)[(size_t)blockIdx.x * V + j];
-        else
-            v = bf16_to_f32(static_cast<const uint16_t*>(logits)[(size_t)blockIdx.x * V + j]);
-        if (v == v && (bi < 0 || v > bv)) {  // ascending j: strict > keeps the lowest index
+    // A thread's elements are visited in ascending index, so "strictly greater" keeps the lowest
+    // index among its own; the merges below break the remaining ties by index.
+    auto visit = [&](float v, int j) {
+        if (v == v && (bi < 0 || v > bv)) {
             bv = v;
             bi = j;
+        }
+    };
+    if (F32 && vec) {
+        // 16-byte loads, four vectors in flight per thread
+        const float4* row = reinterpret_cast<const float4*>(static_cast<const float*>(logits) + (size_t)blockIdx.x * V);
+        const int nv = V >> 2;
+        for (int v0 = threadIdx.x; v0 < nv; v0 += 4 * 256) {
+            float4 x[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (v0 + u * 256 < nv) x[u] = row[v0 + u * 256];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int q = v0 + u * 256;
+                if (q < nv) {
+                    visit(x[u].x, 4 * q);
+                    visit(x[u].y, 4 * q + 1);
+                    visit(x[u].z, 4 * q + 2);
+                    visit(x[u].w, 4 * q + 3);
+                }
+            }
+        }
+    } else if (!F32 && vec) {
+        const uint4* row = reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(logits) + (size_t)blockIdx.x * V);
+        const int nv = V >> 3;
+        for (int v0 = threadIdx.x; v0 < nv; v0 += 4 * 256) {
+            uint4 x[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (v0 + u * 256 < nv) x[u] = row[v0 + u * 256];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int q = v0 + u * 256;
+                if (q < nv) {
+                    const uint32_t p[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        visit(bf16lo_to_f32(p[k]), 8 * q + 2 * k);
+                        visit(bf16hi_to_f32(p[k]), 8 * q + 2 * k + 1);
+                    }
+                }
+            }
+        }
+    } else {
+        for (int j = threadIdx.x; j < V; j += 256) {
+            float v;
+            if (F32)
+                v = static_cast<const float*>(logits)[(size_t)blockIdx.x * V + j];
+            else
+                v = bf16_to_f32(static_cast<const uint16_t*>(logits)[(size_t)blockIdx.x * V + j]);
+            visit(v, j);
         }
     }
 #pragma unroll
@@ -123,9 +171,11 @@ extern "C" int det_argmax(const void* logits, int32_t* idx, int B, int V, int dt
     if (!logits || !idx || B < 1 || V < 1) return DET_EINVAL;
     if (dtype != DET_BF16 && dtype != DET_F32) return DET_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    // 16-byte loads when every row starts on a 16-byte boundary, element loads otherwise
+    const int vec = aligned16(logits) && V % (dtype == DET_F32 ? 4 : 8) == 0;
     if (dtype == DET_F32)
-        hipLaunchKernelGGL(argmax_kernel<true>, dim3(B), dim3(256), 0, s, logits, idx, V);
+        hipLaunchKernelGGL(argmax_kernel<true>, dim3(B), dim3(256), 0, s, logits, idx, V, vec);
     else
-        hipLaunchKernelGGL(argmax_kernel<false>, dim3(B), dim3(256), 0, s, logits, idx, V);
+        hipLaunchKernelGGL(argmax_kernel<false>, dim3(B), dim3(256), 0, s, logits, idx, V, vec);
     return check_launch();
 }
