@@ -47,6 +47,8 @@ def lib():
         _lib.orc_tree256.restype = C.c_float
         _lib.orc_num_threads.restype = C.c_int
         _lib.orc_sumsq.restype = C.c_float
+        _lib.orc_sample_uniform.restype = C.c_float
+        _lib.orc_sample_uniform.argtypes = [C.c_uint64, C.c_int32, C.c_int32]
     return _lib
 
 
@@ -233,3 +235,18 @@ def decoder_layer(x, w, kcache, vcache, positions, cos_t, sin_t, cfg):
                             C.c_int(H), C.c_int(Hq), C.c_int(Hkv), C.c_int(D), C.c_int(F),
                             C.c_int(Lmax), C.c_float(cfg["eps"]), C.c_float(cfg["scale"]))
     return x
+
+
+def sample_uniform(seed: int, seq_id: int, step: int) -> np.float32:
+    return np.float32(lib().orc_sample_uniform(C.c_uint64(seed & (2 ** 64 - 1)), int(seq_id), int(step)))
+
+
+def sample(logits, temperature: float, top_k: int, top_p: float, seed: int, seq_ids, steps) -> np.ndarray:
+    """Seeded temperature / top-k / top-p sampling; logits [B,V] fp32 -> tokens [B] int32."""
+    x, seq_ids, steps = _f32(logits), _i32(seq_ids), _i32(steps)
+    B, V = x.shape
+    assert seq_ids.shape == (B,) and steps.shape == (B,) and top_k >= 1 and temperature > 0 and 0 < top_p <= 1
+    out = np.empty(B, dtype=np.int32)
+    lib().orc_sample(_p(x), C.c_int(B), C.c_int(V), C.c_float(temperature), C.c_int(top_k), C.c_float(top_p),
+                     C.c_uint64(seed & (2 ** 64 - 1)), _p(seq_ids), _p(steps), _p(out))
+    return out

@@ -11,7 +11,8 @@
  *      stated bound, never by bytes (the paper reports a 0 % bit match across architectures,
  *      section 6.7, Table 4).
  *   X  bit-exact references: an fp32 emulation, step by step, of the canonical reduction order
- *      (RMSNorm, softmax statistics, argmax, det_expf, bf16 rounding, RoPE, SwiGLU, residual).
+ *      (RMSNorm, softmax statistics, argmax, det_expf, bf16 rounding, RoPE, SwiGLU, residual,
+ *      seeded sampling).
  *
  * The canonical order follows the paper's three kernel invariants (section 6.5): a fixed mapping
  * of work to threads, a stride-halving binary-tree reduction (the four-line shuffle loop of
@@ -480,6 +481,79 @@ void orc_decoder_layer(uint16_t *x, const uint16_t *w_norm1, const uint16_t *wqk
 
     free(h); free(qkv); free(qr); free(kr); free(att); free(proj); free(gu); free(mm); free(ao);
     free(lens);
+}
+
+/* ---------------------------------------------------------------- seeded sampling (X) */
+
+/* Counter-based uniform in [0,1): the splitmix64 output function applied to
+ * seed + (((uint64)seq_id << 32 | (uint32)step) + 1) * 0x9E3779B97F4A7C15, top 24 bits scaled by 2^-24.
+ * A sample depends on (seed, sequence id, step) only, never on the batch (section 6.6: fixed-seed
+ * PRNG, reproducible per (seed, decode policy)). */
+static uint64_t mix64(uint64_t z)
+{
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+float orc_sample_uniform(uint64_t seed, int32_t seq_id, int32_t step)
+{
+    uint64_t ctr = ((uint64_t)(uint32_t)seq_id << 32) | (uint64_t)(uint32_t)step;
+    uint64_t r = mix64(seed + (ctr + 1) * 0x9E3779B97F4A7C15ull);
+    return (float)(r >> 40) * 0x1p-24f;
+}
+
+typedef struct { float z; int32_t idx; } zi_t;
+
+/* canonical order of candidates: larger z first; equal z: smaller index first */
+static int zi_cmp(const void *a, const void *b)
+{
+    const zi_t *x = (const zi_t *)a, *y = (const zi_t *)b;
+    if (x->z > y->z) return -1;
+    if (x->z < y->z) return 1;
+    return (x->idx > y->idx) - (x->idx < y->idx);
+}
+
+/* Temperature / top-k / top-p sampling in a canonical iteration order (section 6.6).
+ *   z_j = logits_j / T (fp32 divide; NaN counts as -inf);  candidates sorted by (z desc, index asc);
+ *   the first k = min(top_k, V) kept;  e_i = det_expf(z_i - z_0);  c_i = c_{i-1} + e_i in rank
+ *   order (sequential fp32 adds from +0);  n = the smallest i+1 with c_i >= top_p * c_{k-1};
+ *   target = u * c_{n-1};  the token is the candidate of the smallest rank i < n with
+ *   c_i > target (rank n-1 if rounding leaves none).
+ * logits [B,V] fp32; seq_ids, steps [B]; tokens [B]. */
+void orc_sample(const float *logits, int B, int V, float temperature, int top_k, float top_p,
+                uint64_t seed, const int32_t *seq_ids, const int32_t *steps, int32_t *tokens)
+{
+    for (int b = 0; b < B; ++b) {
+        zi_t *c = (zi_t *)malloc(sizeof(zi_t) * (size_t)V);
+        for (int j = 0; j < V; ++j) {
+            float z = logits[(int64_t)b * V + j] / temperature;
+            if (z != z) z = -INFINITY;
+            c[j].z = z;
+            c[j].idx = j;
+        }
+        qsort(c, (size_t)V, sizeof(zi_t), zi_cmp);
+        int k = top_k < V ? top_k : V;
+        float *cum = (float *)malloc(sizeof(float) * (size_t)k);
+        float acc = 0.0f;
+        for (int i = 0; i < k; ++i) {
+            float e = orc_expf(c[i].z - c[0].z);
+            acc = acc + e;
+            cum[i] = acc;
+        }
+        float cut = top_p * cum[k - 1];
+        int n = k;
+        for (int i = 0; i < k; ++i)
+            if (cum[i] >= cut) { n = i + 1; break; }
+        float u = orc_sample_uniform(seed, seq_ids[b], steps[b]);
+        float target = u * cum[n - 1];
+        int pick = n - 1;
+        for (int i = 0; i < n; ++i)
+            if (cum[i] > target) { pick = i; break; }
+        tokens[b] = c[pick].idx;
+        free(cum);
+        free(c);
+    }
 }
 
 /* Threads the parallel loops above will use (reported with the CPU baseline). */

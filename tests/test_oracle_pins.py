@@ -585,3 +585,60 @@ def test_oracle_matches_stored_digests(orc):
     stored = dict(line.split() for line in open(os.path.join(here, "oracle_golden.txt")) if not line.startswith("#"))
     got = dict(mod.digests())
     assert got == stored
+
+
+# ------------------------------------------------------------------ seeded sampling
+
+def test_sample_uniform_matches_independent_splitmix_and_is_uniform(orc):
+    """The counter-based uniform against the input generator's own numpy splitmix64 (written
+    separately from the same published algorithm), and its first two moments."""
+    seed = 0x1234_5678_9ABC_DEF0
+    for seq, step in [(0, 0), (5, 17), (63, 511), (2 ** 31 - 1, 2 ** 31 - 1)]:
+        ctr = (seq << 32) | step
+        h = ds._hash_np(seed, ctr, 1)[0]           # splitmix64 output number ctr for state seed
+        want = np.float32(int(h) >> 40) * np.float32(2.0 ** -24)
+        assert orc.sample_uniform(seed, seq, step) == want
+    u = np.array([orc.sample_uniform(7, s, t) for s in range(40) for t in range(500)], dtype=np.float64)
+    assert 0.0 <= u.min() and u.max() < 1.0
+    assert abs(u.mean() - 0.5) < 0.01 and abs(u.var() - 1 / 12) < 0.005
+
+
+def test_sample_closed_forms(orc):
+    V = 1000
+    rng = np.random.default_rng(8)
+    x = rng.standard_normal((32, V)).astype(np.float32)
+    ids = np.arange(32, dtype=np.int32)
+    st = np.full(32, 3, dtype=np.int32)
+    # top_k = 1 is greedy decoding, whatever the temperature, top_p or seed
+    for T, p, seed in [(1.0, 1.0, 1), (0.3, 0.5, 99), (5.0, 1e-6, 2 ** 63 + 5)]:
+        assert np.array_equal(orc.sample(x, T, 1, p, seed, ids, st), orc.argmax_f32(x))
+    # a tiny top_p keeps the first candidate only
+    assert np.array_equal(orc.sample(x, 1.0, 50, 1e-6, 4, ids, st), orc.argmax_f32(x))
+    # all logits equal, top_k = 4: only the four lowest indices can come out, about equally often
+    flat = np.zeros((4000, V), dtype=np.float32)
+    tok = orc.sample(flat, 1.0, 4, 1.0, 11, np.arange(4000, dtype=np.int32), np.zeros(4000, dtype=np.int32))
+    cnt = np.bincount(tok, minlength=V)
+    assert cnt[4:].sum() == 0 and np.all(np.abs(cnt[:4] - 1000) < 5 * np.sqrt(1000 * 0.75))
+    # two-point distribution: z = (0, -ln 2) -> probabilities (2/3, 1/3)
+    two = np.full((6000, V), -200.0, dtype=np.float32)
+    two[:, 10] = 0.0
+    two[:, 700] = -np.float32(np.log(2.0))
+    tok = orc.sample(two, 1.0, 40, 1.0, 5, np.arange(6000, dtype=np.int32), np.full(6000, 9, dtype=np.int32))
+    assert set(np.unique(tok)) == {10, 700}
+    assert abs((tok == 10).mean() - 2 / 3) < 5 * np.sqrt(2 / 9 / 6000)
+    # temperature 0.5 squares the odds: (4/5, 1/5)
+    tok = orc.sample(two, 0.5, 40, 1.0, 5, np.arange(6000, dtype=np.int32), np.full(6000, 9, dtype=np.int32))
+    assert abs((tok == 10).mean() - 0.8) < 5 * np.sqrt(0.16 / 6000)
+    # top_p: cumulative (2/3, 1) -> top_p = 0.6 keeps token 10 only, top_p = 0.7 keeps both
+    assert np.all(orc.sample(two, 1.0, 40, 0.6, 5, np.arange(6000, dtype=np.int32), np.full(6000, 9, dtype=np.int32)) == 10)
+    assert (orc.sample(two, 1.0, 40, 0.7, 5, np.arange(6000, dtype=np.int32), np.full(6000, 9, dtype=np.int32)) == 700).any()
+    # a sample depends on (seed, sequence id, step), not on the row slot or the batch
+    a = orc.sample(x, 0.9, 64, 0.95, 42, ids, st)
+    perm = rng.permutation(32)
+    assert np.array_equal(orc.sample(x[perm], 0.9, 64, 0.95, 42, ids[perm], st[perm]), a[perm])
+    assert np.array_equal(orc.sample(x[5:6], 0.9, 64, 0.95, 42, ids[5:6], st[5:6]), a[5:6])
+    assert not np.array_equal(orc.sample(x, 0.9, 64, 0.95, 43, ids, st), a)      # the seed matters
+    # NaN logits are never sampled
+    xn = x.copy()
+    xn[:, ::2] = np.nan
+    assert np.all(orc.sample(xn, 1.0, 64, 1.0, 1, ids, st) % 2 == 1)
