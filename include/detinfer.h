@@ -138,6 +138,21 @@ int det_softmax_f32(const float *s, const int32_t *lens, float *p, float *m_out,
  * NaNs gives 0.  logits [B, V] fp32 (DET_F32) or bf16 (DET_BF16); idx [B] int32. */
 int det_argmax(const void *logits, int32_t *idx, int B, int V, int dtype, void *stream);
 
+/* Seeded sampling (section 6.6: a fixed-seed PRNG and a canonical iteration order make the token a
+ * function of (seed, decode policy)).  Per row:
+ *   z_j = logits_j / temperature (NaN counts as -inf);  candidates ordered by (z descending, index
+ *   ascending);  the first k = min(top_k, V) kept;  e_i = det_expf(z_i - z_0);  c_i = c_{i-1} + e_i in
+ *   rank order (sequential fp32 adds from +0);  n = smallest i+1 with c_i >= top_p * c_{k-1};
+ *   u = (splitmix64 output for seed + ((seq_id << 32 | step) + 1) * 0x9E3779B97F4A7C15) >> 40, scaled by
+ *   2^-24;  target = u * c_{n-1};  token = candidate of the smallest rank i < n with c_i > target
+ *   (rank n-1 if none).  top_k = 1 is det_argmax.
+ * The sample depends on (seed, seq_ids[b], steps[b]) and row b's logits only, never on the batch.
+ *   logits [B, V] fp32; seq_ids, steps, tokens [B] int32.
+ *   temperature > 0, 0 < top_p <= 1 (DET_EINVAL otherwise); 1 <= top_k <= 1024 (DET_ESHAPE). */
+int det_sample(const float *logits, int B, int V, float temperature, int top_k, float top_p,
+               uint64_t seed, const int32_t *seq_ids, const int32_t *steps, int32_t *tokens,
+               void *stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Elementwise steps of the decoder layer, exported so each can be checked bit for bit.
  *

@@ -35,6 +35,7 @@ SIGNATURES = {
     "det_attn_decode": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _sz, _i, _i, _i, _i, _i, _f, _vp]),
     "det_softmax_f32": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _vp]),
     "det_argmax": (_i, [_vp, _vp, _i, _i, _i, _vp]),
+    "det_sample": (_i, [_vp, _i, _i, _f, _i, _f, C.c_uint64, _vp, _vp, _vp, _vp]),
     "det_rope": (_i, [_vp, _i, _vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),
     "det_swiglu": (_i, [_vp, _i, _vp, _i, _vp, _i, _i, _i, _vp]),
     "det_residual_add": (_i, [_vp, _vp, _vp, _i64, _vp]),

@@ -13,7 +13,7 @@ from ._lib import LayerCfg, LayerWeights, lib
 __all__ = [
     "DetError", "det_gemm_bf16", "det_gemm_packed_b_bytes", "det_gemm_pack_b", "det_gemm_bf16_residual",
     "det_gemm_pack_gate_up", "det_gemm_swiglu_bf16", "pack_gate_up", "det_rmsnorm",
-    "det_attn_decode_workspace_bytes", "det_attn_decode", "det_softmax_f32", "det_argmax", "det_rope",
+    "det_attn_decode_workspace_bytes", "det_attn_decode", "det_softmax_f32", "det_argmax", "det_sample", "det_rope",
     "det_swiglu", "det_residual_add", "det_embed_gather", "det_decoder_layer_workspace_bytes",
     "det_decoder_layer", "det_next_token", "det_fingerprint", "det_last_hip_error", "layer_cfg",
     "layer_weights", "pack_weight",
@@ -192,6 +192,18 @@ def det_argmax(logits: torch.Tensor, idx: torch.Tensor, stream=None) -> None:
     else:
         raise TypeError("logits must be fp32 or bf16")
     _check("det_argmax", lib().det_argmax(_contig(logits), _contig(idx, torch.int32), B, V, dt, _stream(stream)))
+
+
+def det_sample(logits, temperature: float, top_k: int, top_p: float, seed: int, seq_ids, steps, tokens,
+               stream=None) -> None:
+    B, V = logits.shape
+    for a in (seq_ids, steps, tokens):
+        if a.shape != (B,):
+            raise ValueError("bad sampling shapes")
+    _check("det_sample", lib().det_sample(_contig(logits, torch.float32), B, V, temperature, top_k, top_p,
+                                           seed & (2 ** 64 - 1), _contig(seq_ids, torch.int32),
+                                           _contig(steps, torch.int32), _contig(tokens, torch.int32),
+                                           _stream(stream)))
 
 
 def det_rope(x, y, pos, cos_t, sin_t, stream=None) -> None:

@@ -1,0 +1,167 @@
+// Seeded temperature / top-k / top-p sampling in a canonical iteration order (the paper's section
+// 6.6: a fixed-seed PRNG and a canonical order make the emitted token a function of (seed, decode
+// policy) alone).  One 256-thread workgroup per row.
+//
+//   z_j = logits_j / T (NaN counts as -inf, -0 as +0);  candidates ordered by (z descending, index
+//   ascending);  the first k = min(top_k, V) kept;  e_i = det_expf(z_i - z_0);  c_i = c_{i-1} + e_i
+//   in rank order, sequential fp32 adds from +0;  n = smallest i+1 with c_i >= top_p * c_{k-1};
+//   u = counter-based uniform of (seed, sequence id, step);  target = u * c_{n-1};  the token is the
+//   candidate of the smallest rank i < n with c_i > target (rank n-1 if rounding leaves none).
+//
+// The order is total (index breaks ties), so the k kept candidates and their ranks are unique and any
+// selection / sorting network gives them: here an 8-bit radix select on the 64-bit key
+// (order-preserving image of z, then ~index) with integer LDS histograms, and a bitonic sort of the
+// k survivors.  Every floating-point step is done by one thread in rank order.
+#include <math.h>
+
+#include "common.h"
+
+namespace det {
+
+constexpr int kMaxTopK = 1024;
+
+// Order-preserving map fp32 -> uint32 (larger float, larger key) and its inverse.
+__device__ __forceinline__ uint32_t order_key(float z)
+{
+    const uint32_t u = __float_as_uint(z);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float order_key_inv(uint32_t k)
+{
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
+}
+
+__device__ __forceinline__ uint64_t candidate_key(float logit, float temperature, int j)
+{
+    float z = logit / temperature;
+    if (z != z) z = -INFINITY;
+    if (z == 0.0f) z = 0.0f;  // -0 and +0 are the same candidate value
+    return ((uint64_t)order_key(z) << 32) | (uint64_t)(0xFFFFFFFFu - (uint32_t)j);
+}
+
+__device__ __forceinline__ uint64_t splitmix64_mix(uint64_t z)
+{
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+__global__ __launch_bounds__(256) void sample_kernel(const float* __restrict__ logits, int V, float temperature,
+                                                     int top_k, float top_p, uint64_t seed,
+                                                     const int32_t* __restrict__ seq_ids,
+                                                     const int32_t* __restrict__ steps,
+                                                     int32_t* __restrict__ tokens)
+{
+    __shared__ uint32_t hist[256];
+    __shared__ uint64_t sel[kMaxTopK];
+    __shared__ float ebuf[kMaxTopK];
+    __shared__ int s_digit, s_need, s_bin, s_count;
+
+    const int tid = threadIdx.x;
+    const float* row = logits + (size_t)blockIdx.x * V;
+    const int k = top_k < V ? top_k : V;
+
+    // ---- radix select: the k-th largest key, 8 bits per pass from the top
+    uint64_t prefix = 0;   // decided top bits of the k-th largest key
+    int need = k;          // rank still to be found among the keys that share the prefix
+    int shift = 56;
+    bool all_of_bin = false;
+    for (int pass = 0; pass < 8; ++pass, shift -= 8) {
+        hist[tid] = 0;
+        __syncthreads();
+        for (int j = tid; j < V; j += 256) {
+            const uint64_t key = candidate_key(row[j], temperature, j);
+            if (pass == 0 || (key >> (shift + 8)) == prefix) atomicAdd(&hist[(uint32_t)(key >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        uint32_t above = 0;  // keys with the prefix and a larger digit than tid
+        for (int b = tid + 1; b < 256; ++b) above += hist[b];
+        const uint32_t mine = hist[tid];
+        if ((int)above < need && need <= (int)(above + mine)) {
+            s_digit = tid;
+            s_need = need - (int)above;
+            s_bin = (int)mine;
+        }
+        __syncthreads();
+        prefix = (prefix << 8) | (uint64_t)s_digit;
+        need = s_need;
+        all_of_bin = s_bin == need;  // every key of this bin is wanted: no need to look at lower bits
+        __syncthreads();
+        if (all_of_bin) break;
+    }
+    const uint64_t threshold = all_of_bin ? (prefix << shift) : prefix;
+
+    // ---- gather the k survivors (any order), pad to a power of two, sort descending
+    if (tid == 0) s_count = 0;
+    __syncthreads();
+    for (int j = tid; j < V; j += 256) {
+        const uint64_t key = candidate_key(row[j], temperature, j);
+        if (key >= threshold) sel[atomicAdd(&s_count, 1)] = key;
+    }
+    int kp = 1;
+    while (kp < k) kp <<= 1;
+    __syncthreads();
+    for (int i = k + tid; i < kp; i += 256) sel[i] = 0;  // below every real key
+    __syncthreads();
+    for (int size = 2; size <= kp; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int i = tid; i < (kp >> 1); i += 256) {
+                const int lo = 2 * i - (i & (stride - 1));
+                const int hi = lo + stride;
+                const bool desc = (lo & size) == 0;
+                const uint64_t a = sel[lo], b = sel[hi];
+                if ((a < b) == desc) {
+                    sel[lo] = b;
+                    sel[hi] = a;
+                }
+            }
+            __syncthreads();
+        }
+    }
+
+    // ---- probabilities in rank order
+    const float z0 = order_key_inv((uint32_t)(sel[0] >> 32));
+    for (int i = tid; i < k; i += 256) ebuf[i] = det_expf(order_key_inv((uint32_t)(sel[i] >> 32)) - z0);
+    __syncthreads();
+    if (tid == 0) {
+        float acc = 0.0f;
+        for (int i = 0; i < k; ++i) {
+            acc = acc + ebuf[i];
+            ebuf[i] = acc;  // c_i
+        }
+        const float cut = top_p * ebuf[k - 1];
+        int n = k;
+        for (int i = 0; i < k; ++i)
+            if (ebuf[i] >= cut) {
+                n = i + 1;
+                break;
+            }
+        const uint64_t ctr = ((uint64_t)(uint32_t)seq_ids[blockIdx.x] << 32) | (uint64_t)(uint32_t)steps[blockIdx.x];
+        const uint64_t r = splitmix64_mix(seed + (ctr + 1) * 0x9E3779B97F4A7C15ull);
+        const float u = (float)(uint32_t)(r >> 40) * 0x1p-24f;
+        const float target = u * ebuf[n - 1];
+        int pick = n - 1;
+        for (int i = 0; i < n; ++i)
+            if (ebuf[i] > target) {
+                pick = i;
+                break;
+            }
+        tokens[blockIdx.x] = (int32_t)(0xFFFFFFFFu - (uint32_t)sel[pick]);
+    }
+}
+
+}  // namespace det
+
+using namespace det;
+
+extern "C" int det_sample(const float* logits, int B, int V, float temperature, int top_k, float top_p,
+                          uint64_t seed, const int32_t* seq_ids, const int32_t* steps, int32_t* tokens,
+                          void* stream)
+{
+    if (!logits || !seq_ids || !steps || !tokens || B < 1 || V < 1) return DET_EINVAL;
+    if (!(temperature > 0.0f) || !(top_p > 0.0f) || !(top_p <= 1.0f)) return DET_EINVAL;
+    if (top_k < 1 || top_k > kMaxTopK) return DET_ESHAPE;
+    hipLaunchKernelGGL(sample_kernel, dim3(B), dim3(256), 0, static_cast<hipStream_t>(stream), logits, V,
+                       temperature, top_k, top_p, seed, seq_ids, steps, tokens);
+    return check_launch();
+}

@@ -86,9 +86,23 @@ class DecodeState:
         api.det_gemm_bf16(self.xn, m.lm_head, self.logits, c.V, c.H, stream)
 
 
+@dataclass
+class SamplingPolicy:
+    """Seeded decode policy: det_sample with these parameters instead of det_argmax.  `seq_ids`
+    [B] int32 on the device names each sequence, so that its random stream does not depend on the
+    batch it runs in."""
+    temperature: float
+    top_k: int
+    top_p: float
+    seed: int
+    seq_ids: torch.Tensor
+
+
 def greedy_decode(model: DecodeModel, prompts: torch.Tensor, prompt_lens: torch.Tensor, n_new: int,
-                  rope_cos: torch.Tensor, rope_sin: torch.Tensor, keep_logits_at=(), stream=None):
+                  rope_cos: torch.Tensor, rope_sin: torch.Tensor, keep_logits_at=(), stream=None,
+                  policy: SamplingPolicy | None = None):
     """Runs B sequences together.  prompts [B, Tp] int32 (padded), prompt_lens [B] int32.
+    With `policy`, tokens are drawn by det_sample (step = position) instead of det_argmax.
 
     Returns (generated [B, n_new] int32 on the device, {step: logits [B, V] fp32 clone}).
     Step t feeds prompt token t while t < len, else the token sampled at step t-1; sequence b's
@@ -107,7 +121,11 @@ def greedy_decode(model: DecodeModel, prompts: torch.Tensor, prompt_lens: torch.
         last = sampled[t - 1] if t > 0 else sampled[0]
         api.det_next_token(prompts, prompt_lens, last, st.tokens, st.positions, history, t, stream)
         st.forward(stream)
-        api.det_argmax(st.logits, sampled[t], stream)
+        if policy is None:
+            api.det_argmax(st.logits, sampled[t], stream)
+        else:
+            api.det_sample(st.logits, policy.temperature, policy.top_k, policy.top_p, policy.seed, policy.seq_ids,
+                           st.positions, sampled[t], stream)
         if t in keep_logits_at:
             kept[t] = st.logits.clone()
     idx = (lens_host.to(torch.int64) - 1)[:, None] + torch.arange(n_new)[None, :]

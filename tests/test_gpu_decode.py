@@ -81,3 +81,35 @@ def test_token_streams_identical_across_batchings(model, prompts):
         assert np.array_equal(alone[0], full[i]), f"prompt {i}: alone differs from batched"
         for t, lg in alone_logits.items():
             assert np.array_equal(lg[0].view(np.uint32), full_logits[t][i].view(np.uint32))
+
+
+def test_seeded_sampling_streams_identical_across_batchings(model, prompts):
+    """Seeded top-k / top-p decoding (section 6.6): for a fixed (seed, policy) a prompt's token stream
+    is the same alone and in any batch, and changes with the seed."""
+    from paper_2602_00182_amd.decode import SamplingPolicy, greedy_decode
+
+    toks, lens = prompts
+    n_new = 48
+    cos_t, sin_t = ds.rope_tables(512 + n_new, D, 5.0e5)
+    cos_d, sin_d = up(cos_t), up(sin_t)
+
+    def run(ids, seed=2026):
+        ids = list(ids)
+        pol = SamplingPolicy(0.8, 50, 0.95, seed, up(np.asarray(ids, dtype=np.int32)))
+        gen, _ = greedy_decode(model, up(toks[ids]), up(lens[ids]), n_new, cos_d, sin_d, policy=pol)
+        torch.cuda.synchronize()
+        return gen.cpu().numpy()
+
+    step("sampled decode, 16 prompts in one batch")
+    full = run(range(16))
+    step("sampled decode, same batch again")
+    assert np.array_equal(run(range(16)), full)
+    step("sampled decode, batch of 4")
+    assert np.array_equal(run(range(8, 12)), full[8:12])
+    step("sampled decode, prompt 5 alone")
+    assert np.array_equal(run([5])[0], full[5])
+    step("sampled decode, another seed")
+    other = run(range(16), seed=2027)
+    assert not np.array_equal(other, full)
+    greedy, _ = greedy_decode(model, up(toks[:16]), up(lens[:16]), n_new, cos_d, sin_d)
+    assert not np.array_equal(greedy.cpu().numpy(), full)

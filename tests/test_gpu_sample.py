@@ -1,0 +1,83 @@
+"""det_sample: seeded temperature / top-k / top-p sampling must give the oracle's tokens exactly."""
+import numpy as np
+import pytest
+import torch
+
+import detsynth as ds
+from gpu_util import DEV, step, up
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def d():
+    import paper_2602_00182_amd as d
+    return d
+
+
+def run(d, x, T, k, p, seed, ids, steps):
+    tok = torch.full((x.shape[0],), -1, dtype=torch.int32, device=DEV)
+    d.det_sample(up(x), T, k, p, seed, up(np.asarray(ids, dtype=np.int32)), up(np.asarray(steps, dtype=np.int32)), tok)
+    torch.cuda.synchronize()
+    return tok.cpu().numpy()
+
+
+@pytest.mark.parametrize("V,T,k,p", [
+    (32000, 1.0, 40, 0.95), (32000, 0.7, 1, 1.0), (32000, 1.3, 1024, 1.0), (32000, 0.05, 64, 0.5),
+    (32000, 8.0, 500, 0.999), (1000, 1.0, 1024, 0.9), (7, 1.0, 5, 1.0), (1, 1.0, 3, 1.0), (257, 2.0, 256, 0.3),
+])
+def test_sample_matches_oracle(d, orc, V, T, k, p):
+    B = 64
+    x = (ds.bf16_bits_to_f32(ds.normal_bf16(800 + V + k, (B, V))) * np.float32(2.5)).astype(np.float32)
+    x += np.float32(1e-4) * np.arange(V, dtype=np.float32)[None, :] / max(V, 1)   # fp32, not only bf16 values
+    ids = ds.uniform_int(801, (B,), 0, 2 ** 31 - 1)
+    steps = ds.uniform_int(802, (B,), 0, 4096)
+    step(f"sample V={V} T={T} k={k} p={p}")
+    got = run(d, x, T, k, p, 0xDEADBEEFCAFEF00D, ids, steps)
+    want = orc.sample(x, T, k, p, 0xDEADBEEFCAFEF00D, ids, steps)
+    assert np.array_equal(got, want)
+
+
+def test_sample_ties_nan_and_batch_invariance(d, orc):
+    V, B = 32000, 48
+    x = ds.bf16_bits_to_f32(ds.normal_bf16(810, (B, V))).copy()     # bf16-valued logits tie often
+    x[0, :] = 0.0                      # all equal: the k lowest indices are the candidates
+    x[1, :] = -np.inf
+    x[1, [5, 9000]] = 0.0
+    x[2, ::2] = np.nan                 # NaN never sampled
+    x[3, :] = -0.0
+    x[3, 100] = 0.0                    # -0 and +0 are one value: index order decides
+    x[4, :] = np.nan                   # nothing but NaN
+    ids = np.arange(B, dtype=np.int32) * 7
+    steps = np.arange(B, dtype=np.int32) + 3
+    step("sample ties / NaN / inf")
+    got = run(d, x, 1.0, 50, 0.9, 123, ids, steps)
+    want = orc.sample(x, 1.0, 50, 0.9, 123, ids, steps)
+    assert np.array_equal(got, want)
+    assert got[0] < 50 and got[1] in (5, 9000) and got[2] % 2 == 1
+    step("sample: row alone, rows permuted, many (sequence, step) pairs")
+    perm = np.random.default_rng(4).permutation(B)
+    assert np.array_equal(run(d, x[perm], 1.0, 50, 0.9, 123, ids[perm], steps[perm]), got[perm])
+    assert np.array_equal(run(d, x[7:8], 1.0, 50, 0.9, 123, ids[7:8], steps[7:8]), got[7:8])
+    for rep in range(5):
+        assert np.array_equal(run(d, x, 1.0, 50, 0.9, 123, ids, steps), got)
+    flat = np.zeros((4096, 64), dtype=np.float32)
+    tok = run(d, flat, 1.0, 4, 1.0, 11, np.arange(4096), np.zeros(4096))
+    assert np.array_equal(tok, orc.sample(flat, 1.0, 4, 1.0, 11, np.arange(4096), np.zeros(4096)))
+    cnt = np.bincount(tok, minlength=64)
+    assert cnt[4:].sum() == 0 and np.all(np.abs(cnt[:4] - 1024) < 5 * np.sqrt(1024 * 0.75))
+
+
+def test_sample_error_codes(d):
+    x = torch.zeros((2, 16), dtype=torch.float32, device=DEV)
+    i = torch.zeros(2, dtype=torch.int32, device=DEV)
+    lib = d.api.lib()
+    s = torch.cuda.current_stream().cuda_stream
+    args = lambda T, k, p: (x.data_ptr(), 2, 16, T, k, p, 1, i.data_ptr(), i.data_ptr(), i.data_ptr(), s)
+    assert lib.det_sample(*args(1.0, 4, 1.0)) == 0
+    assert lib.det_sample(*args(0.0, 4, 1.0)) == 1
+    assert lib.det_sample(*args(1.0, 4, 0.0)) == 1
+    assert lib.det_sample(*args(1.0, 4, 1.5)) == 1
+    assert lib.det_sample(*args(1.0, 0, 1.0)) == 2
+    assert lib.det_sample(*args(1.0, 1025, 1.0)) == 2
+    torch.cuda.synchronize()
