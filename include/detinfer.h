@@ -125,6 +125,14 @@ int det_attn_decode(const void *q, const void *kcache, const void *vcache, const
                     void *out, void *ws, size_t ws_bytes, int B, int Hq, int Hkv, int D, int Lmax,
                     float scale, void *stream);
 
+/* The same operation on R rows that name their cache slot: row r reads slot slots[r] of caches
+ * [S, Hkv, Lmax, D] with length seqlens[r].  Several rows may share a slot (the tokens of one prompt
+ * at lengths 1..T: batch-invariant prefill, since each row is exactly the single-token operation).
+ * 0 <= slots[r] < S is the caller's responsibility.  Workspace: det_attn_decode_workspace_bytes(R, ...). */
+int det_attn_decode_rows(const void *q, const void *kcache, const void *vcache, const int32_t *seqlens,
+                         const int32_t *slots, void *out, void *ws, size_t ws_bytes, int R, int Hq,
+                         int Hkv, int D, int Lmax, float scale, void *stream);
+
 /* Test hook: the softmax statistics of det_attn_decode on caller-provided fp32 scores, computed by
  * the same device code.  s, p [R, Lmax] fp32; lens [R]; m_out, l_out [R] fp32.
  * p_j = (w_c * e_j) / L for j < lens[r]; entries at or past lens[r] are not written.
@@ -217,6 +225,17 @@ size_t det_decoder_layer_workspace_bytes(const det_layer_cfg *cfg /* host */, in
 int det_decoder_layer(const det_layer_weights *w, const det_layer_cfg *cfg, void *x_inout,
                       void *kcache, void *vcache, const int32_t *positions, const float *rope_cos,
                       const float *rope_sin, void *ws, size_t ws_bytes, int B, void *stream);
+
+/* The layer on R rows that name their cache slot (caches [S, Hkv, Lmax, D]): row r is one token at
+ * position positions[r] of the sequence in slot slots[r].  All keys and values of the call are
+ * written before any row attends, so the T tokens of a prompt can go through in one call (rows at
+ * positions 0..T-1 of one slot): every row's bytes are those of feeding the tokens one call at a
+ * time.  No two rows may name the same (slot, position).  Workspace:
+ * det_decoder_layer_workspace_bytes(cfg, R). */
+int det_decoder_layer_rows(const det_layer_weights *w, const det_layer_cfg *cfg, void *x_inout,
+                           void *kcache, void *vcache, const int32_t *positions, const int32_t *slots,
+                           const float *rope_cos, const float *rope_sin, void *ws, size_t ws_bytes,
+                           int R, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Token bookkeeping of the greedy decode loop, on the device so a step needs no host round trip.

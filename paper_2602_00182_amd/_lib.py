@@ -33,6 +33,7 @@ SIGNATURES = {
     "det_rmsnorm": (_i, [_vp, _vp, _vp, _i, _i, _f, _vp]),
     "det_attn_decode_workspace_bytes": (_sz, [_i, _i, _i, _i]),
     "det_attn_decode": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _sz, _i, _i, _i, _i, _i, _f, _vp]),
+    "det_attn_decode_rows": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _i, _i, _i, _i, _i, _f, _vp]),
     "det_softmax_f32": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _vp]),
     "det_argmax": (_i, [_vp, _vp, _i, _i, _i, _vp]),
     "det_sample": (_i, [_vp, _i, _i, _f, _i, _f, C.c_uint64, _vp, _vp, _vp, _vp]),
@@ -43,6 +44,8 @@ SIGNATURES = {
     "det_decoder_layer_workspace_bytes": (_sz, [C.POINTER(LayerCfg), _i]),
     "det_decoder_layer": (_i, [C.POINTER(LayerWeights), C.POINTER(LayerCfg), _vp, _vp, _vp, _vp, _vp, _vp,
                                _vp, _sz, _i, _vp]),
+    "det_decoder_layer_rows": (_i, [C.POINTER(LayerWeights), C.POINTER(LayerCfg), _vp, _vp, _vp, _vp, _vp, _vp, _vp,
+                                    _vp, _sz, _i, _vp]),
     "det_next_token": (_i, [_vp, _i, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _vp]),
     "det_fingerprint": (C.c_char_p, []),
     "det_last_hip_error": (_i, []),

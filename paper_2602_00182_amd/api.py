@@ -13,7 +13,8 @@ from ._lib import LayerCfg, LayerWeights, lib
 __all__ = [
     "DetError", "det_gemm_bf16", "det_gemm_packed_b_bytes", "det_gemm_pack_b", "det_gemm_bf16_residual",
     "det_gemm_pack_gate_up", "det_gemm_swiglu_bf16", "pack_gate_up", "det_rmsnorm",
-    "det_attn_decode_workspace_bytes", "det_attn_decode", "det_softmax_f32", "det_argmax", "det_sample", "det_rope",
+    "det_attn_decode_workspace_bytes", "det_attn_decode", "det_attn_decode_rows", "det_decoder_layer_rows",
+    "det_softmax_f32", "det_argmax", "det_sample", "det_rope",
     "det_swiglu", "det_residual_add", "det_embed_gather", "det_decoder_layer_workspace_bytes",
     "det_decoder_layer", "det_next_token", "det_fingerprint", "det_last_hip_error", "layer_cfg",
     "layer_weights", "pack_weight",
@@ -172,6 +173,17 @@ def det_attn_decode(q, kcache, vcache, seqlens, out, ws, scale: float, stream=No
         ws.numel() * ws.element_size(), B, Hq, Hkv, D, Lmax, scale, _stream(stream)))
 
 
+def det_attn_decode_rows(q, kcache, vcache, seqlens, slots, out, ws, scale: float, stream=None) -> None:
+    R, Hq, D = q.shape
+    S, Hkv, Lmax, D2 = kcache.shape
+    if D2 != D or vcache.shape != kcache.shape or out.shape != q.shape or seqlens.shape != (R,) or slots.shape != (R,):
+        raise ValueError("bad attention shapes")
+    _check("det_attn_decode_rows", lib().det_attn_decode_rows(
+        _contig(q, torch.bfloat16), _contig(kcache, torch.bfloat16), _contig(vcache, torch.bfloat16),
+        _contig(seqlens, torch.int32), _contig(slots, torch.int32), _contig(out, torch.bfloat16), _contig(ws),
+        ws.numel() * ws.element_size(), R, Hq, Hkv, D, Lmax, scale, _stream(stream)))
+
+
 def det_softmax_f32(s, lens, p, m_out, l_out, stream=None) -> None:
     R, Lmax = s.shape
     if p.shape != s.shape or lens.shape != (R,) or m_out.shape != (R,) or l_out.shape != (R,):
@@ -270,6 +282,20 @@ def det_decoder_layer(w: LayerWeights, cfg: LayerCfg, x, kcache, vcache, positio
         C.byref(w), C.byref(cfg), _contig(x, torch.bfloat16), _contig(kcache, torch.bfloat16),
         _contig(vcache, torch.bfloat16), _contig(positions, torch.int32), _contig(rope_cos, torch.float32),
         _contig(rope_sin, torch.float32), _contig(ws), ws.numel() * ws.element_size(), B, _stream(stream)))
+
+
+def det_decoder_layer_rows(w: LayerWeights, cfg: LayerCfg, x, kcache, vcache, positions, slots, rope_cos, rope_sin,
+                           ws, stream=None) -> None:
+    R = x.shape[0]
+    if x.shape != (R, cfg.H) or kcache.shape[1:] != (cfg.Hkv, cfg.Lmax, cfg.D) or vcache.shape != kcache.shape:
+        raise ValueError("bad layer shapes")
+    if positions.shape != (R,) or slots.shape != (R,) or rope_cos.shape != (cfg.Lmax, cfg.D // 2):
+        raise ValueError("bad layer shapes")
+    _check("det_decoder_layer_rows", lib().det_decoder_layer_rows(
+        C.byref(w), C.byref(cfg), _contig(x, torch.bfloat16), _contig(kcache, torch.bfloat16),
+        _contig(vcache, torch.bfloat16), _contig(positions, torch.int32), _contig(slots, torch.int32),
+        _contig(rope_cos, torch.float32), _contig(rope_sin, torch.float32), _contig(ws),
+        ws.numel() * ws.element_size(), R, _stream(stream)))
 
 
 def det_next_token(prompts, prompt_lens, last_sampled, tokens_out, positions_out, history, t: int,

@@ -48,6 +48,7 @@ __global__ __launch_bounds__(256) void attn_chunk_kernel(const uint16_t* __restr
                                                          const uint16_t* __restrict__ kcache,
                                                          const uint16_t* __restrict__ vcache,
                                                          const int32_t* __restrict__ seqlens,
+                                                         const int32_t* __restrict__ slots,
                                                          float* __restrict__ ws_m, float* __restrict__ ws_l,
                                                          float* __restrict__ ws_o, int Hq, int Hkv, int Lmax,
                                                          int ncmax, float scale, int len_offset)
@@ -63,7 +64,8 @@ __global__ __launch_bounds__(256) void attn_chunk_kernel(const uint16_t* __restr
     if (t0 >= len) return;  // uniform over the workgroup
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 4, lr = lane & 15;
-    const size_t kv_base = ((size_t)b * Hkv + kvh) * (size_t)Lmax * kD;
+    const int slot = slots ? slots[b] : b;  // which cache slot this row reads
+    const size_t kv_base = ((size_t)slot * Hkv + kvh) * (size_t)Lmax * kD;
     const uint16_t* kp = kcache + kv_base;
     const uint16_t* vp = vcache + kv_base;
 
@@ -304,7 +306,7 @@ extern "C" size_t det_attn_decode_workspace_bytes(int B, int Hq, int D, int Lmax
 }
 
 int det::attn_decode_impl(const void* q, const void* kcache, const void* vcache, const int32_t* seqlens,
-                          int len_offset, void* out, void* ws, size_t ws_bytes, int B, int Hq, int Hkv, int D,
+                          const int32_t* slots, int len_offset, void* out, void* ws, size_t ws_bytes, int B, int Hq, int Hkv, int D,
                           int Lmax, float scale, hipStream_t s)
 {
     if (!q || !kcache || !vcache || !seqlens || !out || !ws || B < 1 || Hq < 1 || Hkv < 1 || Lmax < 1)
@@ -326,7 +328,7 @@ int det::attn_decode_impl(const void* q, const void* kcache, const void* vcache,
     const uint16_t* kk = static_cast<const uint16_t*>(kcache);
     const uint16_t* vv = static_cast<const uint16_t*>(vcache);
 #define DET_LAUNCH_ATTN(GG)                                                                            \
-    hipLaunchKernelGGL(attn_chunk_kernel<GG>, grid, dim3(256), 0, s, qq, kk, vv, seqlens, ws_m, ws_l, \
+    hipLaunchKernelGGL(attn_chunk_kernel<GG>, grid, dim3(256), 0, s, qq, kk, vv, seqlens, slots, ws_m, ws_l, \
                        ws_o, Hq, Hkv, Lmax, ncmax, scale, len_offset)
     switch (G) {
         case 1: DET_LAUNCH_ATTN(1); break;
@@ -346,7 +348,16 @@ extern "C" int det_attn_decode(const void* q, const void* kcache, const void* vc
                                void* out, void* ws, size_t ws_bytes, int B, int Hq, int Hkv, int D, int Lmax,
                                float scale, void* stream)
 {
-    return attn_decode_impl(q, kcache, vcache, seqlens, 0, out, ws, ws_bytes, B, Hq, Hkv, D, Lmax, scale,
+    return attn_decode_impl(q, kcache, vcache, seqlens, nullptr, 0, out, ws, ws_bytes, B, Hq, Hkv, D, Lmax, scale,
+                            static_cast<hipStream_t>(stream));
+}
+
+extern "C" int det_attn_decode_rows(const void* q, const void* kcache, const void* vcache, const int32_t* seqlens,
+                                    const int32_t* slots, void* out, void* ws, size_t ws_bytes, int R, int Hq, int Hkv,
+                                    int D, int Lmax, float scale, void* stream)
+{
+    if (!slots) return DET_EINVAL;
+    return attn_decode_impl(q, kcache, vcache, seqlens, slots, 0, out, ws, ws_bytes, R, Hq, Hkv, D, Lmax, scale,
                             static_cast<hipStream_t>(stream));
 }
 

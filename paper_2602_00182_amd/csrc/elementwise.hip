@@ -44,6 +44,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const uint16_t* __rest
                                                           uint16_t* __restrict__ kcache,
                                                           uint16_t* __restrict__ vcache,
                                                           const int32_t* __restrict__ pos,
+                                                          const int32_t* __restrict__ slots,
                                                           const float* __restrict__ cos_t,
                                                           const float* __restrict__ sin_t, int Hq, int Hkv,
                                                           int D, int Lmax)
@@ -51,6 +52,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const uint16_t* __rest
     const int b = blockIdx.x, half = D >> 1;
     int p = pos[b];
     p = p < 0 ? 0 : (p >= Lmax ? Lmax - 1 : p);
+    const int slot = slots ? slots[b] : b;  // cache slot the row's key and value go to
     const uint16_t* row = qkv + (size_t)b * (Hq + 2 * Hkv) * D;
     const float* cr = cos_t + (size_t)p * half;
     const float* sr = sin_t + (size_t)p * half;
@@ -62,12 +64,12 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const uint16_t* __rest
     for (int i = threadIdx.x; i < Hkv * half; i += 256) {
         const int h = i / half, k = i % half;
         const uint16_t* src = row + (size_t)(Hq + h) * D;
-        uint16_t* dst = kcache + (((size_t)b * Hkv + h) * Lmax + p) * D;
+        uint16_t* dst = kcache + (((size_t)slot * Hkv + h) * Lmax + p) * D;
         rope_pair(src[k], src[k + half], cr[k], sr[k], dst[k], dst[k + half]);
     }
     for (int i = threadIdx.x; i < Hkv * D; i += 256) {
         const int h = i / D, k = i % D;
-        vcache[(((size_t)b * Hkv + h) * Lmax + p) * D + k] = row[(size_t)(Hq + Hkv + h) * D + k];
+        vcache[(((size_t)slot * Hkv + h) * Lmax + p) * D + k] = row[(size_t)(Hq + Hkv + h) * D + k];
     }
 }
 
@@ -146,13 +148,14 @@ __global__ __launch_bounds__(256) void next_token_kernel(const int32_t* __restri
 using namespace det;
 
 int det::rope_append(const void* qkv, void* qbuf, void* kcache, void* vcache, const int32_t* positions,
+                     const int32_t* slots,
                      const float* cos_t, const float* sin_t, int B, int Hq, int Hkv, int D, int Lmax,
                      hipStream_t s)
 {
     if (D != 128) return DET_ESHAPE;
     hipLaunchKernelGGL(rope_append_kernel, dim3(B), dim3(256), 0, s, static_cast<const uint16_t*>(qkv),
                        static_cast<uint16_t*>(qbuf), static_cast<uint16_t*>(kcache),
-                       static_cast<uint16_t*>(vcache), positions, cos_t, sin_t, Hq, Hkv, D, Lmax);
+                       static_cast<uint16_t*>(vcache), positions, slots, cos_t, sin_t, Hq, Hkv, D, Lmax);
     return check_launch();
 }
 

@@ -7,13 +7,15 @@ namespace det {
 
 // det_attn_decode with the sequence length taken as seqlens[b] + len_offset (the decoder layer
 // passes its `positions` array with len_offset = 1: the new token sits at row positions[b]).
+// slots: cache slot of each row (nullptr: row b uses slot b).
 int attn_decode_impl(const void* q, const void* kcache, const void* vcache, const int32_t* seqlens,
-                     int len_offset, void* out, void* ws, size_t ws_bytes, int B, int Hq, int Hkv, int D,
+                     const int32_t* slots, int len_offset, void* out, void* ws, size_t ws_bytes, int B, int Hq, int Hkv, int D,
                      int Lmax, float scale, hipStream_t s);
 
 // Rotary embedding of the q and k heads of the fused projection, k and v written into the caches
 // at row positions[b].  qkv [B,(Hq+2Hkv)D]; qbuf [B,Hq*D]; caches [B,Hkv,Lmax,D].
 int rope_append(const void* qkv, void* qbuf, void* kcache, void* vcache, const int32_t* positions,
+                const int32_t* slots,
                 const float* cos_t, const float* sin_t, int B, int Hq, int Hkv, int D, int Lmax,
                 hipStream_t s);
 

@@ -47,9 +47,9 @@ extern "C" size_t det_decoder_layer_workspace_bytes(const det_layer_cfg* cfg, in
     return layer_ws(*cfg, B).total;
 }
 
-extern "C" int det_decoder_layer(const det_layer_weights* w, const det_layer_cfg* cfg, void* x_inout,
-                                 void* kcache, void* vcache, const int32_t* positions, const float* rope_cos,
-                                 const float* rope_sin, void* ws, size_t ws_bytes, int B, void* stream)
+static int decoder_layer_impl(const det_layer_weights* w, const det_layer_cfg* cfg, void* x_inout, void* kcache,
+                              void* vcache, const int32_t* positions, const int32_t* slots, const float* rope_cos,
+                              const float* rope_sin, void* ws, size_t ws_bytes, int B, void* stream)
 {
     if (!w || !cfg || !x_inout || !kcache || !vcache || !positions || !rope_cos || !rope_sin || !ws || B < 1)
         return DET_EINVAL;
@@ -77,9 +77,9 @@ extern "C" int det_decoder_layer(const det_layer_weights* w, const det_layer_cfg
     } while (0)
     DET_TRY(det_rmsnorm(x_inout, w->w_norm1, h, B, c.H, c.eps, stream));
     DET_TRY(det_gemm_bf16(h, c.H, w->wqkv, qkv, nqkv, B, nqkv, c.H, DET_BF16, stream));
-    DET_TRY(rope_append(qkv, qbuf, kcache, vcache, positions, rope_cos, rope_sin, B, c.Hq, c.Hkv, c.D, c.Lmax,
+    DET_TRY(rope_append(qkv, qbuf, kcache, vcache, positions, slots, rope_cos, rope_sin, B, c.Hq, c.Hkv, c.D, c.Lmax,
                         s));
-    DET_TRY(attn_decode_impl(qbuf, kcache, vcache, positions, 1, att, aws, l.attn_bytes, B, c.Hq, c.Hkv, c.D,
+    DET_TRY(attn_decode_impl(qbuf, kcache, vcache, positions, slots, 1, att, aws, l.attn_bytes, B, c.Hq, c.Hkv, c.D,
                              c.Lmax, c.scale, s));
     DET_TRY(det_gemm_bf16_residual(att, nq, w->wo, x_inout, c.H, x_inout, c.H, B, c.H, nq, stream));
     DET_TRY(det_rmsnorm(x_inout, w->w_norm2, h, B, c.H, c.eps, stream));
@@ -87,4 +87,22 @@ extern "C" int det_decoder_layer(const det_layer_weights* w, const det_layer_cfg
     DET_TRY(det_gemm_bf16_residual(mm, c.F, w->wdown, x_inout, c.H, x_inout, c.H, B, c.H, c.F, stream));
 #undef DET_TRY
     return DET_OK;
+}
+
+extern "C" int det_decoder_layer(const det_layer_weights* w, const det_layer_cfg* cfg, void* x_inout,
+                                 void* kcache, void* vcache, const int32_t* positions, const float* rope_cos,
+                                 const float* rope_sin, void* ws, size_t ws_bytes, int B, void* stream)
+{
+    return decoder_layer_impl(w, cfg, x_inout, kcache, vcache, positions, nullptr, rope_cos, rope_sin, ws, ws_bytes, B,
+                              stream);
+}
+
+extern "C" int det_decoder_layer_rows(const det_layer_weights* w, const det_layer_cfg* cfg, void* x_inout,
+                                      void* kcache, void* vcache, const int32_t* positions, const int32_t* slots,
+                                      const float* rope_cos, const float* rope_sin, void* ws, size_t ws_bytes,
+                                      int R, void* stream)
+{
+    if (!slots) return DET_EINVAL;
+    return decoder_layer_impl(w, cfg, x_inout, kcache, vcache, positions, slots, rope_cos, rope_sin, ws, ws_bytes, R,
+                              stream);
 }

@@ -4,10 +4,13 @@ kernels, on one stream, with no host round trip inside the loop).
 One step, for B sequences at step t (the paper's section 6.6: greedy decoding in a fixed order):
     token select -> embedding gather -> L x decoder layer -> final RMSNorm -> lm_head GEMM (fp32
     logits) -> argmax.
-Prompts are fed through the same step one token at a time, so a sequence's bytes are those of the
-single-sequence run whatever batch it sits in."""
+greedy_decode feeds prompts through the same step one token at a time; prefill_decode pushes all
+prompt tokens of all sequences through each layer in one call (rows that name their cache slot) and
+then decodes.  Either way a sequence's bytes are those of the single-sequence, token-by-token run,
+whatever batch it sits in."""
 from __future__ import annotations
 
+import contextlib
 from dataclasses import dataclass
 
 import torch
@@ -131,3 +134,74 @@ def greedy_decode(model: DecodeModel, prompts: torch.Tensor, prompt_lens: torch.
     idx = (lens_host.to(torch.int64) - 1)[:, None] + torch.arange(n_new)[None, :]
     gen = sampled.t().contiguous().gather(1, idx.to(dev))
     return gen, kept
+
+
+def _select(policy, logits, positions, out, stream):
+    if policy is None:
+        api.det_argmax(logits, out, stream)
+    else:
+        api.det_sample(logits, policy.temperature, policy.top_k, policy.top_p, policy.seed, policy.seq_ids,
+                       positions, out, stream)
+
+
+def prefill_decode(model: DecodeModel, prompts: torch.Tensor, prompt_lens: torch.Tensor, n_new: int,
+                   rope_cos: torch.Tensor, rope_sin: torch.Tensor, stream=None,
+                   policy: SamplingPolicy | None = None, keep_logits: bool = False):
+    """Same results as greedy_decode, with the prompts processed in one pass.
+
+    Prefill: row r is token prompts[b, p] with position p and cache slot b, for every b and p < len_b
+    (R = sum of the lengths).  Each layer writes all keys and values first and then lets row r attend
+    to positions 0..p of its slot, which is exactly what the token-by-token run computes for that
+    token.  The last row of each sequence goes on to the final norm, lm_head and token selection.
+    Decode: sequence b then advances from its own position len_b, one token per step.
+
+    Returns (generated [B, n_new] int32 on the device, list of n_new logits clones [B, V] if
+    keep_logits else [])."""
+    with torch.cuda.stream(stream) if stream is not None else contextlib.nullcontext():
+        return _prefill_decode(model, prompts, prompt_lens, n_new, rope_cos, rope_sin, stream, policy, keep_logits)
+
+
+def _prefill_decode(model, prompts, prompt_lens, n_new, rope_cos, rope_sin, stream, policy, keep_logits):
+    c = model.cfg
+    B, _ = prompts.shape
+    dev = prompts.device
+    lens_host = prompt_lens.cpu().to(torch.int64)
+    T = int(lens_host.max()) + n_new - 1
+    if rope_cos.shape[0] < T:
+        raise ValueError("rope tables shorter than the run")
+    st = model.new_state(B, T, rope_cos[:T].contiguous(), rope_sin[:T].contiguous())
+
+    # row tables, built on the host once (integer bookkeeping only)
+    slots_h = torch.repeat_interleave(torch.arange(B), lens_host)
+    starts = torch.cumsum(lens_host, 0) - lens_host
+    pos_h = torch.arange(int(lens_host.sum())) - torch.repeat_interleave(starts, lens_host)
+    R = int(lens_host.sum())
+    row_tokens = prompts.cpu()[slots_h, pos_h].to(torch.int32).to(dev)
+    row_slots = slots_h.to(torch.int32).to(dev)
+    row_pos = pos_h.to(torch.int32).to(dev)
+    last_rows = (starts + lens_host - 1).to(torch.int32).to(dev)
+
+    xr = torch.empty((R, c.H), dtype=torch.bfloat16, device=dev)
+    ws = torch.empty(api.det_decoder_layer_workspace_bytes(st.lcfg, R), dtype=torch.uint8, device=dev)
+    api.det_embed_gather(model.embed, row_tokens, xr, stream)
+    for i, (_, struct) in enumerate(model.layers):
+        api.det_decoder_layer_rows(struct, st.lcfg, xr, st.kcache[i], st.vcache[i], row_pos, row_slots,
+                                   st.rope_cos, st.rope_sin, ws, stream)
+    api.det_embed_gather(xr, last_rows, st.x, stream)  # row gather: the last token of each sequence
+    api.det_rmsnorm(st.x, model.final_norm, st.xn, c.eps, stream)
+    api.det_gemm_bf16(st.xn, model.lm_head, st.logits, c.V, c.H, stream)
+
+    gen = torch.zeros((n_new, B), dtype=torch.int32, device=dev)
+    kept = []
+    st.positions.copy_((lens_host - 1).to(torch.int32))
+    _select(policy, st.logits, st.positions, gen[0], stream)
+    if keep_logits:
+        kept.append(st.logits.clone())
+    for j in range(1, n_new):
+        st.tokens.copy_(gen[j - 1])
+        st.positions.add_(1)
+        st.forward(stream)
+        _select(policy, st.logits, st.positions, gen[j], stream)
+        if keep_logits:
+            kept.append(st.logits.clone())
+    return gen.t().contiguous(), kept

@@ -153,3 +153,39 @@ def test_full_size_batch64_context32768_sampled(d, orc):
         vh = ds.normal_bf16_slice(sv, (b * Hkv + g) * per_head, per_head).reshape(1, 1, Lmax, D)
         ref, refabs = orc.attn_decode_f64(qh, kh, vh, lens_h[b:b + 1], SCALE)
         assert within_bound(bits_to_f64(got[b, h]), ref[0, 0], refabs[0, 0]).all(), (b, h)
+
+
+def test_rows_variant_slots(d, orc):
+    """det_attn_decode_rows: identity slots give the bytes of det_attn_decode; a permuted slot table
+    gives the permuted rows; rows that share one slot at lengths 1..R (the tokens of a prompt) each
+    equal the single-row call on that slot at that length."""
+    S, Hq, Hkv, Lmax = 6, 32, 8, 700
+    q, k, v = inputs(560, S, Hq, Hkv, Lmax)
+    lens = np.asarray([700, 1, 256, 257, 511, 40], dtype=np.int32)
+    plain = run_attn(d, q, k, v, lens)
+
+    def rows(qr, slots, seqlens):
+        R = qr.shape[0]
+        ws = torch.empty(d.det_attn_decode_workspace_bytes(R, Hq, 128, Lmax), dtype=torch.uint8, device=DEV)
+        ws.fill_(0xFF)
+        out = torch.empty((R, Hq, 128), dtype=torch.bfloat16, device=DEV)
+        d.det_attn_decode_rows(up_bf16(qr), up_bf16(k), up_bf16(v), up(np.asarray(seqlens, dtype=np.int32)),
+                               up(np.asarray(slots, dtype=np.int32)), out, ws, SCALE)
+        torch.cuda.synchronize()
+        return down_bf16(out)
+
+    step("attention rows, identity slots")
+    assert np.array_equal(rows(q, np.arange(S), lens), plain)
+    step("attention rows, permuted slots")
+    perm = np.asarray([4, 0, 5, 2, 2, 1])
+    assert np.array_equal(rows(q[perm], perm, lens[perm]), plain[perm])
+    step("attention rows, 300 rows on one slot at lengths 1..300")
+    R = 300
+    qr = ds.normal_bf16(565, (R, Hq, 128))
+    got = rows(qr, np.full(R, 3), np.arange(1, R + 1))
+    for r in (0, 1, 127, 255, 256, 299):
+        q1 = np.repeat(qr[r:r + 1], S, axis=0)
+        one = run_attn(d, q1, k, v, np.full(S, r + 1, dtype=np.int32))
+        assert np.array_equal(got[r], one[3])
+    ref, refabs = orc.attn_decode_f64(qr[250:251], k[3:4], v[3:4], [251], SCALE)
+    assert within_bound(bits_to_f64(got[250:251]), ref, refabs).all()

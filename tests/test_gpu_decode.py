@@ -113,3 +113,35 @@ def test_seeded_sampling_streams_identical_across_batchings(model, prompts):
     assert not np.array_equal(other, full)
     greedy, _ = greedy_decode(model, up(toks[:16]), up(lens[:16]), n_new, cos_d, sin_d)
     assert not np.array_equal(greedy.cpu().numpy(), full)
+
+
+def test_prefill_rows_match_token_by_token(model, prompts):
+    """Batch-invariant prefill: all prompt tokens of a batch go through each layer in one call (rows
+    that name their cache slot) and the result is, byte for byte, that of feeding them one step at a
+    time: same generated tokens, same logits, same KV-cache contents."""
+    from paper_2602_00182_amd.decode import greedy_decode, prefill_decode
+
+    toks, lens = prompts
+    n_new = 24
+    cos_t, sin_t = ds.rope_tables(512 + n_new, D, 5.0e5)
+    cos_d, sin_d = up(cos_t), up(sin_t)
+    ids = list(range(8, 24))
+    lens_b = lens[ids]
+    keep = tuple(int(l) - 1 + j for l in lens_b for j in (0, 5, n_new - 1))
+    step("token-by-token decode of 16 prompts")
+    ref, ref_logits = greedy_decode(model, up(toks[ids]), up(lens_b), n_new, cos_d, sin_d, keep_logits_at=keep)
+    torch.cuda.synchronize()
+    step("prefill + decode of the same 16 prompts")
+    gen, logits = prefill_decode(model, up(toks[ids]), up(lens_b), n_new, cos_d, sin_d, keep_logits=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(gen.cpu().numpy(), ref.cpu().numpy())
+    for b, l in enumerate(lens_b):
+        for j in (0, 5, n_new - 1):
+            a = logits[j][b].cpu().numpy().view(np.uint32)
+            r = ref_logits[int(l) - 1 + j][b].cpu().numpy().view(np.uint32)
+            assert np.array_equal(a, r), f"logits differ: prompt {ids[b]}, generated token {j}"
+    step("prefill + decode, prompt 13 alone and a batch of 4")
+    alone, _ = prefill_decode(model, up(toks[[13]]), up(lens[[13]]), n_new, cos_d, sin_d)
+    assert np.array_equal(alone.cpu().numpy()[0], ref.cpu().numpy()[13 - 8])
+    four, _ = prefill_decode(model, up(toks[[20, 9, 13, 16]]), up(lens[[20, 9, 13, 16]]), n_new, cos_d, sin_d)
+    assert np.array_equal(four.cpu().numpy(), ref.cpu().numpy()[[12, 1, 5, 8]])

@@ -136,3 +136,40 @@ def test_layer_bytes_across_batch_compositions(d, layer, B):
         xr, kr, vr = run_layer(d, layer, ids, pos)
         assert torch.equal(xr.view(torch.int16), xb.view(torch.int16))
         assert torch.equal(kr.view(torch.int16), kb.view(torch.int16))
+
+
+def test_rows_variant_prefill_equals_steps(d, layer):
+    """det_decoder_layer_rows with T rows on one cache slot at positions 0..T-1 (a prompt in one call)
+    leaves the hidden rows and the cache bytes that T single-token det_decoder_layer calls leave; a
+    second slot processed in the same call does not change them."""
+    T = 40
+    s = ds.tensor_seed(4, 900)
+    xs = ds.normal_bf16_torch(s, (2, T, CFG["H"]), 1.0, 0.0, DEV)
+    shape = (1, CFG["Hkv"], CFG["Lmax"], CFG["D"])
+    step("layer, token by token, sequence 0")
+    kc = torch.zeros(shape, dtype=torch.bfloat16, device=DEV)
+    vc = torch.zeros_like(kc)
+    ws1 = torch.empty(d.det_decoder_layer_workspace_bytes(layer["cfg"], 1), dtype=torch.uint8, device=DEV)
+    want = []
+    for t in range(T):
+        x = xs[0, t:t + 1].clone()
+        d.det_decoder_layer(layer["struct"], layer["cfg"], x, kc, vc, up(np.asarray([t], dtype=np.int32)),
+                            layer["cos"], layer["sin"], ws1)
+        want.append(x)
+    want = torch.cat(want)
+    step("layer rows, two slots, 2 x 40 rows interleaved")
+    kc2 = torch.zeros((2,) + shape[1:], dtype=torch.bfloat16, device=DEV)
+    vc2 = torch.zeros_like(kc2)
+    order = np.random.default_rng(4).permutation(2 * T)      # row -> (slot, position), shuffled
+    slots = (order // T).astype(np.int32)
+    pos = (order % T).astype(np.int32)
+    x = xs.reshape(2 * T, -1)[torch.from_numpy(order).to(DEV)].contiguous()
+    ws = torch.empty(d.det_decoder_layer_workspace_bytes(layer["cfg"], 2 * T), dtype=torch.uint8, device=DEV)
+    ws.fill_(0xFF)
+    d.det_decoder_layer_rows(layer["struct"], layer["cfg"], x, kc2, vc2, up(pos), up(slots), layer["cos"],
+                             layer["sin"], ws)
+    torch.cuda.synchronize()
+    rows0 = np.argsort(order)[:T]                              # rows of slot 0 in position order
+    assert torch.equal(x[torch.from_numpy(rows0).to(DEV)], want)
+    assert torch.equal(kc2[0], kc[0]) and torch.equal(vc2[0], vc[0])
+    assert bool((kc2[1, :, :T] != 0).any()) and bool((kc2[1, :, T:] == 0).all())
