@@ -7,10 +7,12 @@
 //   * A workgroup (NW = 4 or 8 wavefronts) owns BN = 16*CB output columns and up to 256 rows; grid.x = N/BN,
 //     grid.y = ceil(M/256).  CB and the LDS ring size are functions of N alone, so the
 //     configuration never depends on M.
-//   * K is cut into 64-deep stages.  Operands travel as 1 KB blocks, each already in the operand
-//     order of v_mfma_f32_16x16x32_bf16 (lane l holds 8 consecutive k of row/column l%16, k group
-//     l/16): a stage has 2*CB weight blocks and 2*RB activation blocks, RB = number of 16-row
-//     blocks of the tile that hold data.  M decides RB and nothing else.
+//   * K is cut into 64-deep stages.  Operands travel as 1 KB blocks.  A weight block is already in
+//     the operand order of v_mfma_f32_16x16x32_bf16 (lane l holds 8 consecutive k of column l%16, k
+//     group l/16); an activation block is 8 rows x 64 k as they lie in A (whole 128-byte lines),
+//     swizzled in LDS so that the operand reads are conflict free.  A stage has 2*CB weight blocks
+//     and one activation block per 8 rows that hold data.  M decides the number of row blocks and
+//     which waves issue loads, nothing else.
 //   * Stages are grouped into chunks and streamed through a ring of up to 4 LDS slots with the
 //     LDS-DMA form of the global load (global_load_lds_dwordx4: no staging registers, one wave
 //     instruction fills one 1 KB block).  Up to 3 chunks are in flight while the waves compute on
@@ -51,6 +53,8 @@ int gemm_cols_per_block(int N)
 // Wavefronts per workgroup: 4 for narrow tiles, 8 (two per SIMD, so that one can issue loads while
 // the other feeds the matrix core) for wide ones, which measured faster from 64 rows up.
 __host__ __device__ constexpr int gemm_waves(int cb) { return cb >= 4 ? 8 : 4; }
+// Wavefronts that never compute and only issue loads (on top of those above): one per SIMD for wide tiles.
+__host__ __device__ constexpr int gemm_loader_waves(int cb, bool small_ring) { return small_ring ? 2 : 4; }
 
 constexpr int kRingBig = 144;
 __host__ __device__ constexpr int gemm_small_ring_blocks(int cb) { return 4 * (cb + 16); }
@@ -63,18 +67,50 @@ bool gemm_small_ring(int N)
 // One wave instruction: 64 lanes x 16 bytes from global memory straight into the 1 KB LDS block at
 // byte address lds_addr (wave-uniform); lane l lands at lds_addr + 16 l.  Written as assembly so
 // that the completion wait below can name a count instead of draining every load in flight.
-__device__ __forceinline__ void dma_block(const void* gsrc, uint32_t lds_addr)
+// The source is a wave-uniform base plus a 32-bit byte offset per lane, so that the per-lane part is
+// a constant of the kernel and every advance is scalar arithmetic.
+__device__ __forceinline__ void dma_block(const void* base, uint32_t lane_off, uint32_t lds_addr)
 {
     uint32_t saved_m0;
     asm volatile(
         "s_mov_b32 %0, m0\n\t"
         "s_mov_b32 m0, %1\n\t"
         "s_nop 0\n\t"
-        "global_load_lds_dwordx4 %2, off\n\t"
+        "global_load_lds_dwordx4 %2, %3\n\t"
         "s_mov_b32 m0, %0"
         : "=&s"(saved_m0)
-        : "s"(lds_addr), "v"(gsrc)
+        : "s"(lds_addr), "v"(lane_off), "s"(base)
         : "memory");
+}
+
+// A run of such loads with constant strides, three instructions a load: M0 is set once and then
+// advanced in place, and the source advances in the per-lane offset.  (Nothing else in this file
+// uses M0, and the compiler sets it itself before any instruction of its own that reads it.)
+__device__ __forceinline__ void dma_run_begin(uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" ::"s"(lds_addr) : "memory");
+}
+__device__ __forceinline__ void dma_run_next(const void* base, uint32_t& lane_off, uint32_t src_stride, uint32_t lds_stride)
+{
+    asm volatile(
+        "global_load_lds_dwordx4 %0, %1\n\t"
+        "s_add_u32 m0, m0, %3\n\t"
+        "v_add_u32 %0, %2, %0"
+        : "+v"(lane_off)
+        : "s"(base), "s"(src_stride), "s"(lds_stride)
+        : "memory", "scc");
+}
+__device__ __forceinline__ void dma_run(const void* base, uint32_t lane_off, uint32_t src_stride, uint32_t lds_addr,
+                                        uint32_t lds_stride, int n)
+{
+    dma_run_begin(lds_addr);
+    for (; n >= 4; n -= 4) {
+        dma_run_next(base, lane_off, src_stride, lds_stride);
+        dma_run_next(base, lane_off, src_stride, lds_stride);
+        dma_run_next(base, lane_off, src_stride, lds_stride);
+        dma_run_next(base, lane_off, src_stride, lds_stride);
+    }
+    for (; n > 0; --n) dma_run_next(base, lane_off, src_stride, lds_stride);
 }
 
 // Waits until at most n of this wave's loads are outstanding (the counter holds 0..63; anything
@@ -111,12 +147,48 @@ __device__ __forceinline__ float silu_mul(float gate, float up)
     return sg * up;
 }
 
-template <int CB, int RINGB, int EPI, int NW>
-__global__ __launch_bounds__(64 * NW) void gemm_kernel(const uint16_t* __restrict__ A, int lda,
-                                                   const uint4* __restrict__ Bp, void* C, int ldc,
-                                                   const uint16_t* R, int ldr, int M, int K, int out_f32)
+// Schedule of one 256-row tile: a function of the tile's row count, the kernel configuration and K,
+// worked out on the host (the kernel's own prologue is on the critical path of a launch that lasts
+// ten microseconds, and integer division is slow on the device).
+struct gemm_tile_plan {
+    int mrem;         // rows of the tile that hold data
+    int RB, HB;       // 16-row blocks and 8-row half blocks that hold data
+    int SPC;          // stages per chunk: three chunks fill the ring
+    int slot_blocks;  // 1 KB blocks per ring slot
+    int nslots;       // ring slots in use, 2..4
+    int nchunks;
+    int last_cnt;     // stages of the last chunk
+    int nload;        // waves that load
+    uint32_t inv_nload, inv_hb;  // floor(2^20/d)+1: n/d = (n * inv) >> 20, exact for the small n used here
+};
+
+static gemm_tile_plan make_tile_plan(int mrem, int cb, int ringb, int nw, int nl, int K)
+{
+    gemm_tile_plan t;
+    t.mrem = mrem;
+    t.RB = (mrem + 15) >> 4;
+    t.HB = (mrem + 7) >> 3;
+    const int nb = 2 * cb + 2 * t.RB;
+    t.SPC = (ringb / 3) / nb > 1 ? (ringb / 3) / nb : 1;
+    t.slot_blocks = t.SPC * nb;
+    t.nslots = ringb / t.slot_blocks < 4 ? ringb / t.slot_blocks : 4;
+    const int nstages = K >> 6;
+    t.nchunks = (nstages + t.SPC - 1) / t.SPC;
+    t.last_cnt = nstages - (t.nchunks - 1) * t.SPC;
+    t.nload = nw + nl - (t.RB < nw ? t.RB : nw);
+    t.inv_nload = (1u << 20) / (uint32_t)t.nload + 1u;
+    t.inv_hb = (1u << 20) / (uint32_t)t.HB + 1u;
+    return t;
+}
+
+template <int CB, int RINGB, int EPI, int NW, int NL>
+__global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __restrict__ A, int lda,
+                                                          const uint4* __restrict__ Bp, void* C, int ldc,
+                                                          const uint16_t* R, int ldr, int K, int out_f32,
+                                                          gemm_tile_plan plan_full, gemm_tile_plan plan_tail)
 {
     static_assert(RINGB >= 4 * (CB + 16), "the ring must hold two stages of the largest tile");
+    static_assert(NL >= 1, "a tile of NW row blocks or more needs waves that only load");
     __shared__ uint4 ring[RINGB * 64];
 
     const int tid = threadIdx.x;
@@ -125,196 +197,126 @@ __global__ __launch_bounds__(64 * NW) void gemm_kernel(const uint16_t* __restric
     const int g = lane >> 4;   // k group of the lane
     const int lr = lane & 15;  // row of A / column-in-block of the weights
     const int m0 = blockIdx.y * 256;
-    const int mrem = min(M - m0, 256);
-    const int RB = (mrem + 15) >> 4;                 // 16-row blocks holding data
-    const int nA = 2 * RB;                           // activation blocks per stage
-    const int nb = 2 * CB + nA;                      // 1 KB blocks per stage
-    const int SPC = max(1, (RINGB / 3) / nb);        // stages per chunk: three chunks fill the ring
-    const int slot_blocks = SPC * nb;                // blocks per ring slot
-    const int nslots = min(4, RINGB / slot_blocks);  // >= 2 by the static_assert
-    const int P = nslots - 1;                        // chunks in flight
+    const gemm_tile_plan& tp = blockIdx.y + 1 == gridDim.y ? plan_tail : plan_full;
+    const int mrem = tp.mrem;
+    const int RB = tp.RB;    // 16-row blocks holding data
+    const int HB = tp.HB;    // 8-row half blocks holding data (one load each per stage)
+    const int nA = 2 * RB;   // activation blocks per stage
+    const int SPC = tp.SPC;  // stages per chunk
+    const int slot_blocks = tp.slot_blocks;
+    const int nslots = tp.nslots;  // >= 2 by the static_assert
+    const int P = nslots - 1;      // chunks in flight
     const int nstages = K >> 6;
-    const int nchunks = (nstages + SPC - 1) / SPC;
-    const uint4* __restrict__ bsrc = Bp + (size_t)blockIdx.x * nstages * (2 * CB * 64);
-    const uint16_t* __restrict__ abase = A + (size_t)m0 * lda;
+    const int nchunks = tp.nchunks;
     const uint32_t ring_addr = (uint32_t)(uintptr_t)(lds_char_t*)ring;
+    auto chunk_stages = [&](int c) { return c < nchunks - 1 ? SPC : (c == nchunks - 1 ? tp.last_cnt : 0); };
 
-    // Row blocks of this wave: rb = wave + 4r, active while rb < RB.
-    const int nrb = RB > wave ? (RB - wave + NW - 1) / NW : 0;
-
-    // Which waves issue loads: while fewer than NW row blocks hold data, the waves without a row block
-    // (waves RB..NW-1) do all the loading and the computing waves only compute; from NW row blocks on,
-    // every wave does both.  lrank < 0: this wave issues no loads.
-    const int nload = RB >= NW ? NW : NW - RB;
-    const int lrank = RB >= NW ? wave : wave - RB;
-
-    auto chunk_stages = [&](int c) { return c < nchunks ? min(SPC, nstages - c * SPC) : 0; };
-    // Loads this wave issues for a chunk of s_cnt stages: weight blocks q = lrank, lrank+nload, ...
-    // below s_cnt*2*CB, one load each; activation pairs pp = lrank, lrank+nload, ... below s_cnt*RB,
-    // two loads each (a pair always has a live lane: row 16*rb exists for rb < RB).
-    // For narrow tiles, from NW row blocks on (every wave loads and computes) the split is per stage
-    // instead: wave w takes the weight blocks f = w, w+NW, ... below 2*CB of each stage and the pairs of its own row
-    // blocks, and issues them between the matrix-core steps of the stage it is computing.
-    const bool interleaved = CB <= 3 && RB >= NW;  // wide tiles measured faster with burst issue
-    const int nbw = 2 * CB > wave ? (2 * CB - wave + NW - 1) / NW : 0;  // weight blocks per stage, this wave
-    auto strided = [&](int n) { return n > lrank ? (n - lrank + nload - 1) / nload : 0; };
-    auto loads_for = [&](int s_cnt) {
-        if (interleaved) return s_cnt * (nbw + 2 * nrb);
-        return lrank < 0 ? 0 : strided(s_cnt * 2 * CB) + 2 * strided(s_cnt * RB);
-    };
-    // every chunk but the last has SPC stages, so two values cover all chunks
-    const int loads_full = loads_for(SPC);
-    const int loads_last = loads_for(nstages - (nchunks - 1) * SPC);
-    auto wave_loads = [&](int c) { return c < nchunks - 1 ? loads_full : (c == nchunks - 1 ? loads_last : 0); };
+    // Roles.  Row block rb belongs to wave rb % NW (waves 0 .. NW-1); a wave with a row block only
+    // computes, every other wave (waves min(RB,NW) .. NW+NL-1) only loads.  A load instruction blocks
+    // its wave until the address unit accepts it, so a wave that issued a chunk's loads could not feed
+    // the matrix core meanwhile, and one that computed first would leave the load queue empty
+    // meanwhile; with the roles in different waves the loads of a chunk go out the moment its ring slot
+    // is free and the compute units' memory pipe, which bounds tall tiles, never idles.
+    // One barrier per chunk in both roles: passing barrier c means chunk c has landed for everyone
+    // and everyone is done reading chunk c-1.
+    const int ncomp = min(RB, NW);
+    const int nrb = wave < ncomp ? (int)((unsigned)(RB - wave + NW - 1) / (unsigned)NW) : 0;
 
     // LDS layout of a chunk of s_cnt stages inside its slot: first the s_cnt*2*CB weight blocks in
-    // the order they lie in the packed matrix (stage, column block, step), then the s_cnt*2*RB
-    // activation blocks (stage, row block, step).
-    const uint4* wsrc = bsrc + lane;                          // this lane's slot in weight block 0
-    const uint16_t* asrc = abase + (size_t)lr * lda + 8 * g;  // row lr, k group g of stage 0
-    // One stage's loads of this wave under the per-stage split (stage sl of a chunk starting at
-    // global stage s0 whose slot starts at slot_addr and holds nw weight blocks).
-    auto issue_weight = [&](int s0, int sl, int t, uint32_t slot_addr) {
-        const int f = wave + NW * t;
-        if (f < 2 * CB)
-            dma_block(wsrc + ((size_t)(s0 + sl) * (2 * CB) + f) * 64, slot_addr + (uint32_t)(sl * 2 * CB + f) * 1024u);
-    };
-    auto issue_pair = [&](int s0, int sl, int r, uint32_t slot_addr, int nw) {
-        const int rb = wave + NW * r;
-        if (16 * rb + lr < mrem) {  // lanes of rows past M load nothing: their LDS bytes are never used
-            const uint16_t* src_a = asrc + (size_t)(16 * rb) * lda + ((s0 + sl) << 6);
-            const uint32_t d = slot_addr + (uint32_t)nw * 1024u + (uint32_t)(sl * RB + rb) * 2048u;
-            dma_block(src_a, d);
-            dma_block(src_a + 32, d + 1024u);
-        }
-    };
-    auto load_chunk = [&](int c, int slot_idx) {
-        const int s_cnt = chunk_stages(c);
-        if (s_cnt == 0 || lrank < 0) return;
-        const int s0 = c * SPC;
-        const int nw = s_cnt * 2 * CB;
-        const uint32_t slot_addr = ring_addr + (uint32_t)(slot_idx * slot_blocks) * 1024u;
-        if (interleaved) {  // burst form of the per-stage split (used to prime the ring)
-            for (int sl = 0; sl < s_cnt; ++sl) {
-                for (int t = 0; t < nbw; ++t) issue_weight(s0, sl, t, slot_addr);
-                for (int r = 0; r < nrb; ++r) issue_pair(s0, sl, r, slot_addr, nw);
-            }
-            return;
-        }
-        const uint4* src = wsrc + ((size_t)s0 * (2 * CB) + lrank) * 64;
-        uint32_t dst = slot_addr + (uint32_t)lrank * 1024u;
-        for (int q = lrank; q < nw; q += nload) {
-            dma_block(src, dst);
-            src += nload * 64;
-            dst += (uint32_t)nload * 1024u;
-        }
-        // activation blocks in pairs (both steps of one row block), pair pp = sl*RB + rb, so that the
-        // two 64-byte halves of each 128-byte line of A are fetched back to back
-        uint32_t adst = slot_addr + (uint32_t)nw * 1024u + (uint32_t)lrank * 2048u;
-        int sl = 0, rb = lrank;
-        while (rb >= RB) {
-            rb -= RB;
-            ++sl;
-        }
-        const int npair = s_cnt * RB;
-        for (int pp = lrank; pp < npair; pp += nload) {
-            if (16 * rb + lr < mrem) {  // lanes of rows past M load nothing: their LDS bytes are never used
-                const uint16_t* src_a = asrc + (size_t)(16 * rb) * lda + ((s0 + sl) << 6);
-                dma_block(src_a, adst);
-                dma_block(src_a + 32, adst + 1024u);
-            }
-            adst += (uint32_t)nload * 2048u;
-            rb += nload;
-            while (rb >= RB) {
-                rb -= RB;
-                ++sl;
-            }
-        }
-    };
+    // the order they lie in the packed matrix (stage, column block, step), then s_cnt*RB activation
+    // tiles of 2 KB (stage, row block), each 16 rows x 64 k.
+    //
+    // Activation tile: two half blocks of 8 rows, one load instruction each; lane l of the load takes
+    // 16 bytes of row l/8, so a quarter wave covers two whole 128-byte lines of A (the memory pipe
+    // handles a quarter wave at a time, and sixteen lanes on sixteen different lines cost it nearly
+    // twice the time).  The row sits at 128*(row%8) inside its half block with its eight 16-byte
+    // pieces XOR-swizzled: piece p (k = 8p .. 8p+7 of the stage) lies at slot p ^ z(row),
+    // z(row) = 2*((row/2)%4) + row/8, which spreads the sixteen rows a quarter wave reads for one
+    // matrix-core step (same piece of rows 0..15) over all sixteen 16-byte bank groups.
 
-    // The whole K loop and the store, for a wave with NRB row blocks (0: a wave that only loads).
-    // NRB is a compile-time constant inside so that the loop bodies have no branches.
-    auto run = [&](auto nrb_tag) {
-        constexpr int NRB = decltype(nrb_tag)::value;
-        constexpr int NR = NRB > 0 ? NRB : 1;
-        struct Frags {
-            bf16x8 wf[CB][2];
-            bf16x8 xf[NR][2];
+    if (nrb == 0) {
+        // ---------------------------------------------------------------- loading wave
+        const int nload = tp.nload;  // = NW + NL - ncomp
+        const int lrank = wave - ncomp;
+        const char* wbytes = reinterpret_cast<const char*>(Bp + (size_t)blockIdx.x * nstages * (2 * CB * 64));
+        const char* abytes = reinterpret_cast<const char*>(A + (size_t)m0 * lda);
+        const size_t half_bytes = (size_t)lda * 16;  // 8 rows of A
+        const uint32_t w_lane_off = (uint32_t)lane * 16u;
+        const int lrow = lane >> 3;  // row of this lane inside a half block
+        const uint32_t zl = (uint32_t)(((lane >> 4) & 3) << 1);
+        const uint32_t a_lane_off0 = (uint32_t)lrow * (uint32_t)lda * 2u + 16u * ((uint32_t)(lane & 7) ^ zl);
+        const uint32_t a_lane_off1 = (uint32_t)lrow * (uint32_t)lda * 2u + 16u * ((uint32_t)(lane & 7) ^ (zl | 1u));
+        const uint32_t a_lane_off_mine = (lrank & 1) ? a_lane_off1 : a_lane_off0;
+        // Split of a chunk's loads over the loading waves.  Weight blocks: q = lrank, lrank+nload, ...
+        // below s_cnt*2*CB.  Half blocks: if every half block is whole and there are at least nload of
+        // them, hb = lrank, lrank+nload, ... below HB in every stage (short loop: the loaders'
+        // instruction count per load matters for tall tiles); else unit pp = sl*HB + hb = lrank,
+        // lrank+nload, ... below s_cnt*HB.  A half block that holds data always has a live lane.
+        const bool stage_split = (mrem & 7) == 0 && HB >= nload;
+        auto strided = [&](int n) { return n > lrank ? (int)(((uint32_t)(n - lrank + nload - 1) * tp.inv_nload) >> 20) : 0; };
+        auto loads_for = [&](int s_cnt) {
+            return strided(s_cnt * 2 * CB) + (stage_split ? s_cnt * strided(HB) : strided(s_cnt * HB));
         };
-        f32x4 acc[NR][CB];
-#pragma unroll
-        for (int r = 0; r < NR; ++r)
-#pragma unroll
-            for (int j = 0; j < CB; ++j) acc[r][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        // every chunk but the last has SPC stages, so two values cover all chunks
+        const int loads_full = loads_for(SPC);
+        const int loads_last = loads_for(tp.last_cnt);
+        auto wave_loads = [&](int c) { return c < nchunks - 1 ? loads_full : (c == nchunks - 1 ? loads_last : 0); };
+        const int nw_full = strided(SPC * 2 * CB);  // weight blocks of a chunk, this wave
+        const int nw_last = strided(tp.last_cnt * 2 * CB);
+        const int nh_stage = strided(HB);  // half blocks of a stage, this wave, under the stage split
+        const int first_sl = (int)(((uint32_t)lrank * tp.inv_hb) >> 20);  // lrank / HB: first unit of a chunk under the unit split
+        const int first_hb = lrank - first_sl * HB;
 
-        // cn / slot_n: the chunk whose loads are issued between the steps (interleaved regime), -1: none
-        auto compute_chunk = [&](int c, int slot_idx, int cn, int slot_n) {
+        auto load_chunk = [&](int c, int slot_idx) {
             const int s_cnt = chunk_stages(c);
-            const int sn_cnt = cn >= 0 ? chunk_stages(cn) : 0;
-            const int sn0 = cn * SPC;
-            const int nwn = sn_cnt * 2 * CB;
-            const uint32_t slot_n_addr = ring_addr + (uint32_t)(slot_n * slot_blocks) * 1024u;
-            const uint4* slot = ring + (size_t)(slot_idx * slot_blocks) * 64;
-            const uint4* wbase = slot + lane;
-            const uint4* abuf = slot + s_cnt * (2 * CB * 64) + 2 * wave * 64 + lane;
-            auto read_stage = [&](Frags& fr, int sl) {
-                const uint4* wp = wbase + sl * (2 * CB * 64);
-#pragma unroll
-                for (int j = 0; j < CB; ++j) {
-                    fr.wf[j][0] = __builtin_bit_cast(bf16x8, wp[(2 * j) * 64]);
-                    fr.wf[j][1] = __builtin_bit_cast(bf16x8, wp[(2 * j + 1) * 64]);
+            if (s_cnt == 0) return;
+            const int s0 = c * SPC;
+            const int nw = s_cnt * 2 * CB;
+            const uint32_t slot_addr = ring_addr + (uint32_t)(slot_idx * slot_blocks) * 1024u;
+            dma_run(wbytes, w_lane_off + (uint32_t)(s0 * (2 * CB) + lrank) * 1024u, (uint32_t)nload * 1024u,
+                    slot_addr + (uint32_t)lrank * 1024u, (uint32_t)nload * 1024u, s_cnt == SPC ? nw_full : nw_last);
+            // Half block hb of stage sl comes from abytes + hb*half_bytes + 128*(s0+sl) and goes to block
+            // 2*RB*sl + hb of the tile area; both are walked with running addresses.
+            if (stage_split && (nload & 1) == 0) {  // all of this wave's half blocks have the parity of its rank
+                uint32_t off = a_lane_off_mine + (uint32_t)lrank * (uint32_t)half_bytes + ((uint32_t)s0 << 7);
+                uint32_t adst = slot_addr + (uint32_t)(nw + lrank) * 1024u;
+                for (int sl = 0; sl < s_cnt; ++sl) {
+                    dma_run(abytes, off, (uint32_t)nload * (uint32_t)half_bytes, adst, (uint32_t)nload * 1024u, nh_stage);
+                    off += 128;
+                    adst += (uint32_t)(2 * RB) * 1024u;
                 }
-                const uint4* ap = abuf + sl * nA * 64;
-#pragma unroll
-                for (int r = 0; r < NRB; ++r) {
-                    fr.xf[r][0] = __builtin_bit_cast(bf16x8, ap[(2 * NW * r) * 64]);
-                    fr.xf[r][1] = __builtin_bit_cast(bf16x8, ap[(2 * NW * r + 1) * 64]);
-                }
-                __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the steps they feed
-            };
-            // Steps of stage sl.  In the interleaved regime the loads of stage sl of chunk cn go out
-            // between the groups of steps (pairs after the i = 0 groups, weight blocks after the i = 1
-            // groups), so that address generation overlaps the matrix-core pipe.
-            constexpr int NBW = (2 * CB + NW - 1) / NW;  // most weight blocks per stage any wave takes
-            auto mfma_stage = [&](const Frags& fr, int sl) {
-                const bool ld = sl < sn_cnt;
-#pragma unroll
-                for (int i = 0; i < 2; ++i)
-#pragma unroll
-                    for (int r = 0; r < NRB; ++r) {
-#pragma unroll
-                        for (int j = 0; j < CB; ++j)
-                            acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fr.wf[j][i], fr.xf[r][i], acc[r][j], 0, 0, 0);
-                        if (ld) {
-                            __builtin_amdgcn_sched_barrier(0);
-                            if (i == 0) {
-                                issue_pair(sn0, sl, r, slot_n_addr, nwn);
-                            } else {
-                                issue_weight(sn0, sl, r, slot_n_addr);
-                                if (r == NRB - 1) {
-#pragma unroll
-                                    for (int t = NRB; t < NBW; ++t) issue_weight(sn0, sl, t, slot_n_addr);
-                                }
-                            }
-                        }
+                return;
+            }
+            if (stage_split) {
+                const char* src0 = abytes + (size_t)lrank * half_bytes + ((size_t)s0 << 7);
+                uint32_t dst0 = slot_addr + (uint32_t)(nw + lrank) * 1024u;
+                for (int sl = 0; sl < s_cnt; ++sl) {
+                    const char* asrc = src0;
+                    uint32_t adst = dst0;
+                    for (int hb = lrank; hb < HB; hb += nload) {
+                        dma_block(asrc, (hb & 1) ? a_lane_off1 : a_lane_off0, adst);
+                        asrc += (size_t)nload * half_bytes;
+                        adst += (uint32_t)nload * 1024u;
                     }
-                __builtin_amdgcn_sched_barrier(0);
-            };
-            // Stages in ascending order, software pipelined: the LDS reads of stage s+D-1 are issued
-            // before the steps of stage s (D = 4 for small tiles, whose steps are too few to cover the
-            // LDS latency, else 2).  Reads past the last stage are redirected to the last stage: in
-            // bounds and unused, which keeps the loop body free of branches.
-            constexpr int D = (CB * NRB >= 4) ? 2 : 4;
-            Frags f[D];
-            const int last = s_cnt - 1;
-#pragma unroll
-            for (int d = 0; d < D - 1; ++d) read_stage(f[d], min(d, last));
-            for (int sl = 0; sl < s_cnt; sl += D) {
-#pragma unroll
-                for (int u = 0; u < D; ++u) {
-                    if (sl + u >= s_cnt) return;
-                    read_stage(f[(u + D - 1) % D], min(sl + u + D - 1, last));
-                    mfma_stage(f[u], sl + u);
+                    src0 += 128;
+                    dst0 += (uint32_t)(2 * RB) * 1024u;
+                }
+                return;
+            }
+            const int nhalf = s_cnt * HB;
+            int hb = first_hb;
+            const char* asrc = abytes + (size_t)hb * half_bytes + ((size_t)(s0 + first_sl) << 7);
+            uint32_t adst = slot_addr + (uint32_t)(nw + first_sl * 2 * RB + hb) * 1024u;
+            for (int pp = lrank; pp < nhalf; pp += nload) {
+                // rows past M load nothing: their LDS bytes feed only outputs that are never stored
+                if (8 * hb + lrow < mrem) dma_block(asrc, (hb & 1) ? a_lane_off1 : a_lane_off0, adst);
+                hb += nload;
+                asrc += (size_t)nload * half_bytes;
+                adst += (uint32_t)nload * 1024u;
+                while (hb >= HB) {  // next stage
+                    hb -= HB;
+                    asrc += 128 - (ptrdiff_t)((size_t)HB * half_bytes);
+                    adst += (uint32_t)(2 * RB - HB) * 1024u;
                 }
             }
         };
@@ -323,24 +325,126 @@ __global__ __launch_bounds__(64 * NW) void gemm_kernel(const uint16_t* __restric
         int slot_c = 0;    // slot of chunk c
         int slot_new = P;  // slot of chunk c+P (the slot chunk c-1 used: nslots = P+1)
         for (int c = 0; c < nchunks; ++c) {
-            // Loads issued after chunk c's: chunks c+1 .. c+P-1.  Once chunk c has landed here and
-            // the barrier is passed, it has landed for every wave, and every wave is done with chunk
-            // c-1, whose slot is the one chunk c+P goes into.
+            // Loads issued after chunk c's: chunks c+1 .. c+P-1.  Once chunk c has landed here and the
+            // barrier is passed, it has landed for every loader, and every computing wave is done with
+            // chunk c-1, whose slot is the one chunk c+P goes into.
             int younger = 0;
             for (int d = 1; d < P; ++d) younger += wave_loads(c + d);
             wait_loads_then_barrier(younger);
-            if constexpr (NRB > 0) {
-                if (interleaved) {
-                    compute_chunk(c, slot_c, c + P, slot_new);
-                } else {
-                    load_chunk(c + P, slot_new);
-                    compute_chunk(c, slot_c, -1, 0);
-                }
-            } else {
-                load_chunk(c + P, slot_new);
-            }
+            load_chunk(c + P, slot_new);
             slot_new = slot_c;
             slot_c = slot_c + 1 == nslots ? 0 : slot_c + 1;
+        }
+        return;
+    }
+
+    // -------------------------------------------------------------------- computing wave
+    // NRB (row blocks of the wave) is a compile-time constant inside so that the loop bodies have no
+    // branches.
+    auto run = [&](auto nrb_tag) {
+        constexpr int NRB = decltype(nrb_tag)::value;
+        struct Frags {  // operands of one matrix-core step
+            bf16x8 wf[CB];
+            bf16x8 xf[NRB];
+        };
+        f32x4 acc[NRB][CB];
+#pragma unroll
+        for (int r = 0; r < NRB; ++r)
+#pragma unroll
+            for (int j = 0; j < CB; ++j) acc[r][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+        // this lane's two pieces (k group g of step 0 and of step 1) of row lr in the tile of row block `wave`
+        const int zr = (((lr >> 1) & 3) << 1) | (lr >> 3);
+        const int a_lane = 2 * wave * 64 + 64 * (lr >> 3) + 8 * (lr & 7);
+        const int a0_off = a_lane + (g ^ zr), a1_off = a_lane + ((g ^ zr) ^ 4);
+        // wp: weight block of the step (this lane's 16 bytes of column block 0); ap: the lane's piece in
+        // the tile of row block `wave`
+        auto rd = [&](Frags& fr, const uint4* wp, const uint4* ap) {
+#pragma unroll
+            for (int j = 0; j < CB; ++j) fr.wf[j] = __builtin_bit_cast(bf16x8, wp[(2 * j) * 64]);
+#pragma unroll
+            for (int r = 0; r < NRB; ++r) fr.xf[r] = __builtin_bit_cast(bf16x8, ap[(2 * NW * r) * 64]);
+            __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the steps they feed
+        };
+        auto mm = [&](const Frags& fr) {
+#pragma unroll
+            for (int r = 0; r < NRB; ++r)
+#pragma unroll
+                for (int j = 0; j < CB; ++j)
+                    acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fr.wf[j], fr.xf[r], acc[r][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        // all of this wave's LDS reads have returned, then the barrier that opens the next chunk
+        auto open_chunk = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+
+        if constexpr (CB * NRB >= 6) {
+            // One two-deep pipeline over the whole K range: the operands of a chunk's first step are read
+            // while the last step of the chunk before is in the matrix core, so that no LDS latency is
+            // exposed at a chunk boundary (a chunk is a single stage for the tallest tiles).  The barrier
+            // that opens chunk c+1 therefore sits before the last step of chunk c; the wave has issued,
+            // and waited for, all its reads of chunk c-1 by then, which is what the loaders rely on.
+            Frags f0, f1;
+            int slot_c = 0;
+            int s_cnt = chunk_stages(0);
+            open_chunk();
+            const uint4* wp = ring + lane;
+            const uint4* ab = ring + s_cnt * (2 * CB * 64);  // activation tiles of the stage
+            rd(f0, wp, ab + a0_off);
+            for (int c = 0; c < nchunks; ++c) {
+                int next_cnt = 0;
+                for (int sl = 0; sl < s_cnt; ++sl) {
+                    rd(f1, wp + 64, ab + a1_off);
+                    mm(f0);
+                    if (sl + 1 < s_cnt) {
+                        wp += 2 * CB * 64;
+                        ab += nA * 64;
+                        rd(f0, wp, ab + a0_off);
+                    } else if (c + 1 < nchunks) {
+                        open_chunk();
+                        slot_c = slot_c + 1 == nslots ? 0 : slot_c + 1;
+                        next_cnt = chunk_stages(c + 1);
+                        wp = ring + (size_t)(slot_c * slot_blocks) * 64 + lane;
+                        ab = ring + (size_t)(slot_c * slot_blocks) * 64 + next_cnt * (2 * CB * 64);
+                        rd(f0, wp, ab + a0_off);
+                    }
+                    mm(f1);
+                }
+                s_cnt = next_cnt;
+            }
+        } else {
+            // Small tiles: a step has too few matrix-core instructions to cover the LDS latency, so the
+            // reads run DS-1 steps ahead (DS = 8, or 4 from 4 instructions a step on), one pipeline per
+            // chunk (a chunk has many stages here).  Reads past the chunk's last stage are redirected to
+            // the last stage: in bounds and unused, which keeps the loop body free of branches.
+            constexpr int DS = (CB * NRB >= 4) ? 4 : 8;
+            int slot_c = 0;
+            for (int c = 0; c < nchunks; ++c) {
+                open_chunk();
+                const int s_cnt = chunk_stages(c);
+                const uint4* slot = ring + (size_t)(slot_c * slot_blocks) * 64;
+                const uint4* wbase = slot + lane;
+                const uint4* abase0 = slot + s_cnt * (2 * CB * 64) + a0_off;
+                const uint4* abase1 = slot + s_cnt * (2 * CB * 64) + a1_off;
+                const int last = s_cnt - 1;
+                auto rd_step = [&](Frags& fr, int u, int odd) {  // step u = 2*stage + odd; odd is static at every call
+                    const int sl = min(u >> 1, last);
+                    rd(fr, wbase + sl * (2 * CB * 64) + odd * 64, (odd ? abase1 : abase0) + sl * nA * 64);
+                };
+                Frags f[DS];
+#pragma unroll
+                for (int d = 0; d < DS - 1; ++d) rd_step(f[d], d, d & 1);
+                const int nsteps = 2 * s_cnt;
+                for (int u0 = 0; u0 < nsteps; u0 += DS) {
+#pragma unroll
+                    for (int k = 0; k < DS; ++k) {  // DS is even, so the parity of step u0+k is that of k
+                        if (u0 + k < nsteps) {
+                            rd_step(f[(k + DS - 1) % DS], u0 + k + DS - 1, (k + DS - 1) & 1);
+                            mm(f[k]);
+                        }
+                    }
+                }
+                slot_c = slot_c + 1 == nslots ? 0 : slot_c + 1;
+            }
         }
 
         // Lane holds C[row = 16*rb + lr][n0 + 16j + 4g + v], v = 0..3.
@@ -382,14 +486,12 @@ __global__ __launch_bounds__(64 * NW) void gemm_kernel(const uint16_t* __restric
         }
     };
     if constexpr (NW == 8) {
-        switch (nrb) {
-            case 0: run(std::integral_constant<int, 0>{}); break;
-            case 1: run(std::integral_constant<int, 1>{}); break;
-            default: run(std::integral_constant<int, 2>{}); break;
-        }
+        if (nrb == 1)
+            run(std::integral_constant<int, 1>{});
+        else
+            run(std::integral_constant<int, 2>{});
     } else {
         switch (nrb) {
-            case 0: run(std::integral_constant<int, 0>{}); break;
             case 1: run(std::integral_constant<int, 1>{}); break;
             case 2: run(std::integral_constant<int, 2>{}); break;
             case 3: run(std::integral_constant<int, 3>{}); break;
@@ -431,14 +533,16 @@ __global__ __launch_bounds__(256) void gemm_pack_kernel(const uint16_t* __restri
     }
 }
 
-template <int CB, int RINGB, int EPI, int NW>
+template <int CB, int RINGB, int EPI, int NW, int NL>
 static void launch_gemm(const void* A, int lda, const void* Bp, void* C, int ldc, const void* R, int ldr, int M,
                         int N, int K, int out_f32, hipStream_t s)
 {
     dim3 grid(N / (16 * CB), (M + 255) / 256);
-    hipLaunchKernelGGL((gemm_kernel<CB, RINGB, EPI, NW>), grid, dim3(64 * NW), 0, s, static_cast<const uint16_t*>(A), lda,
-                       static_cast<const uint4*>(Bp), C, ldc, static_cast<const uint16_t*>(R), ldr, M, K,
-                       out_f32);
+    const gemm_tile_plan full = make_tile_plan(256, CB, RINGB, NW, NL, K);
+    const gemm_tile_plan tail = make_tile_plan(M - 256 * ((M - 1) / 256), CB, RINGB, NW, NL, K);
+    hipLaunchKernelGGL((gemm_kernel<CB, RINGB, EPI, NW, NL>), grid, dim3(64 * (NW + NL)), 0, s,
+                       static_cast<const uint16_t*>(A), lda, static_cast<const uint4*>(Bp), C, ldc,
+                       static_cast<const uint16_t*>(R), ldr, K, out_f32, full, tail);
 }
 
 // Picks the kernel configuration from N alone and launches it.
@@ -452,11 +556,11 @@ static int gemm_dispatch(const void* A, int lda, const void* Bp, void* C, int ld
     case CBV:                                                                                               \
         if constexpr (CBV <= 3) {                                                                           \
             if (small) {                                                                                    \
-                launch_gemm<CBV, gemm_small_ring_blocks(CBV), EPI, gemm_waves(CBV)>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s); \
+                launch_gemm<CBV, gemm_small_ring_blocks(CBV), EPI, gemm_waves(CBV), gemm_loader_waves(CBV, true)>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s); \
                 break;                                                                                      \
             }                                                                                               \
         }                                                                                                   \
-        launch_gemm<CBV, kRingBig, EPI, gemm_waves(CBV)>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s);                       \
+        launch_gemm<CBV, kRingBig, EPI, gemm_waves(CBV), gemm_loader_waves(CBV, false)>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s);                       \
         break;
     switch (cb) {
         DET_GEMM_CASE(1)
@@ -467,7 +571,7 @@ static int gemm_dispatch(const void* A, int lda, const void* Bp, void* C, int ld
         DET_GEMM_CASE(6)
         DET_GEMM_CASE(7)
         default:
-            launch_gemm<8, kRingBig, EPI, gemm_waves(8)>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s);
+            launch_gemm<8, kRingBig, EPI, gemm_waves(8), gemm_loader_waves(8, false)>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s);
             break;
     }
 #undef DET_GEMM_CASE
@@ -515,6 +619,7 @@ static int gemm_args_ok(const void* A, int lda, const void* Bp, const void* C, i
     if (!A || !Bp || !C || M < 1) return DET_EINVAL;
     if (!gemm_shape_ok(N, K)) return DET_ESHAPE;
     if (lda < K) return DET_EINVAL;
+    if (lda > (1 << 22)) return DET_ESHAPE;  // the kernel keeps byte offsets inside a 256-row tile of A in 32 bits
     if (!aligned16(A) || !aligned16(Bp) || !aligned16(C) || lda % 8 != 0 || ldc % 4 != 0) return DET_EALIGN;
     return DET_OK;
 }
