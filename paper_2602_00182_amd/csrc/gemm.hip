@@ -4,31 +4,38 @@
 // no atomics).
 //
 // Shape of the kernel
-//   * A workgroup (NW = 4 or 8 wavefronts) owns BN = 16*CB output columns and up to 256 rows; grid.x = N/BN,
-//     grid.y = ceil(M/256).  CB and the LDS ring size are functions of N alone, so the
-//     configuration never depends on M.
+//   * A workgroup owns BN = 16*CB output columns and up to 256 rows; grid.x = N/BN, grid.y =
+//     ceil(M/256).  It has NW (4 or 8) wavefronts that can compute plus NL (2 or 4) that only load.
+//     CB, the LDS ring size and the wave counts are functions of N alone, so the configuration never
+//     depends on M.
 //   * K is cut into 64-deep stages.  Operands travel as 1 KB blocks.  A weight block is already in
 //     the operand order of v_mfma_f32_16x16x32_bf16 (lane l holds 8 consecutive k of column l%16, k
 //     group l/16); an activation block is 8 rows x 64 k as they lie in A (whole 128-byte lines),
 //     swizzled in LDS so that the operand reads are conflict free.  A stage has 2*CB weight blocks
 //     and one activation block per 8 rows that hold data.  M decides the number of row blocks and
-//     which waves issue loads, nothing else.
+//     which waves compute, nothing else.
 //   * Stages are grouped into chunks and streamed through a ring of up to 4 LDS slots with the
 //     LDS-DMA form of the global load (global_load_lds_dwordx4: no staging registers, one wave
-//     instruction fills one 1 KB block).  Up to 3 chunks are in flight while the waves compute on
-//     a fourth; a wave waits only for its own loads of the oldest chunk (s_waitcnt vmcnt(n) with n
-//     = its loads of the younger chunks), then the workgroup barrier makes the chunk visible.
-//     The weight slab of a workgroup is one contiguous run of the packed matrix.
+//     instruction fills one 1 KB block).  Up to 3 chunks are in flight while the computing waves
+//     work on a fourth; a loading wave waits only for its own loads of the oldest chunk (s_waitcnt
+//     vmcnt(n) with n = its loads of the younger chunks), then the workgroup barrier makes the chunk
+//     visible.  The weight slab of a workgroup is one contiguous run of the packed matrix.
+//   * 16-row blocks are dealt round-robin to the waves 0..NW-1 (block rb -> wave rb % NW).  A wave
+//     with a row block only computes; every other wave only loads.  What bounds a tall tile is the
+//     compute unit's memory pipe (about 25 bytes a clock into LDS for data that hits in L2, and
+//     every load, hit or miss, completes in issue order), so the load queue must never run dry: a
+//     wave that both loads and computes either blocks on a full queue with matrix-core work
+//     unissued or computes while the queue drains.
 //   * Weights are the ROW operand of the MFMA (16 output columns of C), activations its COLUMN
 //     operand (16 rows of C): a lane then holds 4 consecutive columns of one row of C and the
 //     store is one 8- or 16-byte write.  Rows of the operand are independent in the matrix core,
 //     so rows past M may hold anything: their lanes load nothing and their outputs are never
 //     stored.
-//   * 16-row blocks are dealt round-robin to the waves (block rb -> wave rb % NW).
 //
 // K order: matrix-core step t (t = 0 .. K/32-1, ascending) takes k in [32t, 32t+32); inside a step
 // lane group g supplies k = 32t + 8g + e, e = 0..7.
 #include <type_traits>
+#include <utility>
 
 #include "common.h"
 
@@ -114,24 +121,34 @@ __device__ __forceinline__ void dma_run(const void* base, uint32_t lane_off, uin
 }
 
 // Waits until at most n of this wave's loads are outstanding (the counter holds 0..63; anything
-// above falls back to waiting for all of them), then the workgroup barrier.
-#define DET_WB(n) \
-    case n: asm volatile("s_waitcnt vmcnt(" #n ")\n\ts_barrier" ::: "memory"); break;
+// above falls back to waiting for all of them), then the workgroup barrier.  The count is an
+// immediate of the wait instruction, so the wait is picked by a computed jump into a table of
+// 64 two-instruction entries (8 bytes each): two taken branches where a compare tree takes six.
+#define DET_W1(n) "s_waitcnt vmcnt(" #n ")\n\ts_branch .Ldet_wend%=\n\t"
+#define DET_W8(a, b, c, d, e, f, g, h) DET_W1(a) DET_W1(b) DET_W1(c) DET_W1(d) DET_W1(e) DET_W1(f) DET_W1(g) DET_W1(h)
 __device__ __forceinline__ void wait_loads_then_barrier(int n)
 {
-    switch (n) {
-        DET_WB(1) DET_WB(2) DET_WB(3) DET_WB(4) DET_WB(5) DET_WB(6) DET_WB(7) DET_WB(8)
-        DET_WB(9) DET_WB(10) DET_WB(11) DET_WB(12) DET_WB(13) DET_WB(14) DET_WB(15) DET_WB(16)
-        DET_WB(17) DET_WB(18) DET_WB(19) DET_WB(20) DET_WB(21) DET_WB(22) DET_WB(23) DET_WB(24)
-        DET_WB(25) DET_WB(26) DET_WB(27) DET_WB(28) DET_WB(29) DET_WB(30) DET_WB(31) DET_WB(32)
-        DET_WB(33) DET_WB(34) DET_WB(35) DET_WB(36) DET_WB(37) DET_WB(38) DET_WB(39) DET_WB(40)
-        DET_WB(41) DET_WB(42) DET_WB(43) DET_WB(44) DET_WB(45) DET_WB(46) DET_WB(47) DET_WB(48)
-        DET_WB(49) DET_WB(50) DET_WB(51) DET_WB(52) DET_WB(53) DET_WB(54) DET_WB(55) DET_WB(56)
-        DET_WB(57) DET_WB(58) DET_WB(59) DET_WB(60) DET_WB(61) DET_WB(62) DET_WB(63)
-        default: asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory"); break;
-    }
+    uint32_t off = (uint32_t)(n > 63 ? 0 : n) << 3;
+    asm volatile(
+        "s_getpc_b64 s[98:99]\n"
+        ".Ldet_wbase%=:\n\t"
+        "s_add_u32 %0, %0, .Ldet_wtab%=-.Ldet_wbase%=\n\t"
+        "s_add_u32 s98, s98, %0\n\t"
+        "s_addc_u32 s99, s99, 0\n\t"
+        "s_setpc_b64 s[98:99]\n"
+        ".Ldet_wtab%=:\n\t"
+        DET_W8(0, 1, 2, 3, 4, 5, 6, 7) DET_W8(8, 9, 10, 11, 12, 13, 14, 15)
+        DET_W8(16, 17, 18, 19, 20, 21, 22, 23) DET_W8(24, 25, 26, 27, 28, 29, 30, 31)
+        DET_W8(32, 33, 34, 35, 36, 37, 38, 39) DET_W8(40, 41, 42, 43, 44, 45, 46, 47)
+        DET_W8(48, 49, 50, 51, 52, 53, 54, 55) DET_W8(56, 57, 58, 59, 60, 61, 62, 63)
+        ".Ldet_wend%=:\n\t"
+        "s_barrier"
+        : "+s"(off)
+        :
+        : "memory", "scc", "s98", "s99");
 }
-#undef DET_WB
+#undef DET_W8
+#undef DET_W1
 
 // Epilogues.  kEpiStore: C = bf16(acc) or fp32 acc.  kEpiResidual: C = bf16(fp32(bf16(acc)) + fp32(R)),
 // the bytes of the plain GEMM followed by the residual add.  kEpiSwiglu: the weight columns are packed
@@ -145,6 +162,43 @@ __device__ __forceinline__ float silu_mul(float gate, float up)
     const float den = 1.0f + det_expf(-gate);
     const float sg = gate / den;
     return sg * up;
+}
+
+// LDS reads the compiler does not see.  Its own bookkeeping of the LDS counter waits for every read in
+// flight before the first use of any of them once reads cross a loop back edge; written by hand, the
+// wait before a matrix-core step can leave the reads of the following step in flight.  tie() makes a
+// register an output of an (empty) instruction placed after the wait, so that no use of it can be
+// scheduled above the wait.
+template <int OFF>
+__device__ __forceinline__ bf16x8 lds_read_b128(uint32_t addr)
+{
+    bf16x8 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+template <int N>
+__device__ __forceinline__ void wait_lds_reads()
+{
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory");
+}
+template <class T>
+__device__ __forceinline__ void tie(T& v)
+{
+    asm volatile("" : "+v"(v));
+}
+// Operands of one step: weight blocks 2 KB apart from waddr, activation tiles NW*2 KB apart from aaddr.
+template <int NW, class Frags, int... J, int... Q>
+__device__ __forceinline__ void read_frags(Frags& fr, uint32_t waddr, uint32_t aaddr, std::integer_sequence<int, J...>,
+                                           std::integer_sequence<int, Q...>)
+{
+    ((fr.wf[J] = lds_read_b128<J * 2048>(waddr)), ...);
+    ((fr.xf[Q] = lds_read_b128<Q * NW * 2048>(aaddr)), ...);
+}
+template <class Frags, int... J, int... Q>
+__device__ __forceinline__ void tie_frags(Frags& fr, std::integer_sequence<int, J...>, std::integer_sequence<int, Q...>)
+{
+    (tie(fr.wf[J]), ...);
+    (tie(fr.xf[Q]), ...);
 }
 
 // Schedule of one 256-row tile: a function of the tile's row count, the kernel configuration and K,
@@ -322,14 +376,18 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
         };
 
         for (int c = 0; c < P; ++c) load_chunk(c, c);
+        const int younger_steady = (P - 1) * loads_full;  // while chunks c+1 .. c+P-1 are all full ones
         int slot_c = 0;    // slot of chunk c
         int slot_new = P;  // slot of chunk c+P (the slot chunk c-1 used: nslots = P+1)
         for (int c = 0; c < nchunks; ++c) {
             // Loads issued after chunk c's: chunks c+1 .. c+P-1.  Once chunk c has landed here and the
             // barrier is passed, it has landed for every loader, and every computing wave is done with
             // chunk c-1, whose slot is the one chunk c+P goes into.
-            int younger = 0;
-            for (int d = 1; d < P; ++d) younger += wave_loads(c + d);
+            int younger = younger_steady;
+            if (c + P > nchunks - 1) {  // the last chunks: fewer and shorter chunks behind chunk c
+                younger = 0;
+                for (int d = 1; d < P; ++d) younger += wave_loads(c + d);
+            }
             wait_loads_then_barrier(younger);
             load_chunk(c + P, slot_new);
             slot_new = slot_c;
@@ -383,30 +441,47 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
             // exposed at a chunk boundary (a chunk is a single stage for the tallest tiles).  The barrier
             // that opens chunk c+1 therefore sits before the last step of chunk c; the wave has issued,
             // and waited for, all its reads of chunk c-1 by then, which is what the loaders rely on.
+            // The reads of a step are issued before the wait for the step before it, which leaves exactly
+            // these CB+NRB reads in flight (LDS reads return in order).
+            using wseq = std::make_integer_sequence<int, CB>;
+            using xseq = std::make_integer_sequence<int, NRB>;
+            constexpr int kReads = CB + NRB;
+            static_assert(kReads <= 15, "the LDS counter holds 0..15");
             Frags f0, f1;
             int slot_c = 0;
             int s_cnt = chunk_stages(0);
             open_chunk();
-            const uint4* wp = ring + lane;
-            const uint4* ab = ring + s_cnt * (2 * CB * 64);  // activation tiles of the stage
-            rd(f0, wp, ab + a0_off);
+            uint32_t wa = ring_addr + (uint32_t)lane * 16u;                 // weight block 0 of the stage, this lane
+            uint32_t xa = ring_addr + (uint32_t)(s_cnt * 2 * CB) * 1024u;   // activation tiles of the stage
+            const uint32_t x0 = (uint32_t)a0_off * 16u, x1 = (uint32_t)a1_off * 16u;
+            read_frags<NW>(f0, wa, xa + x0, wseq{}, xseq{});
             for (int c = 0; c < nchunks; ++c) {
                 int next_cnt = 0;
                 for (int sl = 0; sl < s_cnt; ++sl) {
-                    rd(f1, wp + 64, ab + a1_off);
+                    read_frags<NW>(f1, wa + 1024u, xa + x1, wseq{}, xseq{});
+                    wait_lds_reads<kReads>();
+                    tie_frags(f0, wseq{}, xseq{});
                     mm(f0);
+                    bool more = true;
                     if (sl + 1 < s_cnt) {
-                        wp += 2 * CB * 64;
-                        ab += nA * 64;
-                        rd(f0, wp, ab + a0_off);
+                        wa += (uint32_t)(2 * CB) * 1024u;
+                        xa += (uint32_t)nA * 1024u;
+                        read_frags<NW>(f0, wa, xa + x0, wseq{}, xseq{});
                     } else if (c + 1 < nchunks) {
                         open_chunk();
                         slot_c = slot_c + 1 == nslots ? 0 : slot_c + 1;
                         next_cnt = chunk_stages(c + 1);
-                        wp = ring + (size_t)(slot_c * slot_blocks) * 64 + lane;
-                        ab = ring + (size_t)(slot_c * slot_blocks) * 64 + next_cnt * (2 * CB * 64);
-                        rd(f0, wp, ab + a0_off);
+                        wa = ring_addr + (uint32_t)(slot_c * slot_blocks) * 1024u + (uint32_t)lane * 16u;
+                        xa = ring_addr + (uint32_t)(slot_c * slot_blocks + next_cnt * 2 * CB) * 1024u;
+                        read_frags<NW>(f0, wa, xa + x0, wseq{}, xseq{});
+                    } else {
+                        more = false;
                     }
+                    if (more)
+                        wait_lds_reads<kReads>();
+                    else
+                        wait_lds_reads<0>();
+                    tie_frags(f1, wseq{}, xseq{});
                     mm(f1);
                 }
                 s_cnt = next_cnt;
