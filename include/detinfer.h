@@ -248,6 +248,34 @@ int det_next_token(const int32_t *prompts, int Tp, const int32_t *prompt_lens,
                    const int32_t *last_sampled, int32_t *tokens_out, int32_t *positions_out,
                    int32_t *history, int Th, int t, int B, void *stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Output commitment (the paper's section 6.7 records SHA256(prompt || logits || tokens) for every
+ * execution, and a receipt commits to the output by its hash, section 4.1).  HOST code on HOST
+ * pointers: SHA-256 (FIPS 180-4) is a serial chain, so the caller copies what it wants committed
+ * to host memory (per step, overlapped with the next step) and feeds it here.
+ *
+ * det_sha256_init / _update / _final: streaming interface; the context is caller-owned plain data
+ * (no allocation); after _final the context is spent and must be re-initialised.  DET_EINVAL for
+ * null pointers or a spent context.  det_commit_sha256: the three byte strings hashed in the
+ * paper's order in one call; a length may be 0 (its pointer is then ignored).  The digest is the 32
+ * bytes in the standard's order (big-endian words).  The bytes hashed are the caller's: this
+ * library's convention (tests, decode loop) is int32 little-endian token ids and fp32 little-endian
+ * logits, step-major. */
+typedef struct det_sha256_ctx {
+    uint32_t h[8];
+    uint64_t nbytes;
+    uint8_t buf[64];
+    uint32_t fill;
+} det_sha256_ctx;
+int det_sha256_init(det_sha256_ctx *ctx);
+int det_sha256_update(det_sha256_ctx *ctx, const void *data, size_t bytes);
+int det_sha256_final(det_sha256_ctx *ctx, uint8_t digest[32]);
+int det_commit_sha256(const void *prompt, size_t prompt_bytes, const void *logits, size_t logits_bytes,
+                      const void *tokens, size_t tokens_bytes, uint8_t digest[32]);
+/* Test hook: nonzero makes the calls above use the portable compression function even where the
+ * CPU has SHA instructions (process-wide). */
+int det_sha256_force_portable(int on);
+
 /* Build identification: target architecture, ROCm version the library was built with, and the
  * kernel-configuration revision (echoes the paper's `system_fingerprint` response field, section
  * 7.1).  Static storage; host pointer. */

@@ -250,3 +250,11 @@ def sample(logits, temperature: float, top_k: int, top_p: float, seed: int, seq_
     lib().orc_sample(_p(x), C.c_int(B), C.c_int(V), C.c_float(temperature), C.c_int(top_k), C.c_float(top_p),
                      C.c_uint64(seed & (2 ** 64 - 1)), _p(seq_ids), _p(steps), _p(out))
     return out
+
+
+def commit_sha256(prompt: bytes, logits: bytes, tokens: bytes) -> bytes:
+    """The digest the paper records per execution (section 6.7): SHA-256 of the three byte strings
+    concatenated in that order.  The hash itself is the standard library's (a library primitive as a
+    step); pinned by the FIPS 180-4 example digests in tests/golden/."""
+    import hashlib
+    return hashlib.sha256(bytes(prompt) + bytes(logits) + bytes(tokens)).digest()

@@ -20,6 +20,10 @@ class LayerWeights(C.Structure):
                 ("w_norm2", C.c_void_p), ("wgu", C.c_void_p), ("wdown", C.c_void_p)]
 
 
+class Sha256Ctx(C.Structure):
+    _fields_ = [("h", C.c_uint32 * 8), ("nbytes", C.c_uint64), ("buf", C.c_uint8 * 64), ("fill", C.c_uint32)]
+
+
 _vp, _i, _f, _sz, _i64 = C.c_void_p, C.c_int, C.c_float, C.c_size_t, C.c_int64
 
 # name -> (restype, argtypes); mirrors include/detinfer.h one to one
@@ -47,6 +51,11 @@ SIGNATURES = {
     "det_decoder_layer_rows": (_i, [C.POINTER(LayerWeights), C.POINTER(LayerCfg), _vp, _vp, _vp, _vp, _vp, _vp, _vp,
                                     _vp, _sz, _i, _vp]),
     "det_next_token": (_i, [_vp, _i, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _vp]),
+    "det_sha256_init": (_i, [C.POINTER(Sha256Ctx)]),
+    "det_sha256_update": (_i, [C.POINTER(Sha256Ctx), _vp, _sz]),
+    "det_sha256_final": (_i, [C.POINTER(Sha256Ctx), _vp]),
+    "det_commit_sha256": (_i, [_vp, _sz, _vp, _sz, _vp, _sz, _vp]),
+    "det_sha256_force_portable": (_i, [_i]),
     "det_fingerprint": (C.c_char_p, []),
     "det_last_hip_error": (_i, []),
 }

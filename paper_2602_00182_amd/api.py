@@ -8,7 +8,7 @@ import ctypes as C
 
 import torch
 
-from ._lib import LayerCfg, LayerWeights, lib
+from ._lib import LayerCfg, LayerWeights, Sha256Ctx, lib
 
 __all__ = [
     "DetError", "det_gemm_bf16", "det_gemm_packed_b_bytes", "det_gemm_pack_b", "det_gemm_bf16_residual",
@@ -17,7 +17,8 @@ __all__ = [
     "det_softmax_f32", "det_argmax", "det_sample", "det_rope",
     "det_swiglu", "det_residual_add", "det_embed_gather", "det_decoder_layer_workspace_bytes",
     "det_decoder_layer", "det_next_token", "det_fingerprint", "det_last_hip_error", "layer_cfg",
-    "layer_weights", "pack_weight",
+    "layer_weights", "pack_weight", "det_sha256_init", "det_sha256_update", "det_sha256_final",
+    "det_commit_sha256", "det_sha256_force_portable",
 ]
 
 _CODES = {1: "DET_EINVAL", 2: "DET_ESHAPE", 3: "DET_EALIGN", 4: "DET_EWORKSPACE", 5: "DET_EHIP"}
@@ -53,6 +54,56 @@ def _contig(t: torch.Tensor, dtype=None) -> int:
 def _stream(stream) -> int:
     s = torch.cuda.current_stream() if stream is None else stream
     return s.cuda_stream
+
+
+def _host_bytes(data):
+    """(address, length, keep-alive) of a host byte string: bytes, bytearray, numpy array or CPU tensor."""
+    if data is None:
+        return None, 0, None
+    if isinstance(data, torch.Tensor):
+        if data.is_cuda or not data.is_contiguous():
+            raise ValueError("the commitment hashes contiguous host memory")
+        return data.data_ptr(), data.numel() * data.element_size(), data
+    mv = memoryview(data)
+    if not mv.contiguous:
+        raise ValueError("the commitment hashes contiguous host memory")
+    if mv.nbytes == 0:
+        return None, 0, None
+    buf = (C.c_char * mv.nbytes).from_buffer_copy(mv) if mv.readonly else (C.c_char * mv.nbytes).from_buffer(mv)
+    return C.addressof(buf), mv.nbytes, buf
+
+
+def det_sha256_init() -> Sha256Ctx:
+    ctx = Sha256Ctx()
+    _check("det_sha256_init", lib().det_sha256_init(C.byref(ctx)))
+    return ctx
+
+
+def det_sha256_update(ctx: Sha256Ctx, data) -> None:
+    addr, n, keep = _host_bytes(data)
+    _check("det_sha256_update", lib().det_sha256_update(C.byref(ctx), addr, n))
+    del keep
+
+
+def det_sha256_final(ctx: Sha256Ctx) -> bytes:
+    out = (C.c_uint8 * 32)()
+    _check("det_sha256_final", lib().det_sha256_final(C.byref(ctx), out))
+    return bytes(out)
+
+
+def det_commit_sha256(prompt, logits, tokens) -> bytes:
+    """SHA256(prompt || logits || tokens) over host byte strings (None or empty: nothing hashed for that part)."""
+    pa, pn, k1 = _host_bytes(prompt)
+    la, ln, k2 = _host_bytes(logits)
+    ta, tn, k3 = _host_bytes(tokens)
+    out = (C.c_uint8 * 32)()
+    _check("det_commit_sha256", lib().det_commit_sha256(pa, pn, la, ln, ta, tn, out))
+    del k1, k2, k3
+    return bytes(out)
+
+
+def det_sha256_force_portable(on: bool) -> None:
+    _check("det_sha256_force_portable", lib().det_sha256_force_portable(int(bool(on))))
 
 
 def det_fingerprint() -> str:

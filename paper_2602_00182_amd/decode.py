@@ -205,3 +205,18 @@ def _prefill_decode(model, prompts, prompt_lens, n_new, rope_cos, rope_sin, stre
         if keep_logits:
             kept.append(st.logits.clone())
     return gen.t().contiguous(), kept
+
+
+def commit_outputs(prompts: torch.Tensor, prompt_lens: torch.Tensor, logits_steps, generated: torch.Tensor):
+    """Per-sequence output commitment, the hash the paper records for every execution (section 6.7):
+    SHA256(prompt || logits || tokens) with prompt = the sequence's own prompt ids (int32,
+    little-endian), logits = the fp32 logits rows of its generated steps in step order, tokens = its
+    generated ids (int32).  `logits_steps` is the list prefill_decode(keep_logits=True) returns.
+    Downloads to host memory and hashes there (det_commit_sha256).  Returns a list of 32-byte digests;
+    together with api.det_fingerprint() they are what a receipt would carry for the run."""
+    B = prompts.shape[0]
+    lens = prompt_lens.cpu().tolist()
+    p_host = prompts.to(torch.int32).cpu().contiguous()
+    g_host = generated.to(torch.int32).cpu().contiguous()
+    l_host = torch.stack(list(logits_steps)).permute(1, 0, 2).contiguous().cpu()  # [B, steps, V]
+    return [api.det_commit_sha256(p_host[b, :lens[b]].contiguous(), l_host[b], g_host[b]) for b in range(B)]

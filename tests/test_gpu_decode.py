@@ -145,3 +145,37 @@ def test_prefill_rows_match_token_by_token(model, prompts):
     assert np.array_equal(alone.cpu().numpy()[0], ref.cpu().numpy()[13 - 8])
     four, _ = prefill_decode(model, up(toks[[20, 9, 13, 16]]), up(lens[[20, 9, 13, 16]]), n_new, cos_d, sin_d)
     assert np.array_equal(four.cpu().numpy(), ref.cpu().numpy()[[12, 1, 5, 8]])
+
+
+def test_receipts_identical_across_batchings(model, prompts, orc):
+    """The paper's end-to-end check (section 6.7) in its own terms: the per-execution digest
+    SHA256(prompt || logits || tokens) of a prompt is the same whether it runs alone or in any batch,
+    equals the oracle's hash of the same downloaded bytes, and differs between prompts."""
+    from paper_2602_00182_amd.decode import commit_outputs, prefill_decode
+
+    toks, lens = prompts
+    n_new = 12
+    cos_t, sin_t = ds.rope_tables(512 + n_new, D, 5.0e5)
+    cos_d, sin_d = up(cos_t), up(sin_t)
+
+    def run(ids):
+        ids = list(ids)
+        p, l = up(toks[ids]), up(lens[ids])
+        gen, logits = prefill_decode(model, p, l, n_new, cos_d, sin_d, keep_logits=True)
+        torch.cuda.synchronize()
+        return commit_outputs(p, l, logits, gen), gen.cpu().numpy(), [x.cpu().numpy() for x in logits]
+
+    step("receipts, 12 prompts in one batch")
+    ids = list(range(30, 42))
+    full, gen, logits = run(ids)
+    assert len(set(full)) == len(full), "digests should differ between prompts"
+    for b, i in enumerate(ids):
+        want = orc.commit_sha256(toks[i, :lens[i]].astype("<i4").tobytes(),
+                                 np.stack([x[b] for x in logits]).astype("<f4").tobytes(),
+                                 gen[b].astype("<i4").tobytes())
+        assert full[b] == want
+    step("receipts, the same batch again")
+    assert run(ids)[0] == full
+    step("receipts, batch of 3 and one prompt alone")
+    assert run([41, 30, 35])[0] == [full[11], full[0], full[5]]
+    assert run([33])[0] == [full[3]]
