@@ -252,6 +252,42 @@ def sample(logits, temperature: float, top_k: int, top_p: float, seed: int, seq_
     return out
 
 
+def quant_w4(w_bits) -> tuple[np.ndarray, np.ndarray]:
+    """Weight quantizer: W bf16 bits [K,N] -> (q int8 [K,N] in -8..7, s bf16 bits [K/64,N])."""
+    w = _u16(w_bits)
+    K, N = w.shape
+    assert K % 64 == 0
+    q = np.empty((K, N), dtype=np.int8)
+    s = np.empty((K // 64, N), dtype=np.uint16)
+    lib().orc_quant_w4(_p(w), C.c_int(K), C.c_int(N), _p(q), _p(s))
+    return q, s
+
+
+def quant_a8(a_bits) -> tuple[np.ndarray, np.ndarray]:
+    """Activation quantizer: A bf16 bits [M,K] -> (p int8 [M,K] in -127..127, d fp32 [M,K/64])."""
+    a = _u16(a_bits)
+    M, K = a.shape
+    assert K % 64 == 0
+    p = np.empty((M, K), dtype=np.int8)
+    d = np.empty((M, K // 64), dtype=np.float32)
+    lib().orc_quant_a8(_p(a), C.c_int(K), C.c_int(M), C.c_int(K), _p(p), _p(d))
+    return p, d
+
+
+def qgemm_w4a8(p, d, q, s) -> tuple[np.ndarray, np.ndarray]:
+    """Quantized GEMM on quantized operands -> (acc fp32 [M,N], C bf16 bits [M,N]), bit-exact reference."""
+    p = np.ascontiguousarray(p, dtype=np.int8)
+    q = np.ascontiguousarray(q, dtype=np.int8)
+    d, s = _f32(d), _u16(s)
+    M, K = p.shape
+    N = q.shape[1]
+    assert q.shape == (K, N) and d.shape == (M, K // 64) and s.shape == (K // 64, N)
+    acc = np.empty((M, N), dtype=np.float32)
+    c = np.empty((M, N), dtype=np.uint16)
+    lib().orc_qgemm_w4a8(_p(p), _p(d), _p(q), _p(s), C.c_int(M), C.c_int(N), C.c_int(K), _p(acc), _p(c))
+    return acc, c
+
+
 def commit_sha256(prompt: bytes, logits: bytes, tokens: bytes) -> bytes:
     """The digest the paper records per execution (section 6.7): SHA-256 of the three byte strings
     concatenated in that order.  The hash itself is the standard library's (a library primitive as a

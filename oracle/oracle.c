@@ -12,7 +12,7 @@
  *      section 6.7, Table 4).
  *   X  bit-exact references: an fp32 emulation, step by step, of the canonical reduction order
  *      (RMSNorm, softmax statistics, argmax, det_expf, bf16 rounding, RoPE, SwiGLU, residual,
- *      seeded sampling).
+ *      seeded sampling, the quantizers and the quantized GEMM, whose contraction is integer).
  *
  * The canonical order follows the paper's three kernel invariants (section 6.5): a fixed mapping
  * of work to threads, a stride-halving binary-tree reduction (the four-line shuffle loop of
@@ -557,6 +557,93 @@ void orc_sample(const float *logits, int B, int V, float temperature, int top_k,
 }
 
 /* Threads the parallel loops above will use (reported with the CPU baseline). */
+/* ---------------------------------------------------------------------------------------------
+ * Deterministic quantized GEMM (the paper's primary kernel family is the quantized one: section
+ * 6.4 names the quantized warp-synchronous kernels of its engine, Table 5 measures them).  The
+ * paper gives no format; this one is defined here, integer where it can be so that the whole
+ * operation has a bit-exact reference (X):
+ *
+ *   weights, block = 64 consecutive k of one column:  amax = max |w|;  s = bf16(amax / 7);
+ *       q_k = clamp(rint(w_k / s), -8, 7)  (0 if s == 0);            w_k ~ s * q_k
+ *   activations, block = 64 consecutive k of one row: amax = max |a|;  d = amax / 127 (fp32);
+ *       p_k = clamp(rint(a_k / d), -127, 127)  (0 if d == 0);        a_k ~ d * p_k
+ *   C[i][n] = bf16( acc ),  acc = 0;  for b = 0 .. K/64-1 ascending:
+ *       P = sum_{k in block b} p_k * q_k            (int32, exact, any order)
+ *       acc = fmaf( d[i][b] * s[b][n], (float)P, acc )     (one rounded multiply, one fma)
+ *
+ * All divisions and multiplies are IEEE fp32, rint is round-to-nearest-even.  NaN/Inf inputs and
+ * blocks whose amax is denormal are unspecified.
+ */
+void orc_quant_w4(const uint16_t *W, int K, int N, int8_t *q, uint16_t *s)
+{
+    const int nb = K / 64;
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int b = 0; b < nb; ++b) {
+            float amax = 0.0f;
+            for (int k = 64 * b; k < 64 * b + 64; ++k) {
+                const float a = fabsf(orc_bf16_to_f32(W[(size_t)k * N + n]));
+                if (a > amax) amax = a;
+            }
+            const uint16_t sb = orc_bf16_rne(amax / 7.0f);
+            const float sf = orc_bf16_to_f32(sb);
+            s[(size_t)b * N + n] = sb;
+            for (int k = 64 * b; k < 64 * b + 64; ++k) {
+                int v = 0;
+                if (sf != 0.0f) {
+                    const float r = nearbyintf(orc_bf16_to_f32(W[(size_t)k * N + n]) / sf);
+                    v = r < -8.0f ? -8 : (r > 7.0f ? 7 : (int)r);
+                }
+                q[(size_t)k * N + n] = (int8_t)v;
+            }
+        }
+}
+
+void orc_quant_a8(const uint16_t *A, int lda, int M, int K, int8_t *p, float *d)
+{
+    const int nb = K / 64;
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < M; ++i)
+        for (int b = 0; b < nb; ++b) {
+            float amax = 0.0f;
+            for (int k = 64 * b; k < 64 * b + 64; ++k) {
+                const float a = fabsf(orc_bf16_to_f32(A[(size_t)i * lda + k]));
+                if (a > amax) amax = a;
+            }
+            const float df = amax / 127.0f;
+            d[(size_t)i * nb + b] = df;
+            for (int k = 64 * b; k < 64 * b + 64; ++k) {
+                int v = 0;
+                if (df != 0.0f) {
+                    const float r = nearbyintf(orc_bf16_to_f32(A[(size_t)i * lda + k]) / df);
+                    v = r < -127.0f ? -127 : (r > 127.0f ? 127 : (int)r);
+                }
+                p[(size_t)i * K + k] = (int8_t)v;
+            }
+        }
+}
+
+/* p [M,K], d [M,K/64], q [K,N], s [K/64,N]  ->  acc fp32 [M,N] and its bf16 rounding c [M,N] */
+void orc_qgemm_w4a8(const int8_t *p, const float *d, const int8_t *q, const uint16_t *s, int M, int N,
+                    int K, float *acc_out, uint16_t *c)
+{
+    const int nb = K / 64;
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < M; ++i)
+        for (int n = 0; n < N; ++n) {
+            float acc = 0.0f;
+            for (int b = 0; b < nb; ++b) {
+                int32_t P = 0;
+                for (int k = 64 * b; k < 64 * b + 64; ++k)
+                    P += (int32_t)p[(size_t)i * K + k] * (int32_t)q[(size_t)k * N + n];
+                const float scale = d[(size_t)i * nb + b] * orc_bf16_to_f32(s[(size_t)b * N + n]);
+                acc = fmaf(scale, (float)P, acc);
+            }
+            acc_out[(size_t)i * N + n] = acc;
+            c[(size_t)i * N + n] = orc_bf16_rne(acc);
+        }
+}
+
 int orc_num_threads(void)
 {
 #ifdef _OPENMP
