@@ -175,6 +175,7 @@ def main():
         torch.cuda.empty_cache()
         result["attention"] = attention_numbers(torch, det, ds, dev)
         result["decode"] = decode_numbers(torch, det, ds, dev)
+        result["qgemm_w4a8"] = qgemm_numbers(torch, det, ds, dev)
     print(json.dumps(result))
 
 
@@ -280,6 +281,40 @@ def attention_numbers(torch, det, ds, dev):
                          "frac_hbm": round(by / us / 1e3 / PEAK_HBM_GBS, 4), "kv_mb": round(by / 1e6, 1)})
             del k, v, ws
             torch.cuda.empty_cache()
+    return rows
+
+
+def qgemm_numbers(torch, det, ds, dev):
+    """Block-quantized GEMM (4-bit weights, 8-bit activations) on the same shapes, weights rotating over
+    3 packed sets (HBM-cold).  us = det_qgemm_w4a8 alone, us_quant = det_quant_act_q8 of the M rows;
+    bytes = packed weights (4.25 bits each) + activation codes and scales + bf16 output."""
+    rows = []
+    for (K, N) in SHAPES + [(2048, 32000)]:
+        packs = [det.quant_pack_weight(ds.normal_bf16_torch(ds.tensor_seed(7, 10 * s + 1), (K, N), 0.02, 0.0, dev))
+                 for s in range(3)]
+        x = ds.normal_bf16_torch(ds.tensor_seed(7, 2), (256, K), 1.0, 0.0, dev)
+        c = torch.empty((256, N), dtype=torch.bfloat16, device=dev)
+        for M in (1, 16, 64, 256):
+            codes, scales = det.quant_activations(x[:M])
+            for i in range(3):
+                det.det_qgemm_w4a8(codes, scales, packs[i], c[:M], N)
+            torch.cuda.synchronize()
+            e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+            e0.record()
+            for i in range(12):
+                det.det_qgemm_w4a8(codes, scales, packs[i % 3], c[:M], N)
+            e1.record()
+            for i in range(12):
+                det.det_quant_act_q8(x[:M], codes, scales)
+            e2.record()
+            torch.cuda.synchronize()
+            us, usq = e0.elapsed_time(e1) / 12 * 1e3, e1.elapsed_time(e2) / 12 * 1e3
+            by = det.det_qgemm_packed_w_bytes(N, K) + M * K + 4 * M * (K // 64) + 2 * M * N
+            rows.append({"K": K, "N": N, "M": M, "us": round(us, 1), "us_quant": round(usq, 1),
+                         "gbs": round(by / us / 1e3, 1), "tflops": round(gemm_flops(M, N, K) / us / 1e6, 1),
+                         "packed_mb": round(det.det_qgemm_packed_w_bytes(N, K) / 1e6, 1)})
+        del packs
+        torch.cuda.empty_cache()
     return rows
 
 

@@ -249,6 +249,39 @@ int det_next_token(const int32_t *prompts, int Tp, const int32_t *prompt_lens,
                    int32_t *history, int Th, int t, int B, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Deterministic block-quantized GEMM (the paper's primary kernel family is the quantized one, section
+ * 6.4 and Table 5; it gives no format, so one is defined here).
+ *
+ *   weights, block = 64 consecutive k of one column:   amax = max|w|; s = bf16(amax / 7);
+ *       q = clamp(rint(w / s), -8, 7), 0 if s == 0                      (4-bit code, bf16 scale)
+ *   activations, block = 64 consecutive k of one row:  amax = max|a|; d = amax / 127 (fp32);
+ *       p = clamp(rint(a / d), -127, 127), 0 if d == 0                  (8-bit code, fp32 scale)
+ *   C[i][n] = bf16(acc) (or acc as fp32), acc = 0; for blocks b ascending:
+ *       acc = fma( d[i][b] * s[b][n], (float)(sum over the block of p*q, int32), acc )
+ *   All of it IEEE fp32 with round-to-nearest-even; the result is a pure function of the operand
+ *   bytes and is reproduced bit for bit by a plain CPU implementation.  NaN/Inf inputs and blocks
+ *   whose largest magnitude is denormal are unspecified.
+ *
+ * det_quant_pack_w4: one-time; B_kn is bf16 row-major [K,N]; `packed` (det_qgemm_packed_w_bytes
+ * bytes, 16-byte aligned, 4.25 bits per weight) is in the kernel's streaming order.  N % 16 == 0,
+ * K % 64 == 0, else DET_ESHAPE.  det_quant_unpack_w4 is a test hook: codes int8 [K,N] and scales bf16
+ * [K/64,N] back out of a packed matrix.
+ * det_quant_act_q8: A bf16 [M,K] with row stride lda -> codes (det_quant_act_codes_bytes: int8
+ * [M,K]) and scales (det_quant_act_scales_bytes: fp32, block-major with row stride (M+3)&~3, so a
+ * test reads scale (i, b) at scales[b * ((M+3)&~3) + i]); both 16-byte aligned.
+ * det_qgemm_w4a8: C [M,N] with row stride ldc (ldc % 4 == 0), out_dtype DET_BF16 or DET_F32; codes and
+ * scales as written by det_quant_act_q8 for the same M and K.  Device pointers; work is enqueued on
+ * `stream`. */
+size_t det_qgemm_packed_w_bytes(int N, int K);
+int det_quant_pack_w4(const void *B_kn, void *packed, int N, int K, void *stream);
+int det_quant_unpack_w4(const void *packed, void *codes, void *scales, int N, int K, void *stream);
+size_t det_quant_act_codes_bytes(int M, int K);
+size_t det_quant_act_scales_bytes(int M, int K);
+int det_quant_act_q8(const void *A, int lda, void *codes, void *scales, int M, int K, void *stream);
+int det_qgemm_w4a8(const void *codes, const void *scales, const void *packed_w, void *C, int ldc, int M,
+                   int N, int K, int out_dtype, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Output commitment (the paper's section 6.7 records SHA256(prompt || logits || tokens) for every
  * execution, and a receipt commits to the output by its hash, section 4.1).  HOST code on HOST
  * pointers: SHA-256 (FIPS 180-4) is a serial chain, so the caller copies what it wants committed

@@ -51,6 +51,13 @@ SIGNATURES = {
     "det_decoder_layer_rows": (_i, [C.POINTER(LayerWeights), C.POINTER(LayerCfg), _vp, _vp, _vp, _vp, _vp, _vp, _vp,
                                     _vp, _sz, _i, _vp]),
     "det_next_token": (_i, [_vp, _i, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _vp]),
+    "det_qgemm_packed_w_bytes": (_sz, [_i, _i]),
+    "det_quant_pack_w4": (_i, [_vp, _vp, _i, _i, _vp]),
+    "det_quant_unpack_w4": (_i, [_vp, _vp, _vp, _i, _i, _vp]),
+    "det_quant_act_codes_bytes": (_sz, [_i, _i]),
+    "det_quant_act_scales_bytes": (_sz, [_i, _i]),
+    "det_quant_act_q8": (_i, [_vp, _i, _vp, _vp, _i, _i, _vp]),
+    "det_qgemm_w4a8": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp]),
     "det_sha256_init": (_i, [C.POINTER(Sha256Ctx)]),
     "det_sha256_update": (_i, [C.POINTER(Sha256Ctx), _vp, _sz]),
     "det_sha256_final": (_i, [C.POINTER(Sha256Ctx), _vp]),

@@ -18,7 +18,9 @@ __all__ = [
     "det_swiglu", "det_residual_add", "det_embed_gather", "det_decoder_layer_workspace_bytes",
     "det_decoder_layer", "det_next_token", "det_fingerprint", "det_last_hip_error", "layer_cfg",
     "layer_weights", "pack_weight", "det_sha256_init", "det_sha256_update", "det_sha256_final",
-    "det_commit_sha256", "det_sha256_force_portable",
+    "det_commit_sha256", "det_sha256_force_portable", "det_qgemm_packed_w_bytes", "det_quant_pack_w4",
+    "det_quant_unpack_w4", "det_quant_act_codes_bytes", "det_quant_act_scales_bytes", "det_quant_act_q8",
+    "det_qgemm_w4a8", "quant_pack_weight", "quant_activations",
 ]
 
 _CODES = {1: "DET_EINVAL", 2: "DET_ESHAPE", 3: "DET_EALIGN", 4: "DET_EWORKSPACE", 5: "DET_EHIP"}
@@ -54,6 +56,69 @@ def _contig(t: torch.Tensor, dtype=None) -> int:
 def _stream(stream) -> int:
     s = torch.cuda.current_stream() if stream is None else stream
     return s.cuda_stream
+
+
+def det_qgemm_packed_w_bytes(N: int, K: int) -> int:
+    return lib().det_qgemm_packed_w_bytes(N, K)
+
+
+def det_quant_pack_w4(b_kn, packed, stream=None) -> None:
+    K, N = b_kn.shape
+    if packed.numel() * packed.element_size() < det_qgemm_packed_w_bytes(N, K):
+        raise ValueError("packed buffer too small")
+    _check("det_quant_pack_w4", lib().det_quant_pack_w4(_contig(b_kn, torch.bfloat16), _contig(packed), N, K,
+                                                          _stream(stream)))
+
+
+def det_quant_unpack_w4(packed, codes, scales, stream=None) -> None:
+    K, N = codes.shape
+    if scales.shape != (K // 64, N):
+        raise ValueError("bad shapes")
+    _check("det_quant_unpack_w4", lib().det_quant_unpack_w4(_contig(packed), _contig(codes, torch.int8),
+                                                              _contig(scales, torch.bfloat16), N, K, _stream(stream)))
+
+
+def det_quant_act_codes_bytes(M: int, K: int) -> int:
+    return lib().det_quant_act_codes_bytes(M, K)
+
+
+def det_quant_act_scales_bytes(M: int, K: int) -> int:
+    return lib().det_quant_act_scales_bytes(M, K)
+
+
+def det_quant_act_q8(a, codes, scales, stream=None) -> None:
+    M, K = a.shape
+    if a.stride(1) != 1 or codes.shape != (M, K) or scales.numel() * 4 < det_quant_act_scales_bytes(M, K):
+        raise ValueError("bad shapes")
+    _check("det_quant_act_q8", lib().det_quant_act_q8(_ptr(a, torch.bfloat16), a.stride(0), _contig(codes, torch.int8),
+                                                        _contig(scales, torch.float32), M, K, _stream(stream)))
+
+
+def det_qgemm_w4a8(codes, scales, packed_w, c, N: int, stream=None) -> None:
+    M, K = codes.shape
+    if c.shape != (M, N) or c.stride(1) != 1:
+        raise ValueError("bad output shape")
+    out_dtype = {torch.bfloat16: DET_BF16, torch.float32: DET_F32}[c.dtype]
+    _check("det_qgemm_w4a8", lib().det_qgemm_w4a8(_contig(codes, torch.int8), _contig(scales, torch.float32),
+                                                    _contig(packed_w), _ptr(c), c.stride(0), M, N, K, out_dtype,
+                                                    _stream(stream)))
+
+
+def quant_pack_weight(b_kn: torch.Tensor) -> torch.Tensor:
+    """Allocates the packed 4-bit matrix for a bf16 weight [K,N] and fills it (det_quant_pack_w4)."""
+    K, N = b_kn.shape
+    packed = torch.empty(det_qgemm_packed_w_bytes(N, K), dtype=torch.uint8, device=b_kn.device)
+    det_quant_pack_w4(b_kn.contiguous(), packed)
+    return packed
+
+
+def quant_activations(a: torch.Tensor):
+    """Allocates codes and scales for a bf16 activation matrix [M,K] and fills them (det_quant_act_q8)."""
+    M, K = a.shape
+    codes = torch.empty((M, K), dtype=torch.int8, device=a.device)
+    scales = torch.empty(det_quant_act_scales_bytes(M, K) // 4, dtype=torch.float32, device=a.device)
+    det_quant_act_q8(a, codes, scales)
+    return codes, scales
 
 
 def _host_bytes(data):

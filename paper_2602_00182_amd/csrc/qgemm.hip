@@ -1,0 +1,461 @@
+// Deterministic block-quantized GEMM for gfx950 (the paper's primary kernel family is the quantized
+// one, section 6.4; its format is not given, this one is defined here):
+//
+//   weights      4-bit codes q in -8..7 and a bf16 scale s per 64 consecutive k of a column
+//   activations  8-bit codes p in -127..127 and an fp32 scale d per 64 consecutive k of a row
+//   C[i][n] = bf16(acc),  acc = 0;  for b ascending:  acc = fma( d[i][b]*s[b][n], float(P), acc ),
+//   P = sum over the block of p*q in int32 (exact: v_mfma_i32_16x16x64_i8, one instruction per block)
+//
+// Every floating-point operation of the definition is an individually rounded IEEE fp32 operation
+// in a written order and the contraction is integer, so a CPU reproduces the bytes exactly.
+// Batch invariance follows as for the bf16 kernel: an output element's chain never depends on M.
+//
+// Kernel shape: as the bf16 GEMM (gemm.hip) -- a workgroup owns 16*CB columns and up to 256 rows,
+// K in 64-deep stages streamed through an LDS ring by waves that only load -- with two differences.
+// Weights arrive packed (544*CB bytes a stage: for each 16-column block, 8 bytes a lane of codes in
+// matrix-core operand order, then 16 scales), so a chunk's weights are one contiguous run copied as
+// it lies.  And the eight computing waves split the tile by column block first (wave w: column block
+// w % CB, row blocks w / CB, w / CB + 8/CB, ...): at small M the work per stage is the unpacking of
+// the codes, which a single wave could not do at the rate the weights stream in.
+#include <type_traits>
+
+#include "common.h"
+#include "stream.h"
+
+namespace det {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+constexpr int kQRing = 144;   // KB of LDS ring
+constexpr int kQWaves = 8;    // waves that can compute
+constexpr int kQLoaders = 4;  // waves that only load
+
+// Columns-per-workgroup factor: the largest of 8, 4, 2, 1 that divides N/16 and leaves at least 192
+// workgroups; 1 if there is none.
+int qgemm_cols_per_block(int N)
+{
+    const int nb = N / 16;
+    for (int cb = 8; cb > 1; cb >>= 1)
+        if (nb % cb == 0 && nb / cb >= 192) return cb;
+    return 1;
+}
+
+__host__ __device__ constexpr int qstage_w_bytes(int cb) { return 544 * cb; }
+
+// ------------------------------------------------------------------------------------------------
+// Weight quantizer + packer: one thread per (block b, column n).
+// Packed layout: workgroup slab (16*cb columns) major, then stage; inside a stage, for column block
+// j: 64 lanes x 8 bytes at j*512 (lane = 16*g + column%16 holds the codes of k = 16g .. 16g+15 of the
+// stage: dword t = 0,1, byte i = 0..3: low nibble = code of k = 16g + 8t + i, high nibble = code of
+// k = 16g + 8t + 4 + i, each stored as q + 8); then at 512*cb the scales, 16 bf16 per column block.
+__global__ __launch_bounds__(256) void quant_pack_w4_kernel(const uint16_t* __restrict__ W, uint8_t* __restrict__ packed,
+                                                            int N, int K, int cb)
+{
+    const int nblk = K >> 6;
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (size_t)nblk * N) return;
+    const int n = (int)(idx % N), b = (int)(idx / N);
+    float w[64];
+    float amax = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 64; ++k) {
+        w[k] = bf16_to_f32(W[(size_t)(64 * b + k) * N + n]);
+        amax = fmaxf(amax, fabsf(w[k]));
+    }
+    const uint16_t sb = f32_to_bf16_rne(amax / 7.0f);
+    const float sf = bf16_to_f32(sb);
+    const int slab = n / (16 * cb), j = (n >> 4) % cb, c = n & 15;
+    uint8_t* stage = packed + ((size_t)slab * nblk + b) * qstage_w_bytes(cb);
+    uint32_t u[64];
+#pragma unroll
+    for (int k = 0; k < 64; ++k) {
+        int v = 0;
+        if (sf != 0.0f) {
+            const float r = rintf(w[k] / sf);
+            v = r < -8.0f ? -8 : (r > 7.0f ? 7 : (int)r);
+        }
+        u[k] = (uint32_t)(v + 8);
+    }
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        uint32_t dw[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            uint32_t x = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) x |= (u[16 * g + 8 * t + i] | (u[16 * g + 8 * t + 4 + i] << 4)) << (8 * i);
+            dw[t] = x;
+        }
+        *reinterpret_cast<uint2*>(stage + j * 512 + (16 * g + c) * 8) = make_uint2(dw[0], dw[1]);
+    }
+    *reinterpret_cast<uint16_t*>(stage + 512 * cb + j * 32 + c * 2) = sb;
+}
+
+// Test hook: the packed matrix back to logical codes q [K,N] (int8) and scales s [K/64,N] (bf16).
+__global__ __launch_bounds__(256) void quant_unpack_w4_kernel(const uint8_t* __restrict__ packed, int8_t* __restrict__ q,
+                                                              uint16_t* __restrict__ s, int N, int K, int cb)
+{
+    const int nblk = K >> 6;
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (size_t)nblk * N) return;
+    const int n = (int)(idx % N), b = (int)(idx / N);
+    const int slab = n / (16 * cb), j = (n >> 4) % cb, c = n & 15;
+    const uint8_t* stage = packed + ((size_t)slab * nblk + b) * qstage_w_bytes(cb);
+    for (int g = 0; g < 4; ++g) {
+        const uint2 d = *reinterpret_cast<const uint2*>(stage + j * 512 + (16 * g + c) * 8);
+        const uint32_t dw[2] = {d.x, d.y};
+        for (int t = 0; t < 2; ++t)
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t byte = (dw[t] >> (8 * i)) & 0xFFu;
+                q[(size_t)(64 * b + 16 * g + 8 * t + i) * N + n] = (int8_t)((int)(byte & 15u) - 8);
+                q[(size_t)(64 * b + 16 * g + 8 * t + 4 + i) * N + n] = (int8_t)((int)(byte >> 4) - 8);
+            }
+    }
+    s[(size_t)b * N + n] = *reinterpret_cast<const uint16_t*>(stage + 512 * cb + j * 32 + c * 2);
+}
+
+// Activation quantizer: one wave per (row, 64-k block); grid (blocks/4, M).  p [M,K] int8 row-major;
+// d stored block-major, d[b*ldd + i], so that the scales of a tile's rows for one stage are contiguous.
+__global__ __launch_bounds__(256) void quant_act_q8_kernel(const uint16_t* __restrict__ A, int lda, int8_t* __restrict__ p,
+                                                           float* __restrict__ d, int ldd, int K)
+{
+    const int i = blockIdx.y, lane = threadIdx.x & 63;
+    const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (b >= (K >> 6)) return;
+    const float a = bf16_to_f32(A[(size_t)i * lda + 64 * b + lane]);
+    float amax = fabsf(a);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
+    const float df = amax / 127.0f;
+    int v = 0;
+    if (df != 0.0f) {
+        const float r = rintf(a / df);
+        v = r < -127.0f ? -127 : (r > 127.0f ? 127 : (int)r);
+    }
+    p[(size_t)i * K + 64 * b + lane] = (int8_t)v;
+    if (lane == 0) d[(size_t)b * ldd + i] = df;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Schedule of one 256-row tile, worked out on the host (see gemm.hip).
+struct qgemm_plan {
+    int mrem, RB;
+    int SPC;         // stages per chunk
+    int slot_bytes;  // bytes of a ring slot
+    int nslots, nchunks, last_cnt;
+    int ncomp;       // waves that compute: CB * min(8/CB, RB)
+    int nload;
+    uint32_t inv_nload;  // floor(2^20/nload)+1
+};
+
+static int q_wrun_bytes(int s_cnt, int cb) { return (s_cnt * qstage_w_bytes(cb) + 1023) & ~1023; }
+
+static qgemm_plan make_qgemm_plan(int mrem, int cb, int K)
+{
+    qgemm_plan t;
+    t.mrem = mrem;
+    t.RB = (mrem + 15) >> 4;
+    const int stage = qstage_w_bytes(cb) + 1024 * t.RB + 1024;
+    const int third = kQRing * 1024 / 3;
+    t.SPC = 1;  // the most stages whose chunk fits a third of the ring
+    while (q_wrun_bytes(t.SPC + 1, cb) + (t.SPC + 1) * (1024 * t.RB + 1024) <= third) ++t.SPC;
+    t.slot_bytes = q_wrun_bytes(t.SPC, cb) + t.SPC * (1024 * t.RB + 1024);
+    (void)stage;
+    t.nslots = kQRing * 1024 / t.slot_bytes < 4 ? kQRing * 1024 / t.slot_bytes : 4;
+    const int nstages = K >> 6;
+    t.nchunks = (nstages + t.SPC - 1) / t.SPC;
+    t.last_cnt = nstages - (t.nchunks - 1) * t.SPC;
+    const int rg = 8 / cb;
+    t.ncomp = cb * (rg < t.RB ? rg : t.RB);
+    t.nload = kQWaves + kQLoaders - t.ncomp;
+    t.inv_nload = (1u << 20) / (uint32_t)t.nload + 1u;
+    return t;
+}
+
+template <int CB>
+__global__ __launch_bounds__(64 * (kQWaves + kQLoaders)) void qgemm_kernel(
+    const int8_t* __restrict__ qa, int K, const float* __restrict__ da, int ldd, const uint8_t* __restrict__ wp, void* C,
+    int ldc, int out_f32, qgemm_plan plan_full, qgemm_plan plan_tail)
+{
+    __shared__ uint4 ring[kQRing * 64];
+    constexpr int RG = 8 / CB;        // row groups: wave w computes column block w % CB for row group w / CB
+    constexpr int MAXR = 16 / RG;     // most row blocks a wave can own
+    constexpr int WST = qstage_w_bytes(CB);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4, lr = lane & 15;
+    const int m0 = blockIdx.y * 256;
+    const qgemm_plan& tp = blockIdx.y + 1 == gridDim.y ? plan_tail : plan_full;
+    const int mrem = tp.mrem, RB = tp.RB, SPC = tp.SPC, nslots = tp.nslots, nchunks = tp.nchunks;
+    const int P = nslots - 1;
+    const int nstages = K >> 6;
+    const uint32_t ring_addr = (uint32_t)(uintptr_t)(lds_char_t*)ring;
+    auto chunk_stages = [&](int c) { return c < nchunks - 1 ? SPC : (c == nchunks - 1 ? tp.last_cnt : 0); };
+    // LDS layout of a chunk of s_cnt stages: the weight run (s_cnt*WST bytes as they lie in memory,
+    // rounded up to 1 KB), then s_cnt*RB activation tiles of 1 KB (stage, row block: 16 rows x 64
+    // codes, the four 16-byte pieces of row i swizzled: piece t at slot t ^ ((i/4)%4)), then s_cnt
+    // blocks of 1 KB with the activation scales of the tile's rows for the stage.
+    auto wrun = [&](int s_cnt) { return (uint32_t)((s_cnt * WST + 1023) & ~1023); };
+
+    if (wave >= tp.ncomp) {
+        // ---------------------------------------------------------------- loading wave
+        const int nload = tp.nload, lrank = wave - tp.ncomp;
+        const char* wbytes = reinterpret_cast<const char*>(wp) + (size_t)blockIdx.x * nstages * WST;
+        const char* abytes = reinterpret_cast<const char*>(qa) + (size_t)m0 * K;
+        const char* dbytes = reinterpret_cast<const char*>(da + m0);
+        const uint32_t lane16 = (uint32_t)lane * 16u;
+        const int lrow = lane >> 2;  // row of this lane inside an activation tile
+        const uint32_t a_lane_off = (uint32_t)lrow * (uint32_t)K + 16u * (uint32_t)((lane & 3) ^ ((lane >> 4) & 3));
+        auto strided = [&](int n) { return n > lrank ? (int)(((uint32_t)(n - lrank + nload - 1) * tp.inv_nload) >> 20) : 0; };
+        auto loads_for = [&](int s_cnt) {
+            return strided((int)(wrun(s_cnt) >> 10)) + strided(s_cnt * RB) + strided(s_cnt);
+        };
+        const int loads_full = loads_for(SPC), loads_last = loads_for(tp.last_cnt);
+        auto wave_loads = [&](int c) { return c < nchunks - 1 ? loads_full : (c == nchunks - 1 ? loads_last : 0); };
+
+        auto load_chunk = [&](int c, int slot_idx) {
+            const int s_cnt = chunk_stages(c);
+            if (s_cnt == 0) return;
+            const int s0 = c * SPC;
+            const uint32_t slot_addr = ring_addr + (uint32_t)slot_idx * (uint32_t)tp.slot_bytes;
+            // weight run: 1 KB units of a contiguous byte range; the last unit may be short
+            const uint32_t wlen = (uint32_t)(s_cnt * WST);
+            const int nwu = (int)(wrun(s_cnt) >> 10);
+            const char* wsrc = wbytes + (size_t)s0 * WST;
+            for (int u = lrank; u < nwu; u += nload) {
+                const uint32_t off = (uint32_t)u << 10;
+                if (off + lane16 < wlen) dma_block(wsrc + off, lane16, slot_addr + off);
+            }
+            // activation tiles: unit (stage, row block); rows past M load nothing
+            const uint32_t tiles = slot_addr + wrun(s_cnt);
+            int sl = 0, rb = lrank;
+            while (rb >= RB) {
+                rb -= RB;
+                ++sl;
+            }
+            const int nt = s_cnt * RB;
+            for (int u = lrank; u < nt; u += nload) {
+                if (16 * rb + lrow < mrem)
+                    dma_block(abytes + (size_t)(16 * rb) * K + ((size_t)(s0 + sl) << 6), a_lane_off, tiles + ((uint32_t)u << 10));
+                rb += nload;
+                while (rb >= RB) {
+                    rb -= RB;
+                    ++sl;
+                }
+            }
+            // activation scales: one unit per stage, 4 rows a lane
+            const uint32_t scales = tiles + ((uint32_t)nt << 10);
+            for (int u = lrank; u < s_cnt; u += nload)
+                if (4 * lane < mrem) dma_block(dbytes + (size_t)(s0 + u) * ldd * 4, lane16, scales + ((uint32_t)u << 10));
+        };
+
+        for (int c = 0; c < P; ++c) load_chunk(c, c);
+        const int younger_steady = (P - 1) * loads_full;
+        int slot_c = 0, slot_new = P;
+        for (int c = 0; c < nchunks; ++c) {
+            int younger = younger_steady;
+            if (c + P > nchunks - 1) {
+                younger = 0;
+                for (int dd = 1; dd < P; ++dd) younger += wave_loads(c + dd);
+            }
+            wait_loads_then_barrier(younger);
+            load_chunk(c + P, slot_new);
+            slot_new = slot_c;
+            slot_c = slot_c + 1 == nslots ? 0 : slot_c + 1;
+        }
+        return;
+    }
+
+    // -------------------------------------------------------------------- computing wave
+    const int j = wave % CB, rg = wave / CB;       // column block and row group of the wave
+    const int cnt = (RB - rg + RG - 1) / RG;       // its row blocks: rg, rg + RG, ... (cnt >= 1 here)
+
+    auto run = [&](auto nr_tag) {
+        constexpr int NR = decltype(nr_tag)::value;  // cnt rounded up to a power of two; the surplus
+                                                     // repeats the last row block and is not stored
+        float acc[NR][4];
+#pragma unroll
+        for (int r = 0; r < NR; ++r)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[r][v] = 0.0f;
+        int rbs[NR];
+#pragma unroll
+        for (int r = 0; r < NR; ++r) rbs[r] = rg + RG * (r < cnt ? r : cnt - 1);
+
+        int slot_c = 0;
+        for (int c = 0; c < nchunks; ++c) {
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            const int s_cnt = chunk_stages(c);
+            const char* slot = reinterpret_cast<const char*>(ring) + (size_t)slot_c * tp.slot_bytes;
+            const char* tiles = slot + wrun(s_cnt);
+            const char* scales = tiles + ((size_t)(s_cnt * RB) << 10);
+            // UU stages at a time: all their LDS reads and matrix-core instructions first, so that the
+            // latencies overlap, then the scaling chain of each output in ascending stage order
+            auto stages = [&](int sl, auto uu_tag) {
+                constexpr int UU = decltype(uu_tag)::value;
+                constexpr int G = NR < 4 ? NR : 4;  // row blocks at a time
+                auto expand = [](uint32_t x) { return (((x & 0x0F0F0F0Fu) | 0x80808080u) - 0x08080808u) ^ 0x80808080u; };
+                v4i wq[UU];
+                float sc[UU][4];
+#pragma unroll
+                for (int u = 0; u < UU; ++u) {
+                    const char* wst = slot + (sl + u) * WST;
+                    const uint2 codes = *reinterpret_cast<const uint2*>(wst + j * 512 + lane * 8);
+                    const uint2 sraw = *reinterpret_cast<const uint2*>(wst + 512 * CB + j * 32 + g * 8);
+                    // 16 codes -> 16 signed bytes: per byte (u | 0x80) - 8, then the top bit flipped back
+                    wq[u][0] = (int)expand(codes.x);
+                    wq[u][1] = (int)expand(codes.x >> 4);
+                    wq[u][2] = (int)expand(codes.y);
+                    wq[u][3] = (int)expand(codes.y >> 4);
+                    sc[u][0] = bf16lo_to_f32(sraw.x);
+                    sc[u][1] = bf16hi_to_f32(sraw.x);
+                    sc[u][2] = bf16lo_to_f32(sraw.y);
+                    sc[u][3] = bf16hi_to_f32(sraw.y);
+                }
+#pragma unroll
+                for (int r0 = 0; r0 < NR; r0 += G) {
+                    v4i pr[UU][G];
+                    float dv[UU][G];
+#pragma unroll
+                    for (int u = 0; u < UU; ++u)
+#pragma unroll
+                        for (int r = 0; r < G; ++r) {
+                            const v4i xa = *reinterpret_cast<const v4i*>(tiles + ((size_t)((sl + u) * RB + rbs[r0 + r]) << 10) +
+                                                                         64 * lr + 16 * (g ^ ((lr >> 2) & 3)));
+                            dv[u][r] = *reinterpret_cast<const float*>(scales + ((size_t)(sl + u) << 10) +
+                                                                       (16 * rbs[r0 + r] + lr) * 4);
+                            pr[u][r] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wq[u], xa, v4i{0, 0, 0, 0}, 0, 0, 0);
+                        }
+#pragma unroll
+                    for (int u = 0; u < UU; ++u)
+#pragma unroll
+                        for (int r = 0; r < G; ++r)
+#pragma unroll
+                            for (int v = 0; v < 4; ++v)
+                                acc[r0 + r][v] = __builtin_fmaf(dv[u][r] * sc[u][v], (float)pr[u][r][v], acc[r0 + r][v]);
+                }
+            };
+            constexpr int U = NR == 1 ? 4 : (NR == 2 ? 2 : 1);
+            int sl = 0;
+            for (; sl + U <= s_cnt; sl += U) stages(sl, std::integral_constant<int, U>{});
+            for (; sl < s_cnt; ++sl) stages(sl, std::integral_constant<int, 1>{});
+            slot_c = slot_c + 1 == nslots ? 0 : slot_c + 1;
+        }
+
+        // Lane holds C[row = 16*rb + lr][n0 + 16j + 4g + v], v = 0..3.
+        const int n = blockIdx.x * (16 * CB) + 16 * j + 4 * g;
+#pragma unroll
+        for (int r = 0; r < NR; ++r) {
+            const int rowl = 16 * rbs[r] + lr;
+            if (r < cnt && rowl < mrem) {
+                const size_t row = (size_t)(m0 + rowl);
+                if (out_f32) {
+                    *reinterpret_cast<float4*>(static_cast<float*>(C) + row * ldc + n) =
+                        make_float4(acc[r][0], acc[r][1], acc[r][2], acc[r][3]);
+                } else {
+                    *reinterpret_cast<uint2*>(static_cast<uint16_t*>(C) + row * ldc + n) =
+                        make_uint2(pack_bf16x2(acc[r][0], acc[r][1]), pack_bf16x2(acc[r][2], acc[r][3]));
+                }
+            }
+        }
+    };
+    // the weight codes of a stage are expanded once per wave whatever the number of row blocks
+    if (cnt == 1) {
+        run(std::integral_constant<int, 1>{});
+    } else if (cnt == 2) {
+        run(std::integral_constant<int, 2>{});
+    } else if (MAXR >= 4 && cnt <= 4) {
+        run(std::integral_constant<int, (MAXR >= 4 ? 4 : MAXR)>{});
+    } else if (MAXR >= 8 && cnt <= 8) {
+        run(std::integral_constant<int, (MAXR >= 8 ? 8 : MAXR)>{});
+    } else {
+        run(std::integral_constant<int, MAXR>{});
+    }
+}
+
+template <int CB>
+static void launch_qgemm(const void* qa, const void* da, int ldd, const void* wp, void* C, int ldc, int M, int N, int K,
+                         int out_f32, hipStream_t s)
+{
+    dim3 grid(N / (16 * CB), (M + 255) / 256);
+    const qgemm_plan full = make_qgemm_plan(256, CB, K);
+    const qgemm_plan tail = make_qgemm_plan(M - 256 * ((M - 1) / 256), CB, K);
+    hipLaunchKernelGGL((qgemm_kernel<CB>), grid, dim3(64 * (kQWaves + kQLoaders)), 0, s, static_cast<const int8_t*>(qa), K,
+                       static_cast<const float*>(da), ldd, static_cast<const uint8_t*>(wp), C, ldc, out_f32, full, tail);
+}
+
+static bool qgemm_shape_ok(int N, int K) { return N > 0 && K > 0 && N % 16 == 0 && K % 64 == 0 && K <= (1 << 22); }
+static int q_ldd(int M) { return (M + 3) & ~3; }
+
+}  // namespace det
+
+using namespace det;
+
+extern "C" size_t det_qgemm_packed_w_bytes(int N, int K)
+{
+    if (!qgemm_shape_ok(N, K)) return 0;
+    return (size_t)(N / 16) * (K / 64) * qstage_w_bytes(1);
+}
+
+extern "C" int det_quant_pack_w4(const void* B_kn, void* packed, int N, int K, void* stream)
+{
+    if (!B_kn || !packed) return DET_EINVAL;
+    if (!qgemm_shape_ok(N, K)) return DET_ESHAPE;
+    if (!aligned16(packed)) return DET_EALIGN;
+    const size_t total = (size_t)N * (K / 64);
+    hipLaunchKernelGGL(quant_pack_w4_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const uint16_t*>(B_kn), static_cast<uint8_t*>(packed), N,
+                       K, qgemm_cols_per_block(N));
+    return check_launch();
+}
+
+extern "C" int det_quant_unpack_w4(const void* packed, void* q, void* s, int N, int K, void* stream)
+{
+    if (!packed || !q || !s) return DET_EINVAL;
+    if (!qgemm_shape_ok(N, K)) return DET_ESHAPE;
+    const size_t total = (size_t)N * (K / 64);
+    hipLaunchKernelGGL(quant_unpack_w4_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const uint8_t*>(packed), static_cast<int8_t*>(q),
+                       static_cast<uint16_t*>(s), N, K, qgemm_cols_per_block(N));
+    return check_launch();
+}
+
+extern "C" size_t det_quant_act_codes_bytes(int M, int K) { return M > 0 && K > 0 ? (size_t)M * K : 0; }
+extern "C" size_t det_quant_act_scales_bytes(int M, int K)
+{
+    return M > 0 && K > 0 && K % 64 == 0 ? (size_t)q_ldd(M) * (K / 64) * sizeof(float) : 0;
+}
+
+extern "C" int det_quant_act_q8(const void* A, int lda, void* codes, void* scales, int M, int K, void* stream)
+{
+    if (!A || !codes || !scales || M < 1) return DET_EINVAL;
+    if (K < 64 || K % 64 != 0 || K > (1 << 22) || M > 65535) return DET_ESHAPE;
+    if (lda < K) return DET_EINVAL;
+    if (!aligned16(codes) || !aligned16(scales)) return DET_EALIGN;
+    hipLaunchKernelGGL(quant_act_q8_kernel, dim3((K / 64 + 3) / 4, M), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint16_t*>(A), lda, static_cast<int8_t*>(codes), static_cast<float*>(scales), q_ldd(M),
+                       K);
+    return check_launch();
+}
+
+extern "C" int det_qgemm_w4a8(const void* codes, const void* scales, const void* packed_w, void* C, int ldc, int M, int N,
+                              int K, int out_dtype, void* stream)
+{
+    if (!codes || !scales || !packed_w || !C || M < 1) return DET_EINVAL;
+    if (out_dtype != DET_BF16 && out_dtype != DET_F32) return DET_EINVAL;
+    if (!qgemm_shape_ok(N, K)) return DET_ESHAPE;
+    if (ldc < N) return DET_EINVAL;
+    if (!aligned16(codes) || !aligned16(scales) || !aligned16(packed_w) || !aligned16(C) || ldc % 4 != 0 || K % 16 != 0)
+        return DET_EALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int f32 = out_dtype == DET_F32;
+    switch (qgemm_cols_per_block(N)) {
+        case 1: launch_qgemm<1>(codes, scales, q_ldd(M), packed_w, C, ldc, M, N, K, f32, s); break;
+        case 2: launch_qgemm<2>(codes, scales, q_ldd(M), packed_w, C, ldc, M, N, K, f32, s); break;
+        case 4: launch_qgemm<4>(codes, scales, q_ldd(M), packed_w, C, ldc, M, N, K, f32, s); break;
+        default: launch_qgemm<8>(codes, scales, q_ldd(M), packed_w, C, ldc, M, N, K, f32, s); break;
+    }
+    return check_launch();
+}

@@ -1,0 +1,109 @@
+"""Block-quantized GEMM on the GPU against the bit-exact oracle: the two quantizers code for code,
+the product byte for byte (bf16 and fp32 outputs), row-byte invariance over M = 1..256 and over the
+content of the other rows, and repeatability."""
+import numpy as np
+import pytest
+import torch
+
+import detsynth as ds
+from gpu_util import DEV, down_bf16, step, up, up_bf16
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def d():
+    import paper_2602_00182_amd as d
+    return d
+
+
+def gpu_quant_w(d, w_bits):
+    K, N = w_bits.shape
+    packed = d.quant_pack_weight(up_bf16(w_bits))
+    q = torch.empty((K, N), dtype=torch.int8, device=DEV)
+    s = torch.empty((K // 64, N), dtype=torch.bfloat16, device=DEV)
+    d.det_quant_unpack_w4(packed, q, s)
+    torch.cuda.synchronize()
+    return packed, q.cpu().numpy(), down_bf16(s)
+
+
+def gpu_quant_a(d, a_bits):
+    M, K = a_bits.shape
+    codes, scales = d.quant_activations(up_bf16(a_bits))
+    torch.cuda.synchronize()
+    ldd = (M + 3) & ~3
+    return codes, scales, codes.cpu().numpy(), scales.cpu().numpy().reshape(K // 64, ldd)[:, :M].T.copy()
+
+
+@pytest.mark.parametrize("K,N", [(256, 64), (512, 4096), (1024, 6144), (4096, 2048), (192, 28672)])
+def test_weight_quantizer_matches_oracle(d, orc, K, N):
+    w = ds.normal_bf16(ds.tensor_seed(6, 10) + K + N, (K, N), 0.02, 0.0)
+    w[5, :] = 0x8000 | (w[5, :] & 0x7FFF)        # some structure: a negative row, a zero block, a big value
+    w[64:128, 3] = 0
+    w[130, 7] = 0x4040                         # 3.0
+    step(f"weight quantizer K={K} N={N}")
+    _, q, s = gpu_quant_w(d, w)
+    qo, so = orc.quant_w4(w)
+    assert np.array_equal(s, so) and np.array_equal(q, qo)
+
+
+@pytest.mark.parametrize("M,K", [(1, 64), (3, 4096), (17, 1024), (256, 4096), (130, 14336)])
+def test_activation_quantizer_matches_oracle(d, orc, M, K):
+    a = ds.normal_bf16(ds.tensor_seed(6, 20) + M + K, (M, K), 1.0, 0.0)
+    a[0, :64] = 0
+    step(f"activation quantizer M={M} K={K}")
+    _, _, p, dd = gpu_quant_a(d, a)
+    po, do = orc.quant_a8(a)
+    assert np.array_equal(dd.view(np.uint32), do.view(np.uint32)) and np.array_equal(p, po)
+
+
+@pytest.mark.parametrize("M,K,N", [
+    (1, 64, 16), (16, 512, 512), (5, 1024, 4096), (33, 2048, 6144), (64, 512, 28672), (200, 1024, 3072),
+    (256, 4096, 4096), (256, 1024, 28672), (300, 512, 2048), (7, 14336, 256), (128, 2048, 32000),
+])
+def test_qgemm_bytes_match_oracle(d, orc, M, K, N):
+    a = ds.normal_bf16(ds.tensor_seed(6, 30) + M, (M, K), 1.0, 0.0)
+    w = ds.normal_bf16(ds.tensor_seed(6, 31) + N, (K, N), 0.02, 0.0)
+    step(f"qgemm M={M} K={K} N={N}")
+    packed, _, _ = gpu_quant_w(d, w)
+    codes, scales, _, _ = gpu_quant_a(d, a)
+    c = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=DEV)
+    cf = torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV)
+    d.det_qgemm_w4a8(codes, scales, packed, c, N)
+    d.det_qgemm_w4a8(codes, scales, packed, cf, N)
+    torch.cuda.synchronize()
+    p, dd = orc.quant_a8(a)
+    q, s = orc.quant_w4(w)
+    acc, cb = orc.qgemm_w4a8(p, dd, q, s)
+    assert np.array_equal(cf.cpu().numpy().view(np.uint32), acc.view(np.uint32))
+    assert np.array_equal(down_bf16(c), cb)
+
+
+def test_qgemm_batch_invariance_and_repeats(d):
+    K, N = 4096, 6144
+    a = ds.normal_bf16(ds.tensor_seed(6, 40), (256, K), 1.0, 0.0)
+    w = ds.normal_bf16(ds.tensor_seed(6, 41), (K, N), 0.02, 0.0)
+    packed = d.quant_pack_weight(up_bf16(w))
+
+    def run(rows_bits):
+        M = rows_bits.shape[0]
+        codes, scales = d.quant_activations(up_bf16(rows_bits))
+        c = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+        d.det_qgemm_w4a8(codes, scales, packed, c, N)
+        torch.cuda.synchronize()
+        return down_bf16(c)
+
+    step("qgemm M=256 reference")
+    full = run(a)
+    for M in (1, 2, 3, 8, 15, 16, 17, 64, 100, 128, 255):
+        step(f"qgemm rows 0..{M - 1} alone")
+        assert np.array_equal(run(a[:M]), full[:M]), M
+    step("qgemm with other rows replaced and slots permuted")
+    other = ds.normal_bf16(ds.tensor_seed(6, 42), (256, K), 3.0, 0.0)
+    mixed = other.copy()
+    mixed[[200, 7, 31]] = a[[0, 1, 2]]
+    got = run(mixed)
+    assert np.array_equal(got[[200, 7, 31]], full[[0, 1, 2]])
+    step("qgemm 20 repeats")
+    for _ in range(20):
+        assert np.array_equal(run(a), full)
