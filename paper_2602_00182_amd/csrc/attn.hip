@@ -6,6 +6,7 @@
 #include <math.h>
 
 #include "internal.h"
+#include "stream.h"
 
 namespace det {
 
@@ -43,7 +44,7 @@ __device__ __forceinline__ float combine_max(const float* mc, int nc)
 //   PV    : lane (p = lane/16, dg = lane%16) of wave w owns d = 8dg..8dg+7 and tokens
 //           64w + 4it + p, it = 0..15, folded in ascending it with fma from +0; the four p are
 //           summed as (p0+p2)+(p1+p3), then the four waves as (w0+w2)+(w1+w3).
-template <int G>
+template <int G, bool VLDS>
 __global__ __launch_bounds__(256) void attn_chunk_kernel(const uint16_t* __restrict__ q,
                                                          const uint16_t* __restrict__ kcache,
                                                          const uint16_t* __restrict__ vcache,
@@ -56,6 +57,7 @@ __global__ __launch_bounds__(256) void attn_chunk_kernel(const uint16_t* __restr
     __shared__ float sc[G][kChunk];       // scores, then e_j
     __shared__ float po[4][G][kD];        // per-wave partial outputs
     __shared__ float scratch[4];
+    __shared__ uint4 vbuf[VLDS ? 4 : 1][VLDS ? 16 : 1][64];  // the chunk's V rows: wave, block of 4 tokens, lane
 
     const int c = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
     int len = seqlens[b] + len_offset;
@@ -68,6 +70,21 @@ __global__ __launch_bounds__(256) void attn_chunk_kernel(const uint16_t* __restr
     const size_t kv_base = ((size_t)slot * Hkv + kvh) * (size_t)Lmax * kD;
     const uint16_t* kp = kcache + kv_base;
     const uint16_t* vp = vcache + kv_base;
+
+    // VLDS (launches with few workgroups, where latency and not bandwidth sets the time): the chunk's
+    // V rows go straight into LDS (64 KB, LDS-DMA) before anything else, so that they travel while the
+    // scores are computed.  Wave w loads what it will use itself: block `it` holds tokens 64w + 4it ..
+    // +3, lane (g, lr) its 16 bytes d = 8lr..8lr+7 of token 4it + g -- the lane that reads it back.
+    // Tokens past the length load nothing.  Large launches read V from global memory in the PV loop:
+    // with 12 KB of LDS many workgroups share a compute unit and their phases overlap.
+    if constexpr (VLDS) {
+        const int wu = __builtin_amdgcn_readfirstlane(wave);  // the load takes wave-uniform base addresses
+        const char* vsrc = reinterpret_cast<const char*>(vp + (size_t)(t0 + 64 * wu) * kD);
+        const uint32_t vdst = (uint32_t)(uintptr_t)(lds_char_t*)&vbuf[0][0][0] + (uint32_t)wu * 16384u;
+#pragma unroll
+        for (int it = 0; it < 16; ++it)
+            if (t0 + 64 * wave + 4 * it + g < len) dma_block(vsrc + it * 1024, (uint32_t)lane * 16u, vdst + it * 1024);
+    }
 
     // query fragments: head lr (< G) of this KV group, d = 32g + 8i + e
     uint4 qf[4];
@@ -122,11 +139,16 @@ __global__ __launch_bounds__(256) void attn_chunk_kernel(const uint16_t* __restr
     for (int h = 0; h < G; ++h)
 #pragma unroll
         for (int d = 0; d < 8; ++d) o[h][d] = 0.0f;
+    if constexpr (VLDS) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's V rows have landed
 #pragma unroll 4
     for (int it = 0; it < 16; ++it) {
         const int tl = 64 * wave + 4 * it + g;
         if (t0 + tl < len) {
-            const uint4 vv = *reinterpret_cast<const uint4*>(vp + (size_t)(t0 + tl) * kD + 8 * lr);
+            uint4 vv;
+            if constexpr (VLDS)
+                vv = vbuf[wave][it][lane];
+            else
+                vv = *reinterpret_cast<const uint4*>(vp + (size_t)(t0 + tl) * kD + 8 * lr);
             const uint32_t pw[4] = {vv.x, vv.y, vv.z, vv.w};
             float vf[8];
 #pragma unroll
@@ -327,9 +349,18 @@ int det::attn_decode_impl(const void* q, const void* kcache, const void* vcache,
     const uint16_t* qq = static_cast<const uint16_t*>(q);
     const uint16_t* kk = static_cast<const uint16_t*>(kcache);
     const uint16_t* vv = static_cast<const uint16_t*>(vcache);
-#define DET_LAUNCH_ATTN(GG)                                                                            \
-    hipLaunchKernelGGL(attn_chunk_kernel<GG>, grid, dim3(256), 0, s, qq, kk, vv, seqlens, slots, ws_m, ws_l, \
-                       ws_o, Hq, Hkv, Lmax, ncmax, scale, len_offset)
+    // Which of the two data paths for V is a matter of time only: the arithmetic and its order are the
+    // same, so a row's bytes do not depend on it.  At most two workgroups per compute unit: latency bound.
+    const bool vlds = (size_t)ncmax * Hkv * B <= 512;
+#define DET_LAUNCH_ATTN(GG)                                                                                      \
+    do {                                                                                                         \
+        if (vlds)                                                                                                \
+            hipLaunchKernelGGL((attn_chunk_kernel<GG, true>), grid, dim3(256), 0, s, qq, kk, vv, seqlens, slots, \
+                               ws_m, ws_l, ws_o, Hq, Hkv, Lmax, ncmax, scale, len_offset);                      \
+        else                                                                                                     \
+            hipLaunchKernelGGL((attn_chunk_kernel<GG, false>), grid, dim3(256), 0, s, qq, kk, vv, seqlens, slots,\
+                               ws_m, ws_l, ws_o, Hq, Hkv, Lmax, ncmax, scale, len_offset);                      \
+    } while (0)
     switch (G) {
         case 1: DET_LAUNCH_ATTN(1); break;
         case 2: DET_LAUNCH_ATTN(2); break;
