@@ -38,38 +38,35 @@ __global__ __launch_bounds__(256) void rope_kernel(const uint16_t* __restrict__ 
 
 // The layer's fused form: rotate the Hq query heads of row b of the fused projection into qbuf,
 // rotate its Hkv key heads into cache row positions[b], copy its Hkv value heads there too.
-// qkv: [B, (Hq+2Hkv)*D]; qbuf: [B, Hq*D]; caches: [B, Hkv, Lmax, D].
-__global__ __launch_bounds__(256) void rope_append_kernel(const uint16_t* __restrict__ qkv,
-                                                          uint16_t* __restrict__ qbuf,
-                                                          uint16_t* __restrict__ kcache,
-                                                          uint16_t* __restrict__ vcache,
-                                                          const int32_t* __restrict__ pos,
-                                                          const int32_t* __restrict__ slots,
-                                                          const float* __restrict__ cos_t,
-                                                          const float* __restrict__ sin_t, int Hq, int Hkv,
-                                                          int D, int Lmax)
+// qkv: [B, (Hq+2Hkv)*D]; qbuf: [B, Hq*D]; caches: [S, Hkv, Lmax, D].
+// Grid (Hq + 2*Hkv, B), one wavefront per head (D = 128: one rotation pair, or two value elements,
+// per thread): the work of a row is a single round trip to memory wide instead of ten deep.
+__global__ __launch_bounds__(64) void rope_append_kernel(const uint16_t* __restrict__ qkv,
+                                                         uint16_t* __restrict__ qbuf,
+                                                         uint16_t* __restrict__ kcache,
+                                                         uint16_t* __restrict__ vcache,
+                                                         const int32_t* __restrict__ pos,
+                                                         const int32_t* __restrict__ slots,
+                                                         const float* __restrict__ cos_t,
+                                                         const float* __restrict__ sin_t, int Hq, int Hkv,
+                                                         int D, int Lmax)
 {
-    const int b = blockIdx.x, half = D >> 1;
+    const int hh = blockIdx.x, b = blockIdx.y, half = D >> 1, k = threadIdx.x;
     int p = pos[b];
     p = p < 0 ? 0 : (p >= Lmax ? Lmax - 1 : p);
     const int slot = slots ? slots[b] : b;  // cache slot the row's key and value go to
     const uint16_t* row = qkv + (size_t)b * (Hq + 2 * Hkv) * D;
-    const float* cr = cos_t + (size_t)p * half;
-    const float* sr = sin_t + (size_t)p * half;
-    for (int i = threadIdx.x; i < Hq * half; i += 256) {
-        const int h = i / half, k = i % half;
-        uint16_t* dst = qbuf + ((size_t)b * Hq + h) * D;
-        rope_pair(row[h * D + k], row[h * D + k + half], cr[k], sr[k], dst[k], dst[k + half]);
-    }
-    for (int i = threadIdx.x; i < Hkv * half; i += 256) {
-        const int h = i / half, k = i % half;
-        const uint16_t* src = row + (size_t)(Hq + h) * D;
-        uint16_t* dst = kcache + (((size_t)slot * Hkv + h) * Lmax + p) * D;
-        rope_pair(src[k], src[k + half], cr[k], sr[k], dst[k], dst[k + half]);
-    }
-    for (int i = threadIdx.x; i < Hkv * D; i += 256) {
-        const int h = i / D, k = i % D;
-        vcache[(((size_t)slot * Hkv + h) * Lmax + p) * D + k] = row[(size_t)(Hq + Hkv + h) * D + k];
+    if (hh < Hq + Hkv) {
+        if (k >= half) return;
+        const uint16_t* src = row + (size_t)hh * D;
+        uint16_t* dst = hh < Hq ? qbuf + ((size_t)b * Hq + hh) * D
+                                : kcache + (((size_t)slot * Hkv + (hh - Hq)) * Lmax + p) * D;
+        rope_pair(src[k], src[k + half], cos_t[(size_t)p * half + k], sin_t[(size_t)p * half + k], dst[k], dst[k + half]);
+    } else {
+        const int h = hh - Hq - Hkv;
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(row + (size_t)(Hq + Hkv + h) * D);
+        uint32_t* dst = reinterpret_cast<uint32_t*>(vcache + (((size_t)slot * Hkv + h) * Lmax + p) * D);
+        for (int i = k; i < half; i += 64) dst[i] = src[i];
     }
 }
 
@@ -152,8 +149,8 @@ int det::rope_append(const void* qkv, void* qbuf, void* kcache, void* vcache, co
                      const float* cos_t, const float* sin_t, int B, int Hq, int Hkv, int D, int Lmax,
                      hipStream_t s)
 {
-    if (D != 128) return DET_ESHAPE;
-    hipLaunchKernelGGL(rope_append_kernel, dim3(B), dim3(256), 0, s, static_cast<const uint16_t*>(qkv),
+    if (D != 128 || B > 65535) return DET_ESHAPE;
+    hipLaunchKernelGGL(rope_append_kernel, dim3(Hq + 2 * Hkv, B), dim3(64), 0, s, static_cast<const uint16_t*>(qkv),
                        static_cast<uint16_t*>(qbuf), static_cast<uint16_t*>(kcache),
                        static_cast<uint16_t*>(vcache), positions, slots, cos_t, sin_t, Hq, Hkv, D, Lmax);
     return check_launch();

@@ -18,8 +18,13 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint4* __restrict__ 
     const uint4* xr = x + (size_t)blockIdx.x * nvec;
     uint4* yr = y + (size_t)blockIdx.x * nvec;
 
-    uint4 xv[kMaxVecPerThread];
+    uint4 xv[kMaxVecPerThread], wv[kMaxVecPerThread];
     float acc = 0.0f;
+#pragma unroll
+    for (int i = 0; i < kMaxVecPerThread; ++i) {  // the weights travel with the row, ahead of the reduction
+        const int v = threadIdx.x + i * 256;
+        if (v < nvec) wv[i] = w[v];
+    }
 #pragma unroll
     for (int i = 0; i < kMaxVecPerThread; ++i) {
         const int v = threadIdx.x + i * 256;
@@ -42,9 +47,8 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint4* __restrict__ 
     for (int i = 0; i < kMaxVecPerThread; ++i) {
         const int v = threadIdx.x + i * 256;
         if (v < nvec) {
-            const uint4 wv = w[v];
             const uint32_t p[4] = {xv[i].x, xv[i].y, xv[i].z, xv[i].w};
-            const uint32_t q[4] = {wv.x, wv.y, wv.z, wv.w};
+            const uint32_t q[4] = {wv[i].x, wv[i].y, wv[i].z, wv[i].w};
             uint32_t o[4];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
