@@ -107,3 +107,22 @@ def test_qgemm_batch_invariance_and_repeats(d):
     step("qgemm 20 repeats")
     for _ in range(20):
         assert np.array_equal(run(a), full)
+
+
+def test_qgemm_argument_errors(d):
+    from paper_2602_00182_amd._lib import lib
+    L = lib()
+    buf = torch.zeros(1 << 16, dtype=torch.uint8, device=DEV)
+    p = buf.data_ptr()
+    assert L.det_qgemm_packed_w_bytes(100, 64) == 0 and L.det_qgemm_packed_w_bytes(64, 100) == 0   # N % 16, K % 64
+    assert L.det_qgemm_packed_w_bytes(64, 128) == 4 * 2 * 544
+    assert L.det_quant_pack_w4(p, p, 100, 64, None) == 2                       # DET_ESHAPE
+    assert L.det_quant_pack_w4(None, p, 64, 64, None) == 1                     # DET_EINVAL
+    assert L.det_quant_pack_w4(p, p + 4, 64, 64, None) == 3                    # DET_EALIGN
+    assert L.det_quant_act_q8(p, 32, p, p, 1, 64, None) == 1                   # lda < K
+    assert L.det_quant_act_q8(p, 64, p, p, 1, 96, None) == 2
+    assert L.det_qgemm_w4a8(p, p, p, p, 60, 1, 64, 64, 0, None) == 1           # ldc < N
+    assert L.det_qgemm_w4a8(p, p, p, p, 64, 1, 64, 64, 7, None) == 1           # out_dtype
+    assert L.det_qgemm_w4a8(p, p, p, p, 64, 0, 64, 64, 0, None) == 1           # M < 1
+    assert L.det_qgemm_w4a8(p, p, p, p, 66, 1, 64, 64, 0, None) == 3           # ldc % 4
+    torch.cuda.synchronize()
