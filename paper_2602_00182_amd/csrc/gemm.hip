@@ -279,6 +279,13 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
                 }
                 return;
             }
+            if (HB == 1) {  // at most 8 rows: one half block a stage, stages lrank, lrank+nload, ...
+                if (lrow < mrem)
+                    dma_run(abytes, a_lane_off0 + ((uint32_t)(s0 + lrank) << 7), (uint32_t)nload << 7,
+                            slot_addr + (uint32_t)(nw + lrank * 2 * RB) * 1024u, (uint32_t)(nload * 2 * RB) * 1024u,
+                            strided(s_cnt));
+                return;
+            }
             const int nhalf = s_cnt * HB;
             int hb = first_hb;
             const char* asrc = abytes + (size_t)hb * half_bytes + ((size_t)(s0 + first_sl) << 7);
@@ -337,15 +344,6 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
         const int zr = (((lr >> 1) & 3) << 1) | (lr >> 3);
         const int a_lane = 2 * wave * 64 + 64 * (lr >> 3) + 8 * (lr & 7);
         const int a0_off = a_lane + (g ^ zr), a1_off = a_lane + ((g ^ zr) ^ 4);
-        // wp: weight block of the step (this lane's 16 bytes of column block 0); ap: the lane's piece in
-        // the tile of row block `wave`
-        auto rd = [&](Frags& fr, const uint4* wp, const uint4* ap) {
-#pragma unroll
-            for (int j = 0; j < CB; ++j) fr.wf[j] = __builtin_bit_cast(bf16x8, wp[(2 * j) * 64]);
-#pragma unroll
-            for (int r = 0; r < NRB; ++r) fr.xf[r] = __builtin_bit_cast(bf16x8, ap[(2 * NW * r) * 64]);
-            __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the steps they feed
-        };
         auto mm = [&](const Frags& fr) {
 #pragma unroll
             for (int r = 0; r < NRB; ++r)
@@ -410,22 +408,27 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
             }
         } else {
             // Small tiles: a step has too few matrix-core instructions to cover the LDS latency, so the
-            // reads run DS-1 steps ahead (DS = 8, or 4 from 4 instructions a step on), one pipeline per
-            // chunk (a chunk has many stages here).  Reads past the chunk's last stage are redirected to
-            // the last stage: in bounds and unused, which keeps the loop body free of branches.
-            constexpr int DS = (CB * NRB >= 4) ? 4 : 8;
+            // reads run DS-1 steps ahead, one pipeline per chunk (a chunk has many stages here).  The wait
+            // before a step leaves the reads of the DS-1 steps after it in flight, so DS-1 times the reads
+            // of a step must fit the LDS counter (0..15).  Reads past the chunk's last stage are redirected
+            // to the last stage: in bounds and unused, which keeps the counts the same in every iteration.
+            constexpr int kReads = CB + NRB;
+            constexpr int kAhead = 15 / kReads >= 7 ? 7 : (15 / kReads >= 5 ? 5 : (15 / kReads >= 3 ? 3 : 1));
+            constexpr int DS = kAhead + 1;  // even, so that the parity of a step is static in the unrolled loop
+            using wseq = std::make_integer_sequence<int, CB>;
+            using xseq = std::make_integer_sequence<int, NRB>;
+            const uint32_t x0 = (uint32_t)a0_off * 16u, x1 = (uint32_t)a1_off * 16u;
             int slot_c = 0;
             for (int c = 0; c < nchunks; ++c) {
                 open_chunk();
                 const int s_cnt = chunk_stages(c);
-                const uint4* slot = ring + (size_t)(slot_c * slot_blocks) * 64;
-                const uint4* wbase = slot + lane;
-                const uint4* abase0 = slot + s_cnt * (2 * CB * 64) + a0_off;
-                const uint4* abase1 = slot + s_cnt * (2 * CB * 64) + a1_off;
+                const uint32_t wb = ring_addr + (uint32_t)(slot_c * slot_blocks) * 1024u + (uint32_t)lane * 16u;
+                const uint32_t xb = ring_addr + (uint32_t)(slot_c * slot_blocks + s_cnt * 2 * CB) * 1024u;
                 const int last = s_cnt - 1;
                 auto rd_step = [&](Frags& fr, int u, int odd) {  // step u = 2*stage + odd; odd is static at every call
                     const int sl = min(u >> 1, last);
-                    rd(fr, wbase + sl * (2 * CB * 64) + odd * 64, (odd ? abase1 : abase0) + sl * nA * 64);
+                    read_frags<NW>(fr, wb + (uint32_t)(sl * 2 * CB + odd) * 1024u, xb + (uint32_t)(sl * nA) * 1024u + (odd ? x1 : x0),
+                                   wseq{}, xseq{});
                 };
                 Frags f[DS];
 #pragma unroll
@@ -433,9 +436,11 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
                 const int nsteps = 2 * s_cnt;
                 for (int u0 = 0; u0 < nsteps; u0 += DS) {
 #pragma unroll
-                    for (int k = 0; k < DS; ++k) {  // DS is even, so the parity of step u0+k is that of k
+                    for (int k = 0; k < DS; ++k) {
                         if (u0 + k < nsteps) {
                             rd_step(f[(k + DS - 1) % DS], u0 + k + DS - 1, (k + DS - 1) & 1);
+                            wait_lds_reads<kAhead * kReads>();
+                            tie_frags(f[k], wseq{}, xseq{});
                             mm(f[k]);
                         }
                     }
