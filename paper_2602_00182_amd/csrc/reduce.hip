@@ -71,12 +71,16 @@ __device__ __forceinline__ void argmax_merge(float& bv, int& bi, float v, int i)
     }
 }
 
+// One workgroup of kArgmaxThreads threads per row: a row of 32000 fp32 logits is 128 KB, and what
+// bounds the kernel is how many of its bytes are in flight at once.
+constexpr int kArgmaxThreads = 1024;
 template <bool F32>
-__global__ __launch_bounds__(256) void argmax_kernel(const void* __restrict__ logits,
-                                                     int32_t* __restrict__ idx, int V, int vec)
+__global__ __launch_bounds__(kArgmaxThreads) void argmax_kernel(const void* __restrict__ logits,
+                                                                int32_t* __restrict__ idx, int V, int vec)
 {
-    __shared__ float sv[4];
-    __shared__ int si[4];
+    constexpr int T = kArgmaxThreads;
+    __shared__ float sv[T / 64];
+    __shared__ int si[T / 64];
     float bv = 0.0f;
     int bi = -1;  // -1: nothing but NaN seen so far
     // A thread's elements are visited in ascending index, so "strictly greater" keeps the lowest
@@ -91,14 +95,14 @@ __global__ __launch_bounds__(256) void argmax_kernel(const void* __restrict__ lo
         // 16-byte loads, four vectors in flight per thread
         const float4* row = reinterpret_cast<const float4*>(static_cast<const float*>(logits) + (size_t)blockIdx.x * V);
         const int nv = V >> 2;
-        for (int v0 = threadIdx.x; v0 < nv; v0 += 4 * 256) {
+        for (int v0 = threadIdx.x; v0 < nv; v0 += 4 * T) {
             float4 x[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u)
-                if (v0 + u * 256 < nv) x[u] = row[v0 + u * 256];
+                if (v0 + u * T < nv) x[u] = row[v0 + u * T];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int q = v0 + u * 256;
+                const int q = v0 + u * T;
                 if (q < nv) {
                     visit(x[u].x, 4 * q);
                     visit(x[u].y, 4 * q + 1);
@@ -110,14 +114,14 @@ __global__ __launch_bounds__(256) void argmax_kernel(const void* __restrict__ lo
     } else if (!F32 && vec) {
         const uint4* row = reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(logits) + (size_t)blockIdx.x * V);
         const int nv = V >> 3;
-        for (int v0 = threadIdx.x; v0 < nv; v0 += 4 * 256) {
+        for (int v0 = threadIdx.x; v0 < nv; v0 += 4 * T) {
             uint4 x[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u)
-                if (v0 + u * 256 < nv) x[u] = row[v0 + u * 256];
+                if (v0 + u * T < nv) x[u] = row[v0 + u * T];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int q = v0 + u * 256;
+                const int q = v0 + u * T;
                 if (q < nv) {
                     const uint32_t p[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
 #pragma unroll
@@ -129,7 +133,7 @@ __global__ __launch_bounds__(256) void argmax_kernel(const void* __restrict__ lo
             }
         }
     } else {
-        for (int j = threadIdx.x; j < V; j += 256) {
+        for (int j = threadIdx.x; j < V; j += T) {
             float v;
             if (F32)
                 v = static_cast<const float*>(logits)[(size_t)blockIdx.x * V + j];
@@ -150,7 +154,7 @@ __global__ __launch_bounds__(256) void argmax_kernel(const void* __restrict__ lo
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        for (int k = 1; k < 4; ++k) argmax_merge(bv, bi, sv[k], si[k]);
+        for (int k = 1; k < T / 64; ++k) argmax_merge(bv, bi, sv[k], si[k]);
         idx[blockIdx.x] = bi < 0 ? 0 : bi;
     }
 }
@@ -178,8 +182,8 @@ extern "C" int det_argmax(const void* logits, int32_t* idx, int B, int V, int dt
     // 16-byte loads when every row starts on a 16-byte boundary, element loads otherwise
     const int vec = aligned16(logits) && V % (dtype == DET_F32 ? 4 : 8) == 0;
     if (dtype == DET_F32)
-        hipLaunchKernelGGL(argmax_kernel<true>, dim3(B), dim3(256), 0, s, logits, idx, V, vec);
+        hipLaunchKernelGGL(argmax_kernel<true>, dim3(B), dim3(kArgmaxThreads), 0, s, logits, idx, V, vec);
     else
-        hipLaunchKernelGGL(argmax_kernel<false>, dim3(B), dim3(256), 0, s, logits, idx, V, vec);
+        hipLaunchKernelGGL(argmax_kernel<false>, dim3(B), dim3(kArgmaxThreads), 0, s, logits, idx, V, vec);
     return check_launch();
 }
