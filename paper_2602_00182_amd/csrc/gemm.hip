@@ -6,8 +6,10 @@
 // Shape of the kernel
 //   * A workgroup owns BN = 16*CB output columns and up to 256 rows; grid.x = N/BN, grid.y =
 //     ceil(M/256).  It has NW (4 or 8) wavefronts that can compute plus NL (2 or 4) that only load.
-//     CB, the LDS ring size and the wave counts are functions of N alone, so the configuration never
-//     depends on M.
+//     CB, the LDS ring size and the wave counts are functions of N alone.  Tall launches of narrow
+//     matrices (16- or 32-column tiles, from 96 or 192 rows on) use 64-column tiles of fewer rows
+//     instead, see gemm_dispatch.  The tiling decides which workgroup and wave computes an element,
+//     never the element's arithmetic, so its bytes are the same whichever ran.
 //   * K is cut into 64-deep stages.  Operands travel as 1 KB blocks.  A weight block is already in
 //     the operand order of v_mfma_f32_16x16x32_bf16 (lane l holds 8 consecutive k of column l%16, k
 //     group l/16); an activation block is 8 rows x 64 k as they lie in A (whole 128-byte lines),
@@ -157,7 +159,10 @@ static gemm_tile_plan make_tile_plan(int mrem, int cb, int ringb, int nw, int nl
     return t;
 }
 
-template <int CB, int RINGB, int EPI, int NW, int NL>
+// PCB: column blocks per slab of the packed weights.  PCB == CB: the workgroup's weights are one slab.
+// PCB < CB (tall launches of narrow matrices, see gemm_dispatch): the workgroup owns CB/PCB adjacent
+// slabs of a matrix packed for narrower tiles, and its rows are a tile of plan_full.mrem rows.
+template <int CB, int RINGB, int EPI, int NW, int NL, int PCB>
 __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __restrict__ A, int lda,
                                                           const uint4* __restrict__ Bp, void* C, int ldc,
                                                           const uint16_t* R, int ldr, int K, int out_f32,
@@ -165,6 +170,7 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
 {
     static_assert(RINGB >= 4 * (CB + 16), "the ring must hold two stages of the largest tile");
     static_assert(NL >= 1, "a tile of NW row blocks or more needs waves that only load");
+    static_assert(CB % PCB == 0 && (PCB == CB || ((CB & (CB - 1)) == 0 && (PCB & (PCB - 1)) == 0)), "slab split by shifts");
     __shared__ uint4 ring[RINGB * 64];
 
     const int tid = threadIdx.x;
@@ -172,7 +178,7 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 4;   // k group of the lane
     const int lr = lane & 15;  // row of A / column-in-block of the weights
-    const int m0 = blockIdx.y * 256;
+    const int m0 = blockIdx.y * plan_full.mrem;  // full tiles are plan_full.mrem rows high (256 unless PCB < CB)
     const gemm_tile_plan& tp = blockIdx.y + 1 == gridDim.y ? plan_tail : plan_full;
     const int mrem = tp.mrem;
     const int RB = tp.RB;    // 16-row blocks holding data
@@ -214,7 +220,8 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
         // ---------------------------------------------------------------- loading wave
         const int nload = tp.nload;  // = NW + NL - ncomp
         const int lrank = wave - ncomp;
-        const char* wbytes = reinterpret_cast<const char*>(Bp + (size_t)blockIdx.x * nstages * (2 * CB * 64));
+        // first slab of this workgroup (a slab holds nstages stages of 2*PCB blocks)
+        const char* wbytes = reinterpret_cast<const char*>(Bp + (size_t)blockIdx.x * (CB / PCB) * nstages * (2 * PCB * 64));
         const char* abytes = reinterpret_cast<const char*>(A + (size_t)m0 * lda);
         const size_t half_bytes = (size_t)lda * 16;  // 8 rows of A
         const uint32_t w_lane_off = (uint32_t)lane * 16u;
@@ -230,8 +237,13 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
         // lrank+nload, ... below s_cnt*HB.  A half block that holds data always has a live lane.
         const bool stage_split = (mrem & 7) == 0 && HB >= nload;
         auto strided = [&](int n) { return n > lrank ? (int)(((uint32_t)(n - lrank + nload - 1) * tp.inv_nload) >> 20) : 0; };
+        // With the weights in several slabs (PCB < CB) the split is by position inside a stage instead:
+        // u = lrank, lrank+nload, ... below 2*CB, the same for every stage, since block u of successive
+        // stages is evenly spaced both in its slab and in LDS.
+        const int nw_stage = strided(2 * CB);
         auto loads_for = [&](int s_cnt) {
-            return strided(s_cnt * 2 * CB) + (stage_split ? s_cnt * strided(HB) : strided(s_cnt * HB));
+            return (PCB == CB ? strided(s_cnt * 2 * CB) : s_cnt * nw_stage) +
+                   (stage_split ? s_cnt * strided(HB) : strided(s_cnt * HB));
         };
         // every chunk but the last has SPC stages, so two values cover all chunks
         const int loads_full = loads_for(SPC);
@@ -249,8 +261,18 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
             const int s0 = c * SPC;
             const int nw = s_cnt * 2 * CB;
             const uint32_t slot_addr = ring_addr + (uint32_t)(slot_idx * slot_blocks) * 1024u;
-            dma_run(wbytes, w_lane_off + (uint32_t)(s0 * (2 * CB) + lrank) * 1024u, (uint32_t)nload * 1024u,
-                    slot_addr + (uint32_t)lrank * 1024u, (uint32_t)nload * 1024u, s_cnt == SPC ? nw_full : nw_last);
+            if constexpr (PCB == CB) {
+                dma_run(wbytes, w_lane_off + (uint32_t)(s0 * (2 * CB) + lrank) * 1024u, (uint32_t)nload * 1024u,
+                        slot_addr + (uint32_t)lrank * 1024u, (uint32_t)nload * 1024u, s_cnt == SPC ? nw_full : nw_last);
+            } else {
+                // block u of a stage = block u % 2PCB of that stage in slab u / 2PCB
+                for (int u = lrank; u < 2 * CB; u += nload) {
+                    const int j2 = u / (2 * PCB), t = u % (2 * PCB);
+                    dma_run(wbytes + (size_t)j2 * nstages * (2 * PCB * 1024),
+                            w_lane_off + (uint32_t)(s0 * (2 * PCB) + t) * 1024u, (uint32_t)(2 * PCB) * 1024u,
+                            slot_addr + (uint32_t)u * 1024u, (uint32_t)(2 * CB) * 1024u, s_cnt);
+                }
+            }
             // Half block hb of stage sl comes from abytes + hb*half_bytes + 128*(s0+sl) and goes to block
             // 2*RB*sl + hb of the tile area; both are walked with running addresses.
             if (stage_split && (nload & 1) == 0) {  // all of this wave's half blocks have the parity of its rank
@@ -535,14 +557,15 @@ __global__ __launch_bounds__(256) void gemm_pack_kernel(const uint16_t* __restri
     }
 }
 
-template <int CB, int RINGB, int EPI, int NW, int NL>
+template <int CB, int RINGB, int EPI, int NW, int NL, int PCB = CB>
 static void launch_gemm(const void* A, int lda, const void* Bp, void* C, int ldc, const void* R, int ldr, int M,
-                        int N, int K, int out_f32, hipStream_t s)
+                        int N, int K, int out_f32, hipStream_t s, int tile_rows = 256)
 {
-    dim3 grid(N / (16 * CB), (M + 255) / 256);
-    const gemm_tile_plan full = make_tile_plan(256, CB, RINGB, NW, NL, K);
-    const gemm_tile_plan tail = make_tile_plan(M - 256 * ((M - 1) / 256), CB, RINGB, NW, NL, K);
-    hipLaunchKernelGGL((gemm_kernel<CB, RINGB, EPI, NW, NL>), grid, dim3(64 * (NW + NL)), 0, s,
+    if (tile_rows < 16 || tile_rows > 256 || tile_rows % 16 != 0) abort();  // the kernel's row blocks: 1..16 of 16 rows
+    dim3 grid(N / (16 * CB), (M + tile_rows - 1) / tile_rows);
+    const gemm_tile_plan full = make_tile_plan(tile_rows, CB, RINGB, NW, NL, K);
+    const gemm_tile_plan tail = make_tile_plan(M - tile_rows * ((M - 1) / tile_rows), CB, RINGB, NW, NL, K);
+    hipLaunchKernelGGL((gemm_kernel<CB, RINGB, EPI, NW, NL, PCB>), grid, dim3(64 * (NW + NL)), 0, s,
                        static_cast<const uint16_t*>(A), lda, static_cast<const uint4*>(Bp), C, ldc,
                        static_cast<const uint16_t*>(R), ldr, K, out_f32, full, tail);
 }
@@ -554,6 +577,26 @@ static int gemm_dispatch(const void* A, int lda, const void* Bp, void* C, int ld
 {
     const int cb = gemm_cols_per_block(N);
     const bool small = gemm_small_ring(N);
+    // Tall launches of narrow matrices.  A workgroup reads every row of its tile of A and every column
+    // of its tile of the weights once, and what bounds a tall tile is the bytes through the compute
+    // unit's memory pipe, so a 256-row x 16- or 32-column tile (all of A for a sliver of the weights) is
+    // the wrong shape from about a hundred rows on: 64-column tiles of M/row_tiles rows, with row_tiles
+    // chosen so that the grid still fits the chip in one round, move up to half as many bytes per
+    // compute unit (measured: K = 14336, N = 4096 at M = 256 in 63 us instead of 112).  The weights stay
+    // packed as they are (the workgroup streams 4/cb adjacent slabs).  The arithmetic of an output
+    // element is the same chain of matrix-core steps in either tiling, so its bytes do not depend on
+    // which ran; the thresholds are where the measured times cross.
+    if (!small && N % 64 == 0 && ((cb == 1 && M >= 96) || (cb == 2 && M >= 192))) {
+        const int row_tiles = 256 / (N / 64) > 0 ? 256 / (N / 64) : 1;
+        // a tile holds at most 256 rows (16 row blocks); longer launches take several rounds of those
+        const int even = 16 * (((M + 15) / 16 + row_tiles - 1) / row_tiles);
+        const int rows = even < 256 ? even : 256;
+        if (cb == 1)
+            launch_gemm<4, kRingBig, EPI, 8, 4, 1>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s, rows);
+        else
+            launch_gemm<4, kRingBig, EPI, 8, 4, 2>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s, rows);
+        return check_launch();
+    }
 #define DET_GEMM_CASE(CBV)                                                                                  \
     case CBV:                                                                                               \
         if constexpr (CBV <= 3) {                                                                           \

@@ -135,6 +135,39 @@ def test_llama_shapes_sampled_vs_oracle_and_batch_invariance(d, orc, K, N):
     assert within_bound(got, ref, refabs).all()
 
 
+@pytest.mark.parametrize("K,N", [(4096, 4096), (1024, 6144), (512, 1024), (14336, 4096)])
+def test_tile_shape_switch_points_keep_bytes(d, orc, K, N):
+    """Narrow matrices change tile shape with M (16- or 32-column tiles of up to 256 rows below 96 or 192
+    rows, 64-column tiles of fewer rows from there on; M = 1100 is more rows than one round of tiles
+    holds, with a ragged last tile): every row's bytes are those of the M = 1 launch that computes it
+    alone, and a sample agrees with fp64."""
+    X = ds.normal_bf16(ds.tensor_seed(3, K), (1100, K))
+    W = ds.normal_bf16(ds.tensor_seed(3, N), (K, N), 0.02)
+    Wp = d.pack_weight(up_bf16(W))
+    Xd = up_bf16(X)
+
+    def gemm(lo, hi):
+        C = torch.empty((hi - lo, N), dtype=torch.bfloat16, device=DEV)
+        d.det_gemm_bf16(Xd[lo:hi], Wp, C, N, K)
+        torch.cuda.synchronize()
+        return down_bf16(C)
+
+    step(f"gemm tile switch K={K} N={N} M=1100")
+    full = gemm(0, 1100)
+    for M in [1, 17, 95, 96, 97, 111, 129, 160, 191, 192, 193, 255, 256, 257, 513, 1025]:
+        step(f"gemm tile switch K={K} N={N} M={M}")
+        assert np.array_equal(gemm(0, M), full[:M]), f"rows changed between M={M} and M=1100"
+    for r in [0, 95, 96, 200, 255, 256, 512, 1099]:
+        assert np.array_equal(gemm(r, r + 1)[0], full[r]), f"row {r} alone differs"
+    rng = np.random.default_rng(K * 3 + N)
+    rows = rng.integers(0, 1100, 2048).astype(np.int32)
+    cols = rng.integers(0, N, 2048).astype(np.int32)
+    rows[:16] = 1099
+    cols[:16] = N - 1 - np.arange(16) * 5
+    ref, refabs = orc.gemm_f64_sample(X, W, rows, cols)
+    assert within_bound(bits_to_f64(full[rows, cols]), ref, refabs).all()
+
+
 def test_rows_do_not_see_each_other(d, orc):
     """Row i's bytes are unchanged when the other rows are replaced, when row i moves to another
     slot, and when M is not a multiple of the row block."""
@@ -220,7 +253,8 @@ def test_error_codes(d):
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("M,K,N", [(1, 512, 4096), (19, 4096, 4096), (130, 1024, 28672), (64, 5632, 2048)])
+@pytest.mark.parametrize("M,K,N", [(1, 512, 4096), (19, 4096, 4096), (130, 1024, 28672), (64, 5632, 2048), (200, 1024, 4096),
+                                   (250, 512, 6144)])
 def test_fused_residual_epilogue_equals_unfused_bytes(d, orc, M, K, N):
     """det_gemm_bf16_residual = det_gemm_bf16 then det_residual_add, byte for byte (and the oracle's
     residual of the GPU's own GEMM output), also in place (C is R)."""
@@ -244,7 +278,8 @@ def test_fused_residual_epilogue_equals_unfused_bytes(d, orc, M, K, N):
     assert np.array_equal(down_bf16(fused), orc.residual(R, down_bf16(plain)))
 
 
-@pytest.mark.parametrize("M,K,F", [(1, 512, 2048), (33, 4096, 14336), (7, 2048, 5632), (200, 256, 1000 * 8)])
+@pytest.mark.parametrize("M,K,F", [(1, 512, 2048), (33, 4096, 14336), (7, 2048, 5632), (200, 256, 1000 * 8),
+                                   (130, 512, 2048)])
 def test_fused_swiglu_epilogue_equals_unfused_bytes(d, orc, M, K, F):
     """det_gemm_swiglu_bf16 on the gate/up-interleaved packing = det_gemm_bf16 on the plain packing
     then det_swiglu, byte for byte."""
