@@ -561,7 +561,7 @@ template <int CB, int RINGB, int EPI, int NW, int NL, int PCB = CB>
 static void launch_gemm(const void* A, int lda, const void* Bp, void* C, int ldc, const void* R, int ldr, int M,
                         int N, int K, int out_f32, hipStream_t s, int tile_rows = 256)
 {
-    if (tile_rows < 16 || tile_rows > 256 || tile_rows % 16 != 0) abort();  // the kernel's row blocks: 1..16 of 16 rows
+    // tile_rows: a multiple of 16 in 16..256 (the kernel handles 1..16 row blocks of 16 rows)
     dim3 grid(N / (16 * CB), (M + tile_rows - 1) / tile_rows);
     const gemm_tile_plan full = make_tile_plan(tile_rows, CB, RINGB, NW, NL, K);
     const gemm_tile_plan tail = make_tile_plan(M - tile_rows * ((M - 1) / tile_rows), CB, RINGB, NW, NL, K);
