@@ -288,6 +288,42 @@ def qgemm_w4a8(p, d, q, s) -> tuple[np.ndarray, np.ndarray]:
     return acc, c
 
 
+def qlinear(a_bits, q, s) -> np.ndarray:
+    """bf16 activations through a quantized projection: quantize the rows (quant_a8), contract with the
+    weight codes and scales (qgemm_w4a8), return the bf16 bits of the result."""
+    p, d = quant_a8(a_bits)
+    return qgemm_w4a8(p, d, q, s)[1]
+
+
+def qdecoder_layer(x, w, kcache, vcache, positions, cos_t, sin_t, cfg):
+    """One decoder layer with every projection block-quantized: the steps of decoder_layer in the same
+    order, each projection replaced by qlinear on the bf16 activations it would have taken.  `w` holds
+    norm1, norm2 (bf16 bits) and wqkv, wo, wgu, wdown as (codes int8 [K,N], scales bf16 bits [K/64,N])
+    pairs from quant_w4 of the logical weights (wgu columns: F gate then F up).  Attention is the fp64
+    reference rounded once to bf16.  Returns the new x; the caches are updated in place."""
+    x = _u16(x).copy()
+    B, H = x.shape
+    positions, cos_t, sin_t = _i32(positions), _f32(cos_t), _f32(sin_t)
+    Hq, Hkv, D, F, Lmax = cfg["Hq"], cfg["Hkv"], cfg["D"], cfg["F"], cfg["Lmax"]
+    assert kcache.dtype == np.uint16 and kcache.flags.c_contiguous and kcache.shape == (B, Hkv, Lmax, D)
+    assert vcache.dtype == np.uint16 and vcache.flags.c_contiguous and vcache.shape == kcache.shape
+    h = rmsnorm(x, w["norm1"], cfg["eps"])
+    qkv = qlinear(h, *w["wqkv"])
+    q_rot = rope(np.ascontiguousarray(qkv[:, :Hq * D]).reshape(B, Hq, D), positions, cos_t, sin_t)
+    k_rot = rope(np.ascontiguousarray(qkv[:, Hq * D:(Hq + Hkv) * D]).reshape(B, Hkv, D), positions, cos_t, sin_t)
+    v_new = qkv[:, (Hq + Hkv) * D:].reshape(B, Hkv, D)
+    for b in range(B):
+        kcache[b, :, positions[b]] = k_rot[b]
+        vcache[b, :, positions[b]] = v_new[b]
+    att, _ = attn_decode_f64(q_rot, kcache, vcache, positions + 1, cfg["scale"])
+    att = bf16_from_f64(att).reshape(B, Hq * D)
+    x = residual(x, qlinear(att, *w["wo"]))
+    h = rmsnorm(x, w["norm2"], cfg["eps"])
+    gu = qlinear(h, *w["wgu"])
+    mm = swiglu(np.ascontiguousarray(gu[:, :F]), np.ascontiguousarray(gu[:, F:]))
+    return residual(x, qlinear(mm, *w["wdown"]))
+
+
 def commit_sha256(prompt: bytes, logits: bytes, tokens: bytes) -> bytes:
     """The digest the paper records per execution (section 6.7): SHA-256 of the three byte strings
     concatenated in that order.  The hash itself is the standard library's (a library primitive as a

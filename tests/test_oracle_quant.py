@@ -109,3 +109,61 @@ def test_qgemm_against_fp64_and_against_the_unquantized_product(orc):
     exact = f32(x).astype(np.float64) @ f32(w).astype(np.float64)           # what is being approximated
     rel = np.linalg.norm(ref - exact) / np.linalg.norm(exact)
     assert 0.01 < rel < 0.15, rel                                           # 4-bit weights: a few per cent
+
+
+def test_quantized_layer_tracks_the_bf16_layer(orc):
+    """qdecoder_layer is decoder_layer with quantized projections: on a small layer its branch update
+    x' - x and its new cache rows stay within the quantization noise of the fp64-reference layer
+    (4-bit weights: about 12 % of a projection's output), and far from it when a step is wrong (the
+    same check fails with gate and up swapped or the rotation skipped, see the planted cases)."""
+    cfg = dict(H=256, Hq=2, Hkv=1, D=128, F=192, Lmax=16, eps=1e-5, scale=float(np.float32(128.0 ** -0.5)))
+    H, Hq, Hkv, D, F, Lmax = (cfg[k] for k in ("H", "Hq", "Hkv", "D", "F", "Lmax"))
+    s0 = ds.tensor_seed(6, 40)
+    w = dict(norm1=ds.normal_bf16(s0, (H,), 0.1, 1.0), norm2=ds.normal_bf16(s0 + 1, (H,), 0.1, 1.0),
+             wqkv=ds.normal_bf16(s0 + 2, (H, (Hq + 2 * Hkv) * D), 0.06, 0.0),
+             wo=ds.normal_bf16(s0 + 3, (Hq * D, H), 0.06, 0.0),
+             wgu=ds.normal_bf16(s0 + 4, (H, 2 * F), 0.06, 0.0),
+             wdown=ds.normal_bf16(s0 + 5, (F, H), 0.06, 0.0))
+    B = 3
+    x = ds.normal_bf16(s0 + 6, (B, H), 1.0, 0.0)
+    kc = ds.normal_bf16(s0 + 7, (B, Hkv, Lmax, D), 1.0, 0.0)
+    vc = ds.normal_bf16(s0 + 8, (B, Hkv, Lmax, D), 1.0, 0.0)
+    pos = np.asarray([15, 4, 0], dtype=np.int32)
+    cos_t, sin_t = ds.rope_tables(Lmax, D, 5.0e5)
+    kr, vr = kc.copy(), vc.copy()
+    ref = orc.decoder_layer(x, w, kr, vr, pos, cos_t, sin_t, cfg)
+
+    def run(wq, cos=cos_t, sin=sin_t):
+        kq, vq = kc.copy(), vc.copy()
+        return orc.qdecoder_layer(x, wq, kq, vq, pos, cos, sin, cfg), kq, vq
+
+    wq = {k: (v if v.ndim == 1 else orc.quant_w4(v)) for k, v in w.items()}
+    got, kq, vq = run(wq)
+
+    def rel(a, b):
+        a, b = f32(a).astype(np.float64), f32(b).astype(np.float64)
+        return np.sqrt(((a - b) ** 2).mean() / (b ** 2).mean())
+
+    upd_ref = f32(ref).astype(np.float64) - f32(x)
+    upd_got = f32(got).astype(np.float64) - f32(x)
+    err = np.sqrt(((upd_got - upd_ref) ** 2).mean() / (upd_ref ** 2).mean())
+    assert err < 0.3, err
+    for b, p in enumerate(pos):
+        assert rel(kq[b, :, p], kr[b, :, p]) < 0.25 and rel(vq[b, :, p], vr[b, :, p]) < 0.25
+        mask = np.ones(Lmax, dtype=bool)
+        mask[p] = False
+        assert np.array_equal(kq[b][:, mask], kc[b][:, mask]) and np.array_equal(vq[b][:, mask], vc[b][:, mask])
+    # planted mistakes in the inputs move the result far outside that bound
+    swapped = dict(wq)
+    gu = w["wgu"]
+    swapped["wgu"] = orc.quant_w4(np.ascontiguousarray(np.concatenate([gu[:, F:], gu[:, :F]], axis=1)))
+    bad, _, _ = run(swapped)
+    assert np.sqrt((((f32(bad).astype(np.float64) - f32(x)) - upd_ref) ** 2).mean() / (upd_ref ** 2).mean()) > 0.5
+    _, k_norot, _ = run(wq, np.ones_like(cos_t), np.zeros_like(sin_t))
+    assert rel(k_norot[0, :, 15], kr[0, :, 15]) > 0.5
+    # a layer whose output projections are zero leaves x unchanged and still appends the cache rows
+    zeroed = dict(wq)
+    zeroed["wo"] = orc.quant_w4(np.zeros_like(w["wo"]))
+    zeroed["wdown"] = orc.quant_w4(np.zeros_like(w["wdown"]))
+    same, kz, _ = run(zeroed)
+    assert np.array_equal(same, x) and np.array_equal(kz, kq)
