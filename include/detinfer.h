@@ -281,6 +281,36 @@ int det_quant_act_q8(const void *A, int lda, void *codes, void *scales, int M, i
 int det_qgemm_w4a8(const void *codes, const void *scales, const void *packed_w, void *C, int ldc, int M,
                    int N, int K, int out_dtype, void *stream);
 
+/* Fused forms for the quantized decoder layer; each gives the bytes of the unfused sequence.
+ * det_quant_pack_w4_gate_up: det_quant_pack_w4 of a [K, 2F] matrix (F gate columns, then F up columns)
+ *   with gate_j and up_j made neighbours, for det_qgemm_w4a8_swiglu.  F % 8 == 0.
+ * det_qgemm_w4a8_residual: C = det_residual_add(R, det_qgemm_w4a8(...) as bf16); C may be R.  R bf16 [M,N]
+ *   with row stride ldr (ldr % 4 == 0).
+ * det_qgemm_w4a8_swiglu: Y[M,F] = det_swiglu(g, u), [g | u] = det_qgemm_w4a8 of the [K, 2F] matrix as bf16;
+ *   packed_gate_up from det_quant_pack_w4_gate_up; ldy >= F, ldy % 4 == 0.
+ * det_rmsnorm_quant_q8: det_quant_act_q8(det_rmsnorm(x, w)) without the bf16 round trip through memory:
+ *   codes int8 [M,H] and scales as det_quant_act_q8 writes them for (M, K = H).  H % 64 == 0, H <= 16384. */
+int det_quant_pack_w4_gate_up(const void *B_kn, void *packed, int F, int K, void *stream);
+int det_qgemm_w4a8_residual(const void *codes, const void *scales, const void *packed_w, const void *R,
+                            int ldr, void *C, int ldc, int M, int N, int K, void *stream);
+int det_qgemm_w4a8_swiglu(const void *codes, const void *scales, const void *packed_gate_up, void *Y,
+                          int ldy, int M, int F, int K, void *stream);
+int det_rmsnorm_quant_q8(const void *x, const void *w, void *codes, void *scales, int M, int H, float eps,
+                         void *stream);
+
+/* The decoder layer with every projection block-quantized (the engine the paper measures runs
+ * quantized models, section 6.4): the steps of det_decoder_layer in the same order, each projection
+ * det_qgemm_w4a8 on the det_quant_act_q8 codes of the bf16 activations it would have taken.  Weights:
+ * w_norm1, w_norm2 bf16 [H]; wqkv, wo, wdown from det_quant_pack_w4; wgu from
+ * det_quant_pack_w4_gate_up.  Other arguments as det_decoder_layer_rows; slots may be NULL (row r is
+ * the sequence in cache slot r).  Same invariance: a row's bytes and its cache rows do not depend on
+ * R or on the other rows.  Workspace: det_qdecoder_layer_workspace_bytes(cfg, R). */
+size_t det_qdecoder_layer_workspace_bytes(const det_layer_cfg *cfg /* host */, int R);
+int det_qdecoder_layer(const det_layer_weights *w, const det_layer_cfg *cfg, void *x_inout, void *kcache,
+                       void *vcache, const int32_t *positions, const int32_t *slots,
+                       const float *rope_cos, const float *rope_sin, void *ws, size_t ws_bytes, int R,
+                       void *stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Output commitment (the paper's section 6.7 records SHA256(prompt || logits || tokens) for every
  * execution, and a receipt commits to the output by its hash, section 4.1).  HOST code on HOST

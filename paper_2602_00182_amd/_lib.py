@@ -58,6 +58,13 @@ SIGNATURES = {
     "det_quant_act_scales_bytes": (_sz, [_i, _i]),
     "det_quant_act_q8": (_i, [_vp, _i, _vp, _vp, _i, _i, _vp]),
     "det_qgemm_w4a8": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp]),
+    "det_quant_pack_w4_gate_up": (_i, [_vp, _vp, _i, _i, _vp]),
+    "det_qgemm_w4a8_residual": (_i, [_vp, _vp, _vp, _vp, _i, _vp, _i, _i, _i, _i, _vp]),
+    "det_qgemm_w4a8_swiglu": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),
+    "det_rmsnorm_quant_q8": (_i, [_vp, _vp, _vp, _vp, _i, _i, _f, _vp]),
+    "det_qdecoder_layer_workspace_bytes": (_sz, [C.POINTER(LayerCfg), _i]),
+    "det_qdecoder_layer": (_i, [C.POINTER(LayerWeights), C.POINTER(LayerCfg), _vp, _vp, _vp, _vp, _vp, _vp, _vp,
+                                _vp, _sz, _i, _vp]),
     "det_sha256_init": (_i, [C.POINTER(Sha256Ctx)]),
     "det_sha256_update": (_i, [C.POINTER(Sha256Ctx), _vp, _sz]),
     "det_sha256_final": (_i, [C.POINTER(Sha256Ctx), _vp]),

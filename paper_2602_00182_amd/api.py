@@ -20,7 +20,9 @@ __all__ = [
     "layer_weights", "pack_weight", "det_sha256_init", "det_sha256_update", "det_sha256_final",
     "det_commit_sha256", "det_sha256_force_portable", "det_qgemm_packed_w_bytes", "det_quant_pack_w4",
     "det_quant_unpack_w4", "det_quant_act_codes_bytes", "det_quant_act_scales_bytes", "det_quant_act_q8",
-    "det_qgemm_w4a8", "quant_pack_weight", "quant_activations",
+    "det_qgemm_w4a8", "quant_pack_weight", "quant_activations", "det_qgemm_w4a8_residual",
+    "det_qgemm_w4a8_swiglu", "det_quant_pack_w4_gate_up", "quant_pack_gate_up", "det_rmsnorm_quant_q8",
+    "det_qdecoder_layer_workspace_bytes", "det_qdecoder_layer",
 ]
 
 _CODES = {1: "DET_EINVAL", 2: "DET_ESHAPE", 3: "DET_EALIGN", 4: "DET_EWORKSPACE", 5: "DET_EHIP"}
@@ -102,6 +104,48 @@ def det_qgemm_w4a8(codes, scales, packed_w, c, N: int, stream=None) -> None:
     _check("det_qgemm_w4a8", lib().det_qgemm_w4a8(_contig(codes, torch.int8), _contig(scales, torch.float32),
                                                     _contig(packed_w), _ptr(c), c.stride(0), M, N, K, out_dtype,
                                                     _stream(stream)))
+
+
+def det_qgemm_w4a8_residual(codes, scales, packed_w, r, c, N: int, stream=None) -> None:
+    """c = bf16(fp32(bf16(qgemm)) + fp32(r)); c may be r."""
+    M, K = codes.shape
+    if c.shape != (M, N) or r.shape != (M, N) or c.stride(1) != 1 or r.stride(1) != 1:
+        raise ValueError("bad output shape")
+    _check("det_qgemm_w4a8_residual", lib().det_qgemm_w4a8_residual(
+        _contig(codes, torch.int8), _contig(scales, torch.float32), _contig(packed_w), _ptr(r, torch.bfloat16),
+        _ld(r, N), _ptr(c, torch.bfloat16), _ld(c, N), M, N, K, _stream(stream)))
+
+
+def det_qgemm_w4a8_swiglu(codes, scales, packed_gate_up, y, F: int, stream=None) -> None:
+    M, K = codes.shape
+    if y.shape != (M, F) or y.stride(1) != 1:
+        raise ValueError("bad output shape")
+    _check("det_qgemm_w4a8_swiglu", lib().det_qgemm_w4a8_swiglu(
+        _contig(codes, torch.int8), _contig(scales, torch.float32), _contig(packed_gate_up),
+        _ptr(y, torch.bfloat16), _ld(y, F), M, F, K, _stream(stream)))
+
+
+def det_quant_pack_w4_gate_up(b_kn, packed, stream=None) -> None:
+    K, N2 = b_kn.shape
+    _check("det_quant_pack_w4_gate_up", lib().det_quant_pack_w4_gate_up(
+        _contig(b_kn, torch.bfloat16), _contig(packed), N2 // 2, K, _stream(stream)))
+
+
+def quant_pack_gate_up(b_kn: torch.Tensor) -> torch.Tensor:
+    """Allocates and fills the packed 4-bit form of a [K, 2F] (gate | up) weight for det_qgemm_w4a8_swiglu."""
+    K, N2 = b_kn.shape
+    packed = torch.empty(det_qgemm_packed_w_bytes(N2, K), dtype=torch.uint8, device=b_kn.device)
+    det_quant_pack_w4_gate_up(b_kn.contiguous(), packed)
+    return packed
+
+
+def det_rmsnorm_quant_q8(x, w, codes, scales, eps: float, stream=None) -> None:
+    M, H = x.shape
+    if w.shape != (H,) or codes.shape != (M, H) or scales.numel() * 4 < det_quant_act_scales_bytes(M, H):
+        raise ValueError("bad RMSNorm/quantizer shapes")
+    _check("det_rmsnorm_quant_q8", lib().det_rmsnorm_quant_q8(
+        _contig(x, torch.bfloat16), _contig(w, torch.bfloat16), _contig(codes, torch.int8),
+        _contig(scales, torch.float32), M, H, eps, _stream(stream)))
 
 
 def quant_pack_weight(b_kn: torch.Tensor) -> torch.Tensor:
@@ -410,6 +454,33 @@ def det_decoder_layer_rows(w: LayerWeights, cfg: LayerCfg, x, kcache, vcache, po
     _check("det_decoder_layer_rows", lib().det_decoder_layer_rows(
         C.byref(w), C.byref(cfg), _contig(x, torch.bfloat16), _contig(kcache, torch.bfloat16),
         _contig(vcache, torch.bfloat16), _contig(positions, torch.int32), _contig(slots, torch.int32),
+        _contig(rope_cos, torch.float32), _contig(rope_sin, torch.float32), _contig(ws),
+        ws.numel() * ws.element_size(), R, _stream(stream)))
+
+
+def det_qdecoder_layer_workspace_bytes(cfg: LayerCfg, R: int) -> int:
+    return lib().det_qdecoder_layer_workspace_bytes(C.byref(cfg), R)
+
+
+def det_qdecoder_layer(w: LayerWeights, cfg: LayerCfg, x, kcache, vcache, positions, slots, rope_cos, rope_sin,
+                       ws, stream=None) -> None:
+    """The decoder layer on quantized weights; slots may be None (row r uses cache slot r)."""
+    R = x.shape[0]
+    if x.shape != (R, cfg.H) or kcache.shape[1:] != (cfg.Hkv, cfg.Lmax, cfg.D) or vcache.shape != kcache.shape:
+        raise ValueError("bad layer shapes")
+    if positions.shape != (R,) or rope_cos.shape != (cfg.Lmax, cfg.D // 2):
+        raise ValueError("bad layer shapes")
+    if slots is None:
+        if kcache.shape[0] < R:
+            raise ValueError("bad layer shapes")
+        sl = None
+    else:
+        if slots.shape != (R,):
+            raise ValueError("bad layer shapes")
+        sl = _contig(slots, torch.int32)
+    _check("det_qdecoder_layer", lib().det_qdecoder_layer(
+        C.byref(w), C.byref(cfg), _contig(x, torch.bfloat16), _contig(kcache, torch.bfloat16),
+        _contig(vcache, torch.bfloat16), _contig(positions, torch.int32), sl,
         _contig(rope_cos, torch.float32), _contig(rope_sin, torch.float32), _contig(ws),
         ws.numel() * ws.element_size(), R, _stream(stream)))
 

@@ -101,6 +101,51 @@ __device__ __forceinline__ float block_max(float v, float* scratch)
     return fmaxf(fmaxf(scratch[0], scratch[1]), fmaxf(scratch[2], scratch[3]));
 }
 
+// Epilogues.  kEpiStore: C = bf16(acc) or fp32 acc.  kEpiResidual: C = bf16(fp32(bf16(acc)) + fp32(R)),
+// the bytes of the plain GEMM followed by the residual add.  kEpiSwiglu: the weight columns are packed
+// gate_j, up_j interleaved, and Y[j] = bf16( silu(bf16(acc_gate_j)) * bf16(acc_up_j) ), the bytes of the
+// plain GEMM followed by the SwiGLU step.  C (and R) may alias nothing the kernel reads except that C
+// may be R itself: an output element is read and written by the same lane only.
+constexpr int kEpiStore = 0, kEpiResidual = 1, kEpiSwiglu = 2;
+
+__device__ __forceinline__ float silu_mul(float gate, float up)
+{
+    const float den = 1.0f + det_expf(-gate);
+    const float sg = gate / den;
+    return sg * up;
+}
+
+// The epilogue of one lane's four consecutive output columns v[0..3] of row `row`, first column n
+// (both GEMM kernels end with a lane holding exactly that).
+template <int EPI>
+__device__ __forceinline__ void gemm_epilogue_store(const float (&v)[4], void* C, int ldc, const uint16_t* R, int ldr,
+                                                    size_t row, int n, int out_f32)
+{
+    if constexpr (EPI == kEpiSwiglu) {
+        const float g0 = bf16_to_f32(f32_to_bf16_rne(v[0])), u0 = bf16_to_f32(f32_to_bf16_rne(v[1]));
+        const float g1 = bf16_to_f32(f32_to_bf16_rne(v[2])), u1 = bf16_to_f32(f32_to_bf16_rne(v[3]));
+        uint32_t* dst = reinterpret_cast<uint32_t*>(static_cast<uint16_t*>(C) + row * ldc + (n >> 1));
+        *dst = pack_bf16x2(silu_mul(g0, u0), silu_mul(g1, u1));
+    } else if constexpr (EPI == kEpiResidual) {
+        const uint2 rv = *reinterpret_cast<const uint2*>(R + row * ldr + n);
+        float y[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) y[e] = bf16_to_f32(f32_to_bf16_rne(v[e]));
+        y[0] = y[0] + bf16lo_to_f32(rv.x);
+        y[1] = y[1] + bf16hi_to_f32(rv.x);
+        y[2] = y[2] + bf16lo_to_f32(rv.y);
+        y[3] = y[3] + bf16hi_to_f32(rv.y);
+        uint2* dst = reinterpret_cast<uint2*>(static_cast<uint16_t*>(C) + row * ldc + n);
+        *dst = make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
+    } else if (out_f32) {
+        float4* dst = reinterpret_cast<float4*>(static_cast<float*>(C) + row * ldc + n);
+        *dst = make_float4(v[0], v[1], v[2], v[3]);
+    } else {
+        uint2* dst = reinterpret_cast<uint2*>(static_cast<uint16_t*>(C) + row * ldc + n);
+        *dst = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+    }
+}
+
 // ---------------------------------------------------------------- host side
 
 void set_last_hip_error(int e);

@@ -74,20 +74,6 @@ bool gemm_small_ring(int N)
 }
 
 
-// Epilogues.  kEpiStore: C = bf16(acc) or fp32 acc.  kEpiResidual: C = bf16(fp32(bf16(acc)) + fp32(R)),
-// the bytes of the plain GEMM followed by the residual add.  kEpiSwiglu: the weight columns are packed
-// gate_j, up_j interleaved, and Y[j] = bf16( silu(bf16(acc_gate_j)) * bf16(acc_up_j) ), the bytes of the
-// plain GEMM followed by the SwiGLU step.  C (and R) may alias nothing the kernel reads except that C
-// may be R itself: an output element is read and written by the same lane only.
-constexpr int kEpiStore = 0, kEpiResidual = 1, kEpiSwiglu = 2;
-
-__device__ __forceinline__ float silu_mul(float gate, float up)
-{
-    const float den = 1.0f + det_expf(-gate);
-    const float sg = gate / den;
-    return sg * up;
-}
-
 // LDS reads the compiler does not see.  Its own bookkeeping of the LDS counter waits for every read in
 // flight before the first use of any of them once reads cross a loop back edge; written by hand, the
 // wait before a matrix-core step can leave the reads of the following step in flight.  tie() makes a
@@ -481,30 +467,9 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
 #pragma unroll
                 for (int j = 0; j < CB; ++j) {
                     const int n = n0 + 16 * j + 4 * g;
-                    const f32x4 v = acc[r][j];
-                    if constexpr (EPI == kEpiSwiglu) {
-                        const float g0 = bf16_to_f32(f32_to_bf16_rne(v[0])), u0 = bf16_to_f32(f32_to_bf16_rne(v[1]));
-                        const float g1 = bf16_to_f32(f32_to_bf16_rne(v[2])), u1 = bf16_to_f32(f32_to_bf16_rne(v[3]));
-                        uint32_t* dst = reinterpret_cast<uint32_t*>(static_cast<uint16_t*>(C) + row * ldc + (n >> 1));
-                        *dst = pack_bf16x2(silu_mul(g0, u0), silu_mul(g1, u1));
-                    } else if constexpr (EPI == kEpiResidual) {
-                        const uint2 rv = *reinterpret_cast<const uint2*>(R + row * ldr + n);
-                        float y[4];
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) y[e] = bf16_to_f32(f32_to_bf16_rne(v[e]));
-                        y[0] = y[0] + bf16lo_to_f32(rv.x);
-                        y[1] = y[1] + bf16hi_to_f32(rv.x);
-                        y[2] = y[2] + bf16lo_to_f32(rv.y);
-                        y[3] = y[3] + bf16hi_to_f32(rv.y);
-                        uint2* dst = reinterpret_cast<uint2*>(static_cast<uint16_t*>(C) + row * ldc + n);
-                        *dst = make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
-                    } else if (out_f32) {
-                        float4* dst = reinterpret_cast<float4*>(static_cast<float*>(C) + row * ldc + n);
-                        *dst = make_float4(v[0], v[1], v[2], v[3]);
-                    } else {
-                        uint2* dst = reinterpret_cast<uint2*>(static_cast<uint16_t*>(C) + row * ldc + n);
-                        *dst = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
-                    }
+                    const f32x4 a4 = acc[r][j];
+                    const float v[4] = {a4[0], a4[1], a4[2], a4[3]};
+                    gemm_epilogue_store<EPI>(v, C, ldc, R, ldr, row, n, out_f32);
                 }
             }
         }

@@ -48,18 +48,20 @@ __host__ __device__ constexpr int qstage_w_bytes(int cb) { return 544 * cb; }
 // j: 64 lanes x 8 bytes at j*512 (lane = 16*g + column%16 holds the codes of k = 16g .. 16g+15 of the
 // stage: dword t = 0,1, byte i = 0..3: low nibble = code of k = 16g + 8t + i, high nibble = code of
 // k = 16g + 8t + 4 + i, each stored as q + 8); then at 512*cb the scales, 16 bf16 per column block.
+// gate_up_f > 0: packed column 2j is logical column j (gate) and 2j+1 is gate_up_f + j (up).
 __global__ __launch_bounds__(256) void quant_pack_w4_kernel(const uint16_t* __restrict__ W, uint8_t* __restrict__ packed,
-                                                            int N, int K, int cb)
+                                                            int N, int K, int cb, int gate_up_f)
 {
     const int nblk = K >> 6;
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (size_t)nblk * N) return;
     const int n = (int)(idx % N), b = (int)(idx / N);
+    const int nsrc = gate_up_f > 0 ? ((n & 1) ? gate_up_f + (n >> 1) : (n >> 1)) : n;
     float w[64];
     float amax = 0.0f;
 #pragma unroll
     for (int k = 0; k < 64; ++k) {
-        w[k] = bf16_to_f32(W[(size_t)(64 * b + k) * N + n]);
+        w[k] = bf16_to_f32(W[(size_t)(64 * b + k) * N + nsrc]);
         amax = fmaxf(amax, fabsf(w[k]));
     }
     const uint16_t sb = f32_to_bf16_rne(amax / 7.0f);
@@ -172,10 +174,12 @@ static qgemm_plan make_qgemm_plan(int mrem, int cb, int K)
     return t;
 }
 
-template <int CB>
+// EPI: the epilogues of the bf16 kernel (plain store, residual add, SwiGLU on gate/up-interleaved columns),
+// applied to the accumulator rounded to bf16, so each gives the bytes of the unfused sequence.
+template <int CB, int EPI>
 __global__ __launch_bounds__(64 * (kQWaves + kQLoaders)) void qgemm_kernel(
     const int8_t* __restrict__ qa, int K, const float* __restrict__ da, int ldd, const uint8_t* __restrict__ wp, void* C,
-    int ldc, int out_f32, qgemm_plan plan_full, qgemm_plan plan_tail)
+    int ldc, const uint16_t* R, int ldr, int out_f32, qgemm_plan plan_full, qgemm_plan plan_tail)
 {
     __shared__ uint4 ring[kQRing * 64];
     constexpr int RG = 8 / CB;        // row groups: wave w computes column block w % CB for row group w / CB
@@ -351,13 +355,8 @@ __global__ __launch_bounds__(64 * (kQWaves + kQLoaders)) void qgemm_kernel(
             const int rowl = 16 * rbs[r] + lr;
             if (r < cnt && rowl < mrem) {
                 const size_t row = (size_t)(m0 + rowl);
-                if (out_f32) {
-                    *reinterpret_cast<float4*>(static_cast<float*>(C) + row * ldc + n) =
-                        make_float4(acc[r][0], acc[r][1], acc[r][2], acc[r][3]);
-                } else {
-                    *reinterpret_cast<uint2*>(static_cast<uint16_t*>(C) + row * ldc + n) =
-                        make_uint2(pack_bf16x2(acc[r][0], acc[r][1]), pack_bf16x2(acc[r][2], acc[r][3]));
-                }
+                const float v[4] = {acc[r][0], acc[r][1], acc[r][2], acc[r][3]};
+                gemm_epilogue_store<EPI>(v, C, ldc, R, ldr, row, n, out_f32);
             }
         }
     };
@@ -375,19 +374,35 @@ __global__ __launch_bounds__(64 * (kQWaves + kQLoaders)) void qgemm_kernel(
     }
 }
 
-template <int CB>
-static void launch_qgemm(const void* qa, const void* da, int ldd, const void* wp, void* C, int ldc, int M, int N, int K,
-                         int out_f32, hipStream_t s)
+static int q_ldd(int M) { return (M + 3) & ~3; }
+
+template <int CB, int EPI>
+static void launch_qgemm(const void* qa, const void* da, int ldd, const void* wp, void* C, int ldc, const void* R, int ldr,
+                         int M, int N, int K, int out_f32, hipStream_t s)
 {
     dim3 grid(N / (16 * CB), (M + 255) / 256);
     const qgemm_plan full = make_qgemm_plan(256, CB, K);
     const qgemm_plan tail = make_qgemm_plan(M - 256 * ((M - 1) / 256), CB, K);
-    hipLaunchKernelGGL((qgemm_kernel<CB>), grid, dim3(64 * (kQWaves + kQLoaders)), 0, s, static_cast<const int8_t*>(qa), K,
-                       static_cast<const float*>(da), ldd, static_cast<const uint8_t*>(wp), C, ldc, out_f32, full, tail);
+    hipLaunchKernelGGL((qgemm_kernel<CB, EPI>), grid, dim3(64 * (kQWaves + kQLoaders)), 0, s,
+                       static_cast<const int8_t*>(qa), K, static_cast<const float*>(da), ldd, static_cast<const uint8_t*>(wp),
+                       C, ldc, static_cast<const uint16_t*>(R), ldr, out_f32, full, tail);
+}
+
+// N: columns of the packed matrix (2F for the SwiGLU epilogue).
+template <int EPI>
+static int qgemm_dispatch(const void* codes, const void* scales, const void* packed_w, void* C, int ldc, const void* R,
+                          int ldr, int M, int N, int K, int f32, hipStream_t s)
+{
+    switch (qgemm_cols_per_block(N)) {
+        case 1: launch_qgemm<1, EPI>(codes, scales, q_ldd(M), packed_w, C, ldc, R, ldr, M, N, K, f32, s); break;
+        case 2: launch_qgemm<2, EPI>(codes, scales, q_ldd(M), packed_w, C, ldc, R, ldr, M, N, K, f32, s); break;
+        case 4: launch_qgemm<4, EPI>(codes, scales, q_ldd(M), packed_w, C, ldc, R, ldr, M, N, K, f32, s); break;
+        default: launch_qgemm<8, EPI>(codes, scales, q_ldd(M), packed_w, C, ldc, R, ldr, M, N, K, f32, s); break;
+    }
+    return check_launch();
 }
 
 static bool qgemm_shape_ok(int N, int K) { return N > 0 && K > 0 && N % 16 == 0 && K % 64 == 0 && K <= (1 << 22); }
-static int q_ldd(int M) { return (M + 3) & ~3; }
 
 }  // namespace det
 
@@ -399,7 +414,7 @@ extern "C" size_t det_qgemm_packed_w_bytes(int N, int K)
     return (size_t)(N / 16) * (K / 64) * qstage_w_bytes(1);
 }
 
-extern "C" int det_quant_pack_w4(const void* B_kn, void* packed, int N, int K, void* stream)
+static int quant_pack_impl(const void* B_kn, void* packed, int N, int K, int gate_up_f, void* stream)
 {
     if (!B_kn || !packed) return DET_EINVAL;
     if (!qgemm_shape_ok(N, K)) return DET_ESHAPE;
@@ -407,8 +422,19 @@ extern "C" int det_quant_pack_w4(const void* B_kn, void* packed, int N, int K, v
     const size_t total = (size_t)N * (K / 64);
     hipLaunchKernelGGL(quant_pack_w4_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
                        static_cast<hipStream_t>(stream), static_cast<const uint16_t*>(B_kn), static_cast<uint8_t*>(packed), N,
-                       K, qgemm_cols_per_block(N));
+                       K, qgemm_cols_per_block(N), gate_up_f);
     return check_launch();
+}
+
+extern "C" int det_quant_pack_w4(const void* B_kn, void* packed, int N, int K, void* stream)
+{
+    return quant_pack_impl(B_kn, packed, N, K, 0, stream);
+}
+
+extern "C" int det_quant_pack_w4_gate_up(const void* B_kn, void* packed, int F, int K, void* stream)
+{
+    if (F < 1 || F % 8 != 0) return DET_ESHAPE;
+    return quant_pack_impl(B_kn, packed, 2 * F, K, F, stream);
 }
 
 extern "C" int det_quant_unpack_w4(const void* packed, void* q, void* s, int N, int K, void* stream)
@@ -440,22 +466,44 @@ extern "C" int det_quant_act_q8(const void* A, int lda, void* codes, void* scale
     return check_launch();
 }
 
+static int qgemm_args_ok(const void* codes, const void* scales, const void* packed_w, const void* C, int ldc, int M, int N,
+                         int ncols_out, int K)
+{
+    if (!codes || !scales || !packed_w || !C || M < 1) return DET_EINVAL;
+    if (!qgemm_shape_ok(N, K)) return DET_ESHAPE;
+    if (ldc < ncols_out) return DET_EINVAL;
+    if (!aligned16(codes) || !aligned16(scales) || !aligned16(packed_w) || !aligned16(C) || ldc % 4 != 0 || K % 16 != 0)
+        return DET_EALIGN;
+    return DET_OK;
+}
+
 extern "C" int det_qgemm_w4a8(const void* codes, const void* scales, const void* packed_w, void* C, int ldc, int M, int N,
                               int K, int out_dtype, void* stream)
 {
-    if (!codes || !scales || !packed_w || !C || M < 1) return DET_EINVAL;
     if (out_dtype != DET_BF16 && out_dtype != DET_F32) return DET_EINVAL;
-    if (!qgemm_shape_ok(N, K)) return DET_ESHAPE;
-    if (ldc < N) return DET_EINVAL;
-    if (!aligned16(codes) || !aligned16(scales) || !aligned16(packed_w) || !aligned16(C) || ldc % 4 != 0 || K % 16 != 0)
-        return DET_EALIGN;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const int f32 = out_dtype == DET_F32;
-    switch (qgemm_cols_per_block(N)) {
-        case 1: launch_qgemm<1>(codes, scales, q_ldd(M), packed_w, C, ldc, M, N, K, f32, s); break;
-        case 2: launch_qgemm<2>(codes, scales, q_ldd(M), packed_w, C, ldc, M, N, K, f32, s); break;
-        case 4: launch_qgemm<4>(codes, scales, q_ldd(M), packed_w, C, ldc, M, N, K, f32, s); break;
-        default: launch_qgemm<8>(codes, scales, q_ldd(M), packed_w, C, ldc, M, N, K, f32, s); break;
-    }
-    return check_launch();
+    const int rc = qgemm_args_ok(codes, scales, packed_w, C, ldc, M, N, N, K);
+    if (rc != DET_OK) return rc;
+    return qgemm_dispatch<kEpiStore>(codes, scales, packed_w, C, ldc, nullptr, 0, M, N, K, out_dtype == DET_F32,
+                                     static_cast<hipStream_t>(stream));
+}
+
+extern "C" int det_qgemm_w4a8_residual(const void* codes, const void* scales, const void* packed_w, const void* R, int ldr,
+                                       void* C, int ldc, int M, int N, int K, void* stream)
+{
+    const int rc = qgemm_args_ok(codes, scales, packed_w, C, ldc, M, N, N, K);
+    if (rc != DET_OK) return rc;
+    if (!R || ldr < N) return DET_EINVAL;
+    if (!aligned16(R) || ldr % 4 != 0) return DET_EALIGN;
+    return qgemm_dispatch<kEpiResidual>(codes, scales, packed_w, C, ldc, R, ldr, M, N, K, 0,
+                                        static_cast<hipStream_t>(stream));
+}
+
+extern "C" int det_qgemm_w4a8_swiglu(const void* codes, const void* scales, const void* packed_gate_up, void* Y, int ldy,
+                                     int M, int F, int K, void* stream)
+{
+    if (F < 1 || F % 8 != 0 || F > (1 << 29)) return DET_ESHAPE;
+    const int rc = qgemm_args_ok(codes, scales, packed_gate_up, Y, ldy, M, 2 * F, F, K);
+    if (rc != DET_OK) return rc;
+    return qgemm_dispatch<kEpiSwiglu>(codes, scales, packed_gate_up, Y, ldy, nullptr, 0, M, 2 * F, K, 0,
+                                      static_cast<hipStream_t>(stream));
 }

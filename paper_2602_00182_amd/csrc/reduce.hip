@@ -9,9 +9,15 @@ constexpr int kMaxVecPerThread = 8;  // H <= 8 * 256 * 8 = 16384
 // Row i: thread t owns the 8-element vectors t, t+256, ... (element e -> lane (e/8) mod 256) and
 // folds them in ascending e with fma(x,x,acc); then the 256-leaf tree; then
 // y = bf16((x*r)*w) with r = 1/sqrt(ss/H + eps).
+// QUANT: instead of y the kernel writes y's 8-bit block quantization (the bytes det_quant_act_q8 makes
+// of y: per 64 consecutive elements d = max|y| / 127, code = clamp(rint(y / d))).  A block is the
+// vectors of eight neighbouring threads, so its maximum is three exchanges inside the wave.
+template <bool QUANT>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint4* __restrict__ x,
                                                       const uint4* __restrict__ w,
-                                                      uint4* __restrict__ y, int H, float eps)
+                                                      uint4* __restrict__ y, int H, float eps,
+                                                      int8_t* __restrict__ codes, float* __restrict__ scales,
+                                                      int ldd)
 {
     __shared__ float scratch[4];
     const int nvec = H >> 3;
@@ -56,7 +62,34 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint4* __restrict__ 
                 const float hi = (bf16hi_to_f32(p[k]) * r) * bf16hi_to_f32(q[k]);
                 o[k] = pack_bf16x2(lo, hi);
             }
-            yr[v] = make_uint4(o[0], o[1], o[2], o[3]);
+            if constexpr (!QUANT) {
+                yr[v] = make_uint4(o[0], o[1], o[2], o[3]);
+            } else {
+                float a[8];
+                float amax = 0.0f;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    a[2 * k] = bf16lo_to_f32(o[k]);
+                    a[2 * k + 1] = bf16hi_to_f32(o[k]);
+                    amax = fmaxf(amax, fmaxf(fabsf(a[2 * k]), fabsf(a[2 * k + 1])));
+                }
+                // H % 64 == 0: the eight threads of a block are all here or all absent
+                amax = fmaxf(amax, __shfl_xor(amax, 1, kWave));
+                amax = fmaxf(amax, __shfl_xor(amax, 2, kWave));
+                amax = fmaxf(amax, __shfl_xor(amax, 4, kWave));
+                const float df = amax / 127.0f;
+                uint32_t c[2] = {0u, 0u};
+                if (df != 0.0f) {
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        const float q = rintf(a[k] / df);
+                        const int iv = q < -127.0f ? -127 : (q > 127.0f ? 127 : (int)q);
+                        c[k >> 2] |= (uint32_t)(iv & 0xFF) << (8 * (k & 3));
+                    }
+                }
+                *reinterpret_cast<uint2*>(codes + (size_t)blockIdx.x * H + 8 * (size_t)v) = make_uint2(c[0], c[1]);
+                if ((threadIdx.x & 7) == 0) scales[(size_t)(v >> 3) * ldd + blockIdx.x] = df;
+            }
         }
     }
 }
@@ -168,9 +201,21 @@ extern "C" int det_rmsnorm(const void* x, const void* w, void* y, int M, int H, 
     if (!x || !w || !y || M < 1 || H < 1) return DET_EINVAL;
     if (H % 8 != 0 || H > 8 * 256 * kMaxVecPerThread) return DET_ESHAPE;
     if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return DET_EALIGN;
-    hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, static_cast<hipStream_t>(stream),
+    hipLaunchKernelGGL(rmsnorm_kernel<false>, dim3(M), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<const uint4*>(x), static_cast<const uint4*>(w), static_cast<uint4*>(y),
-                       H, eps);
+                       H, eps, nullptr, nullptr, 0);
+    return check_launch();
+}
+
+extern "C" int det_rmsnorm_quant_q8(const void* x, const void* w, void* codes, void* scales, int M, int H, float eps,
+                                    void* stream)
+{
+    if (!x || !w || !codes || !scales || M < 1 || H < 1) return DET_EINVAL;
+    if (H % 64 != 0 || H > 8 * 256 * kMaxVecPerThread) return DET_ESHAPE;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(codes) || !aligned16(scales)) return DET_EALIGN;
+    hipLaunchKernelGGL(rmsnorm_kernel<true>, dim3(M), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint4*>(x), static_cast<const uint4*>(w), nullptr, H, eps,
+                       static_cast<int8_t*>(codes), static_cast<float*>(scales), (M + 3) & ~3);
     return check_launch();
 }
 

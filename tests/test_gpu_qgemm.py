@@ -126,3 +126,57 @@ def test_qgemm_argument_errors(d):
     assert L.det_qgemm_w4a8(p, p, p, p, 64, 0, 64, 64, 0, None) == 1           # M < 1
     assert L.det_qgemm_w4a8(p, p, p, p, 66, 1, 64, 64, 0, None) == 3           # ldc % 4
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("M,H", [(1, 4096), (5, 2048), (33, 64), (64, 16384), (130, 4096)])
+def test_rmsnorm_quant_matches_oracle(d, orc, M, H):
+    """det_rmsnorm_quant_q8 = the oracle's activation quantizer applied to the oracle's RMSNorm, code for
+    code and scale bit for bit (and so equal to det_quant_act_q8 of det_rmsnorm)."""
+    x = ds.normal_bf16(ds.tensor_seed(6, 50) + M, (M, H), 1.0, 0.0)
+    w = ds.normal_bf16(ds.tensor_seed(6, 51) + H, (H,), 0.1, 1.0)
+    x[0, :64] = 0                                  # a block of zeros: scale 0, codes 0
+    step(f"rmsnorm+quant M={M} H={H}")
+    codes = torch.full((M, H), 99, dtype=torch.int8, device=DEV)
+    scales = torch.full((d.det_quant_act_scales_bytes(M, H) // 4,), float("nan"), dtype=torch.float32, device=DEV)
+    d.det_rmsnorm_quant_q8(up_bf16(x), up_bf16(w), codes, scales, 1e-5)
+    torch.cuda.synchronize()
+    ldd = (M + 3) & ~3
+    got_d = scales.cpu().numpy().reshape(H // 64, ldd)[:, :M].T
+    po, do = orc.quant_a8(orc.rmsnorm(x, w, 1e-5))
+    assert np.array_equal(codes.cpu().numpy(), po)
+    assert np.array_equal(np.ascontiguousarray(got_d).view(np.uint32), do.view(np.uint32))
+
+
+@pytest.mark.parametrize("M,K,N", [(1, 256, 4096), (19, 1024, 6144), (70, 512, 12288), (130, 512, 28672),
+                                   (300, 256, 2048)])
+def test_qgemm_residual_epilogue_matches_oracle(d, orc, M, K, N):
+    a = ds.normal_bf16(ds.tensor_seed(6, 60) + M, (M, K), 1.0, 0.0)
+    w = ds.normal_bf16(ds.tensor_seed(6, 61) + N, (K, N), 0.02, 0.0)
+    r = ds.normal_bf16(ds.tensor_seed(6, 62) + M, (M, N), 1.0, 0.0)
+    step(f"qgemm residual epilogue M={M} K={K} N={N}")
+    packed = d.quant_pack_weight(up_bf16(w))
+    codes, scales = d.quant_activations(up_bf16(a))
+    rd = up_bf16(r)
+    out = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+    d.det_qgemm_w4a8_residual(codes, scales, packed, rd, out, N)
+    inplace = rd.clone()
+    d.det_qgemm_w4a8_residual(codes, scales, packed, inplace, inplace, N)
+    torch.cuda.synchronize()
+    want = orc.residual(r, orc.qlinear(a, *orc.quant_w4(w)))
+    assert np.array_equal(down_bf16(out), want) and np.array_equal(down_bf16(inplace), want)
+
+
+@pytest.mark.parametrize("M,K,F", [(1, 256, 2048), (19, 512, 14336), (70, 1024, 5632), (200, 256, 3072),
+                                   (130, 256, 6144)])
+def test_qgemm_swiglu_epilogue_matches_oracle(d, orc, M, K, F):
+    a = ds.normal_bf16(ds.tensor_seed(6, 70) + M, (M, K), 1.0, 0.0)
+    w = ds.normal_bf16(ds.tensor_seed(6, 71) + F, (K, 2 * F), 0.05, 0.0)
+    step(f"qgemm swiglu epilogue M={M} K={K} F={F}")
+    packed = d.quant_pack_gate_up(up_bf16(w))
+    codes, scales = d.quant_activations(up_bf16(a))
+    y = torch.empty((M, F), dtype=torch.bfloat16, device=DEV)
+    d.det_qgemm_w4a8_swiglu(codes, scales, packed, y, F)
+    torch.cuda.synchronize()
+    gu = orc.qlinear(a, *orc.quant_w4(w))
+    want = orc.swiglu(np.ascontiguousarray(gu[:, :F]), np.ascontiguousarray(gu[:, F:]))
+    assert np.array_equal(down_bf16(y), want)
