@@ -145,30 +145,55 @@ struct qgemm_plan {
     int SPC;         // stages per chunk
     int slot_bytes;  // bytes of a ring slot
     int nslots, nchunks, last_cnt;
-    int ncomp;       // waves that compute: CB * min(8/CB, RB)
+    int tile_bytes;  // bytes of an activation tile: 1024 (16 rows), or 512 / 256 for a single row block of <= 8 / <= 4 rows
+    uint32_t inv_4rb;  // floor(2^20/(4*RB))+1
+    int nrg;         // row groups in use: min(8/CB, RB)
+    int SG;          // stage groups: 8 / (CB * nrg) waves share a (column block, row group) pair, see run_sp
+    int res_off;     // SG > 1: byte offset in the ring of the two result buffers
+    int ncomp;       // waves that do not load
     int nload;
     uint32_t inv_nload;  // floor(2^20/nload)+1
 };
 
 static int q_wrun_bytes(int s_cnt, int cb) { return (s_cnt * qstage_w_bytes(cb) + 1023) & ~1023; }
 
+static int up1k(int n) { return (n + 1023) & ~1023; }
+
 static qgemm_plan make_qgemm_plan(int mrem, int cb, int K)
 {
     qgemm_plan t;
     t.mrem = mrem;
     t.RB = (mrem + 15) >> 4;
-    const int stage = qstage_w_bytes(cb) + 1024 * t.RB + 1024;
-    const int third = kQRing * 1024 / 3;
-    t.SPC = 1;  // the most stages whose chunk fits a third of the ring
-    while (q_wrun_bytes(t.SPC + 1, cb) + (t.SPC + 1) * (1024 * t.RB + 1024) <= third) ++t.SPC;
-    t.slot_bytes = q_wrun_bytes(t.SPC, cb) + t.SPC * (1024 * t.RB + 1024);
-    (void)stage;
-    t.nslots = kQRing * 1024 / t.slot_bytes < 4 ? kQRing * 1024 / t.slot_bytes : 4;
+    t.tile_bytes = t.RB == 1 ? (mrem <= 4 ? 256 : (mrem <= 8 ? 512 : 1024)) : 1024;
+    t.inv_4rb = (1u << 20) / (uint32_t)(4 * t.RB) + 1u;
+    // bytes of a chunk of spc stages: weight run, activation tiles, activation scales, each rounded up to 1 KB
+    auto chunk_bytes = [&](int spc) { return q_wrun_bytes(spc, cb) + up1k(spc * t.RB * t.tile_bytes) + up1k(spc * t.RB * 64); };
     const int nstages = K >> 6;
+    const int rg = 8 / cb;
+    t.nrg = rg < t.RB ? rg : t.RB;
+    // stage-parallel form (see run_sp) where the results stay small enough for chunks of twenty stages and
+    // more: at most two column blocks of at most 8 rows
+    t.SG = cb <= 2 && t.tile_bytes < 1024 ? 8 / cb : 1;
+    t.res_off = 0;
+    t.SPC = 1;
+    if (t.SG > 1) {
+        // four slots and two result buffers of 128 bytes per (stage, column block, row group, row kept)
+        const int res_stage = 2 * t.tile_bytes * cb * t.nrg;
+        while (4 * chunk_bytes(t.SPC + 1) + 2 * (t.SPC + 1) * res_stage <= kQRing * 1024 && t.SPC < 64) ++t.SPC;
+        t.slot_bytes = chunk_bytes(t.SPC);
+        t.nslots = 4;
+        t.res_off = 4 * t.slot_bytes;
+    } else {
+        const int third = kQRing * 1024 / 3;  // the most stages whose chunk fits a third of the ring
+        while (chunk_bytes(t.SPC + 1) <= third) ++t.SPC;
+        t.slot_bytes = chunk_bytes(t.SPC);
+        t.nslots = kQRing * 1024 / t.slot_bytes < 4 ? kQRing * 1024 / t.slot_bytes : 4;
+    }
     t.nchunks = (nstages + t.SPC - 1) / t.SPC;
     t.last_cnt = nstages - (t.nchunks - 1) * t.SPC;
-    const int rg = 8 / cb;
-    t.ncomp = cb * (rg < t.RB ? rg : t.RB);
+    // waves that do not load: one per (column block, row group, stage group), plus in the stage-parallel
+    // form one wave per pair that only runs the ordered chain
+    t.ncomp = cb * t.nrg * t.SG + (t.SG > 1 ? cb * t.nrg : 0);
     t.nload = kQWaves + kQLoaders - t.ncomp;
     t.inv_nload = (1u << 20) / (uint32_t)t.nload + 1u;
     return t;
@@ -202,6 +227,13 @@ __global__ __launch_bounds__(64 * (kQWaves + kQLoaders)) void qgemm_kernel(
     // codes, the four 16-byte pieces of row i swizzled: piece t at slot t ^ ((i/4)%4)), then s_cnt
     // blocks of 1 KB with the activation scales of the tile's rows for the stage.
     auto wrun = [&](int s_cnt) { return (uint32_t)((s_cnt * WST + 1023) & ~1023); };
+    // The activation tiles of a chunk follow its weight run and the activation scales follow the tiles:
+    // tile (stage, row block) has TB bytes (16 rows of 64 codes; a single row block of at most 8 or 4
+    // rows keeps only 8 or 4), the scales of a stage are 4 bytes for each of the 16*RB rows.
+    const int TB = tp.tile_bytes;
+    auto abytes_of = [&](int s_cnt) { return (uint32_t)((s_cnt * RB * TB + 1023) & ~1023); };
+    auto sbytes_of = [&](int s_cnt) { return (uint32_t)((s_cnt * RB * 64 + 1023) & ~1023); };
+    const int lrc = min(lr, (TB >> 6) - 1);  // row of the tile this lane reads (rows past a short tile repeat its last)
 
     if (wave >= tp.ncomp) {
         // ---------------------------------------------------------------- loading wave
@@ -214,8 +246,14 @@ __global__ __launch_bounds__(64 * (kQWaves + kQLoaders)) void qgemm_kernel(
         const uint32_t a_lane_off = (uint32_t)lrow * (uint32_t)K + 16u * (uint32_t)((lane & 3) ^ ((lane >> 4) & 3));
         auto strided = [&](int n) { return n > lrank ? (int)(((uint32_t)(n - lrank + nload - 1) * tp.inv_nload) >> 20) : 0; };
         auto loads_for = [&](int s_cnt) {
-            return strided((int)(wrun(s_cnt) >> 10)) + strided(s_cnt * RB) + strided(s_cnt);
+            return strided((int)(wrun(s_cnt) >> 10)) + strided((int)(abytes_of(s_cnt) >> 10)) +
+                   strided((int)(sbytes_of(s_cnt) >> 10));
         };
+        // short tiles: a load covers 1024/TB stages; lane -> (stage lane/(TB/16), row (lane/4) % (TB/64), piece lane%4)
+        const int srow = (lane >> 2) & ((TB >> 6) - 1);
+        const int sst = lane / (TB >> 4);
+        const uint32_t a_short_off = (uint32_t)srow * (uint32_t)K + 16u * (uint32_t)((lane & 3) ^ ((srow >> 2) & 3)) +
+                                     64u * (uint32_t)sst;
         const int loads_full = loads_for(SPC), loads_last = loads_for(tp.last_cnt);
         auto wave_loads = [&](int c) { return c < nchunks - 1 ? loads_full : (c == nchunks - 1 ? loads_last : 0); };
 
@@ -232,27 +270,43 @@ __global__ __launch_bounds__(64 * (kQWaves + kQLoaders)) void qgemm_kernel(
                 const uint32_t off = (uint32_t)u << 10;
                 if (off + lane16 < wlen) dma_block(wsrc + off, lane16, slot_addr + off);
             }
-            // activation tiles: unit (stage, row block); rows past M load nothing
+            // activation tiles; rows past M load nothing
             const uint32_t tiles = slot_addr + wrun(s_cnt);
-            int sl = 0, rb = lrank;
-            while (rb >= RB) {
-                rb -= RB;
-                ++sl;
-            }
-            const int nt = s_cnt * RB;
-            for (int u = lrank; u < nt; u += nload) {
-                if (16 * rb + lrow < mrem)
-                    dma_block(abytes + (size_t)(16 * rb) * K + ((size_t)(s0 + sl) << 6), a_lane_off, tiles + ((uint32_t)u << 10));
-                rb += nload;
+            if (TB == 1024) {  // unit (stage, row block)
+                int sl = 0, rb = lrank;
                 while (rb >= RB) {
                     rb -= RB;
                     ++sl;
                 }
+                const int nt = s_cnt * RB;
+                for (int u = lrank; u < nt; u += nload) {
+                    if (16 * rb + lrow < mrem)
+                        dma_block(abytes + (size_t)(16 * rb) * K + ((size_t)(s0 + sl) << 6), a_lane_off,
+                                  tiles + ((uint32_t)u << 10));
+                    rb += nload;
+                    while (rb >= RB) {
+                        rb -= RB;
+                        ++sl;
+                    }
+                }
+            } else {  // one row block of short tiles: unit = 1024/TB stages
+                const int spu = 1024 / TB;
+                const int nau = (int)(abytes_of(s_cnt) >> 10);
+                for (int u = lrank; u < nau; u += nload)
+                    if (srow < mrem && u * spu + sst < s_cnt)
+                        dma_block(abytes + ((size_t)(s0 + u * spu) << 6), a_short_off, tiles + ((uint32_t)u << 10));
             }
-            // activation scales: one unit per stage, 4 rows a lane
-            const uint32_t scales = tiles + ((uint32_t)nt << 10);
-            for (int u = lrank; u < s_cnt; u += nload)
-                if (4 * lane < mrem) dma_block(dbytes + (size_t)(s0 + u) * ldd * 4, lane16, scales + ((uint32_t)u << 10));
+            // activation scales: 16-byte piece p of the chunk's scale area = rows 4w .. 4w+3 of stage p / (4 RB),
+            // w = p % (4 RB)
+            const uint32_t scales = tiles + abytes_of(s_cnt);
+            const int nsu = (int)(sbytes_of(s_cnt) >> 10);
+            for (int u = lrank; u < nsu; u += nload) {
+                const uint32_t pce = (uint32_t)(64 * u + lane);
+                const uint32_t st = (pce * tp.inv_4rb) >> 20;
+                const uint32_t w = pce - st * (uint32_t)(4 * RB);
+                if ((int)st < s_cnt && (int)(4 * w) < mrem)
+                    dma_block(dbytes + (size_t)s0 * ldd * 4, st * (uint32_t)ldd * 4u + 16u * w, scales + ((uint32_t)u << 10));
+            }
         };
 
         for (int c = 0; c < P; ++c) load_chunk(c, c);
@@ -269,12 +323,141 @@ __global__ __launch_bounds__(64 * (kQWaves + kQLoaders)) void qgemm_kernel(
             slot_new = slot_c;
             slot_c = slot_c + 1 == nslots ? 0 : slot_c + 1;
         }
+        if (tp.SG > 1) __builtin_amdgcn_s_barrier();  // the barrier after which the last chunk's results are read
         return;
     }
 
     // -------------------------------------------------------------------- computing wave
-    const int j = wave % CB, rg = wave / CB;       // column block and row group of the wave
-    const int cnt = (RB - rg + RG - 1) / RG;       // its row blocks: rg, rg + RG, ... (cnt >= 1 here)
+    const int nstagew = CB * tp.nrg * tp.SG;  // waves that work on stages; any further non-loading wave runs a chain
+    const int pw = wave < nstagew ? wave : wave - nstagew;
+    const int j = pw % CB, rg = (pw / CB) % tp.nrg;  // column block and row group of the wave
+    const int cnt = (RB - rg + RG - 1) / RG;         // its row blocks: rg, rg + RG, ... (cnt >= 1 here)
+
+    // Stage-parallel form for tiles with fewer row blocks than row groups (M <= 16*(8/CB - 1)): one wave
+    // per (column block, row group) would leave most of the compute unit's vector units idle while it
+    // works through every stage by itself.  The SG waves of a pair split the stages of a chunk
+    // (stage sl -> wave sl % SG); for its stages a wave computes t = d*s and the block's integer
+    // product as fp32 (exact) and leaves both in LDS.  After the next barrier the pair's chain wave
+    // (a wave with no other work, so that the chain of chunk c runs beside the stage work of chunk
+    // c+1) runs acc = fma(t, P, acc) over the chunk's stages in ascending order: the chain, the only
+    // part whose order is defined, is the same sequence of operations as in the serial form.
+    auto run_sp = [&]() {
+        const int SG = tp.SG, npair = CB * tp.nrg;
+        const bool chain_wave = wave >= nstagew;
+        const int sg = wave / npair, pair = j + CB * rg;
+        // results of a stage: for each pair RT = TB/64 rows x 16 columns of t, then of P; lane (g, lr) holds the
+        // four columns 4g .. 4g+3 of row lr and takes part if its row is kept
+        const int RT = TB >> 6;
+        const int res_pair = RT * 128, res_stage = npair * res_pair;
+        const bool row_kept = lr < RT;
+        char* const resbase = reinterpret_cast<char*>(ring) + tp.res_off;
+        const int res_chunk = SPC * res_stage;
+        const int res_lane = pair * res_pair + (g * RT + lr) * 16;
+        float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        auto chain = [&](int c) {
+            const int s_cnt = chunk_stages(c);
+            if (!row_kept) return;
+            const char* rr = resbase + (c & 1) * res_chunk + res_lane;
+            const int stride = res_stage, pf_off = RT * 64;
+            // eight stages' operands are read before their (ordered) chain runs, so that one LDS latency is
+            // paid per eight stages
+            constexpr int W = 8;
+            int sl = 0;
+            for (; sl + W <= s_cnt; sl += W) {
+                float4 t[W], pf[W];
+#pragma unroll
+                for (int u = 0; u < W; ++u) {
+                    t[u] = *reinterpret_cast<const float4*>(rr + u * stride);
+                    pf[u] = *reinterpret_cast<const float4*>(rr + u * stride + pf_off);
+                }
+#pragma unroll
+                for (int u = 0; u < W; ++u) {
+                    acc[0] = __builtin_fmaf(t[u].x, pf[u].x, acc[0]);
+                    acc[1] = __builtin_fmaf(t[u].y, pf[u].y, acc[1]);
+                    acc[2] = __builtin_fmaf(t[u].z, pf[u].z, acc[2]);
+                    acc[3] = __builtin_fmaf(t[u].w, pf[u].w, acc[3]);
+                }
+                rr += W * stride;
+            }
+            for (; sl < s_cnt; ++sl) {
+                const float4 t = *reinterpret_cast<const float4*>(rr);
+                const float4 pf = *reinterpret_cast<const float4*>(rr + pf_off);
+                acc[0] = __builtin_fmaf(t.x, pf.x, acc[0]);
+                acc[1] = __builtin_fmaf(t.y, pf.y, acc[1]);
+                acc[2] = __builtin_fmaf(t.z, pf.z, acc[2]);
+                acc[3] = __builtin_fmaf(t.w, pf.w, acc[3]);
+                rr += stride;
+            }
+        };
+        int slot_c = 0;
+        for (int c = 0; c < nchunks; ++c) {
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            if (chain_wave) {
+                if (c > 0) chain(c - 1);
+                continue;
+            }
+            const int s_cnt = chunk_stages(c);
+            const char* slot = reinterpret_cast<const char*>(ring) + (size_t)slot_c * tp.slot_bytes;
+            const char* tiles = slot + wrun(s_cnt);
+            const char* scales = tiles + abytes_of(s_cnt);
+            char* rw = resbase + (c & 1) * res_chunk + res_lane;
+            // UU of the wave's stages at a time: all reads and matrix-core instructions first
+            auto stages = [&](int sl, auto uu_tag) {
+                constexpr int UU = decltype(uu_tag)::value;
+                v4i wu[UU], xa[UU];
+                uint2 sraw[UU];
+                float dv[UU];
+#pragma unroll
+                for (int u = 0; u < UU; ++u) {
+                    const int s = sl + u * SG;
+                    const char* wst = slot + s * WST;
+                    const uint2 codes = *reinterpret_cast<const uint2*>(wst + j * 512 + lane * 8);
+                    sraw[u] = *reinterpret_cast<const uint2*>(wst + 512 * CB + j * 32 + g * 8);
+                    xa[u] = *reinterpret_cast<const v4i*>(tiles + (size_t)(s * RB + rg) * TB + 64 * lrc +
+                                                          16 * (g ^ ((lrc >> 2) & 3)));
+                    dv[u] = *reinterpret_cast<const float*>(scales + (size_t)s * RB * 64 + (16 * rg + lr) * 4);
+                    // the stored nibble is q + 8: taken as it is, with -8 * (sum of the block's activation
+                    // codes) as the matrix core's starting value, which is the same integer
+                    wu[u][0] = (int)(codes.x & 0x0F0F0F0Fu);
+                    wu[u][1] = (int)((codes.x >> 4) & 0x0F0F0F0Fu);
+                    wu[u][2] = (int)(codes.y & 0x0F0F0F0Fu);
+                    wu[u][3] = (int)((codes.y >> 4) & 0x0F0F0F0Fu);
+                }
+                v4i pr[UU];
+#pragma unroll
+                for (int u = 0; u < UU; ++u) {
+                    const int m8 = (int)0xF8F8F8F8u;
+                    const v4i base = __builtin_amdgcn_mfma_i32_16x16x64_i8(v4i{m8, m8, m8, m8}, xa[u], v4i{0, 0, 0, 0}, 0, 0, 0);
+                    pr[u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wu[u], xa[u], base, 0, 0, 0);
+                }
+#pragma unroll
+                for (int u = 0; u < UU; ++u) {
+                    const int s = sl + u * SG;
+                    const float4 t = make_float4(dv[u] * bf16lo_to_f32(sraw[u].x), dv[u] * bf16hi_to_f32(sraw[u].x),
+                                                 dv[u] * bf16lo_to_f32(sraw[u].y), dv[u] * bf16hi_to_f32(sraw[u].y));
+                    const float4 pf = make_float4((float)pr[u][0], (float)pr[u][1], (float)pr[u][2], (float)pr[u][3]);
+                    if (row_kept) {
+                        *reinterpret_cast<float4*>(rw + (size_t)s * res_stage) = t;
+                        *reinterpret_cast<float4*>(rw + (size_t)s * res_stage + RT * 64) = pf;
+                    }
+                }
+            };
+            int sl = sg;
+            for (; sl + SG < s_cnt; sl += 2 * SG) stages(sl, std::integral_constant<int, 2>{});
+            for (; sl < s_cnt; sl += SG) stages(sl, std::integral_constant<int, 1>{});
+            slot_c = slot_c + 1 == nslots ? 0 : slot_c + 1;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        if (!chain_wave) return;
+        chain(nchunks - 1);
+        const int n = blockIdx.x * (16 * CB) + 16 * j + 4 * g;
+        const int rowl = 16 * rg + lr;
+        if (rowl < mrem) gemm_epilogue_store<EPI>(acc, C, ldc, R, ldr, (size_t)(m0 + rowl), n, out_f32);
+    };
+    if (tp.SG > 1) {
+        run_sp();
+        return;
+    }
 
     auto run = [&](auto nr_tag) {
         constexpr int NR = decltype(nr_tag)::value;  // cnt rounded up to a power of two; the surplus
@@ -294,7 +477,7 @@ __global__ __launch_bounds__(64 * (kQWaves + kQLoaders)) void qgemm_kernel(
             const int s_cnt = chunk_stages(c);
             const char* slot = reinterpret_cast<const char*>(ring) + (size_t)slot_c * tp.slot_bytes;
             const char* tiles = slot + wrun(s_cnt);
-            const char* scales = tiles + ((size_t)(s_cnt * RB) << 10);
+            const char* scales = tiles + abytes_of(s_cnt);
             // UU stages at a time: all their LDS reads and matrix-core instructions first, so that the
             // latencies overlap, then the scaling chain of each output in ascending stage order
             auto stages = [&](int sl, auto uu_tag) {
@@ -326,9 +509,9 @@ __global__ __launch_bounds__(64 * (kQWaves + kQLoaders)) void qgemm_kernel(
                     for (int u = 0; u < UU; ++u)
 #pragma unroll
                         for (int r = 0; r < G; ++r) {
-                            const v4i xa = *reinterpret_cast<const v4i*>(tiles + ((size_t)((sl + u) * RB + rbs[r0 + r]) << 10) +
-                                                                         64 * lr + 16 * (g ^ ((lr >> 2) & 3)));
-                            dv[u][r] = *reinterpret_cast<const float*>(scales + ((size_t)(sl + u) << 10) +
+                            const v4i xa = *reinterpret_cast<const v4i*>(tiles + (size_t)((sl + u) * RB + rbs[r0 + r]) * TB +
+                                                                         64 * lrc + 16 * (g ^ ((lrc >> 2) & 3)));
+                            dv[u][r] = *reinterpret_cast<const float*>(scales + (size_t)(sl + u) * RB * 64 +
                                                                        (16 * rbs[r0 + r] + lr) * 4);
                             pr[u][r] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wq[u], xa, v4i{0, 0, 0, 0}, 0, 0, 0);
                         }
