@@ -383,33 +383,46 @@ def decode_numbers(torch, det, ds, dev):
     packed = [g(0, (H,), 0.0, 1.0), det.pack_weight(g(1, (H, (Hq + 2 * Hkv) * D))), det.pack_weight(g(2, (Hq * D, H))),
               g(3, (H,), 0.0, 1.0), det.pack_gate_up(g(4, (H, 2 * F))), det.pack_weight(g(5, (F, H)))]
     struct = det.layer_weights(*packed)
+    # the same layer with 4-bit weights and 8-bit activations (det_qdecoder_layer)
+    qpacked = [packed[0], det.quant_pack_weight(g(1, (H, (Hq + 2 * Hkv) * D))), det.quant_pack_weight(g(2, (Hq * D, H))),
+               packed[3], det.quant_pack_gate_up(g(4, (H, 2 * F))), det.quant_pack_weight(g(5, (F, H)))]
+    qstruct = det.layer_weights(*qpacked)
+    qwbytes = float(sum(t.numel() * t.element_size() for t in qpacked))
     cfg = det.layer_cfg(H, Hq, Hkv, D, F, Lmax, 1e-5, scale)
     cos_t, sin_t = ds.rope_tables(Lmax, D, 5.0e5)
     cos_d, sin_d = torch.from_numpy(cos_t).to(dev), torch.from_numpy(sin_t).to(dev)
     wbytes = 2.0 * (H * (Hq + 2 * Hkv) * D + Hq * D * H + H * 2 * F + F * H)
-    layer_rows = []
+    layer_rows, qlayer_rows = [], []
     for B in (1, 32, 128):
         x = ds.normal_bf16_torch(s + 50, (B, H), 1.0, 0.0, dev)
         kc = ds.normal_bf16_torch(s + 51, (B, Hkv, Lmax, D), 1.0, 0.0, dev)
         vc = ds.normal_bf16_torch(s + 52, (B, Hkv, Lmax, D), 1.0, 0.0, dev)
         pos = torch.full((B,), Lmax - 1, dtype=torch.int32, device=dev)
-        ws = torch.empty(det.det_decoder_layer_workspace_bytes(cfg, B), dtype=torch.uint8, device=dev)
-        for _ in range(3):
-            det.det_decoder_layer(struct, cfg, x, kc, vc, pos, cos_d, sin_d, ws)
-        torch.cuda.synchronize()
-        n = 20
-        t0 = time.perf_counter()
-        for _ in range(n):
-            det.det_decoder_layer(struct, cfg, x, kc, vc, pos, cos_d, sin_d, ws)
-        torch.cuda.synchronize()
-        dt = (time.perf_counter() - t0) / n
-        by = wbytes + B * Hkv * Lmax * D * 2 * 2
-        layer_rows.append({"B": B, "context": Lmax, "us_per_layer": round(dt * 1e6, 1),
-                           "layer_tokens_per_s": round(B / dt, 1), "gbs": round(by / dt / 1e9, 1),
-                           "frac_hbm": round(by / dt / 1e9 / PEAK_HBM_GBS, 4)})
-        del x, kc, vc, ws
+        for quantized, rows_out, wb in ((False, layer_rows, wbytes), (True, qlayer_rows, qwbytes)):
+            if quantized:
+                ws = torch.empty(det.det_qdecoder_layer_workspace_bytes(cfg, B), dtype=torch.uint8, device=dev)
+                call = lambda: det.det_qdecoder_layer(qstruct, cfg, x, kc, vc, pos, None, cos_d, sin_d, ws)
+            else:
+                ws = torch.empty(det.det_decoder_layer_workspace_bytes(cfg, B), dtype=torch.uint8, device=dev)
+                call = lambda: det.det_decoder_layer(struct, cfg, x, kc, vc, pos, cos_d, sin_d, ws)
+            for _ in range(3):
+                call()
+            torch.cuda.synchronize()
+            n = 20
+            t0 = time.perf_counter()
+            for _ in range(n):
+                call()
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / n
+            by = wb + B * Hkv * Lmax * D * 2 * 2
+            rows_out.append({"B": B, "context": Lmax, "us_per_layer": round(dt * 1e6, 1),
+                             "layer_tokens_per_s": round(B / dt, 1), "gbs": round(by / dt / 1e9, 1),
+                             "frac_hbm": round(by / dt / 1e9 / PEAK_HBM_GBS, 4)})
+            del ws
+        del x, kc, vc
     out["decoder_layer"] = layer_rows
-    del packed, struct
+    out["decoder_layer_w4a8"] = qlayer_rows
+    del packed, struct, qpacked, qstruct
     torch.cuda.empty_cache()
 
     H, Hq, Hkv, D, F, V, NL = 2048, 16, 4, 128, 5632, 32000, 8
@@ -420,34 +433,35 @@ def decode_numbers(torch, det, ds, dev):
         o = 10 + 10 * l
         layers.append(dict(norm1=g(o, (H,), 0.0, 1.0), wqkv=g(o + 1, (H, (Hq + 2 * Hkv) * D)), wo=g(o + 2, (Hq * D, H)),
                            norm2=g(o + 3, (H,), 0.0, 1.0), wgu=g(o + 4, (H, 2 * F)), wdown=g(o + 5, (F, H))))
-    model = DecodeModel(ModelCfg(H, Hq, Hkv, D, F, V, NL),
-                        dict(embed=g(1, (V, H), 1.0), lm_head=g(2, (H, V)), final_norm=g(3, (H,), 0.0, 1.0),
-                             layers=layers))
+    weights = dict(embed=g(1, (V, H), 1.0), lm_head=g(2, (H, V)), final_norm=g(3, (H,), 0.0, 1.0), layers=layers)
+    models = (("model_8_layer_step", DecodeModel(ModelCfg(H, Hq, Hkv, D, F, V, NL), weights)),
+              ("model_8_layer_step_w4a8", DecodeModel(ModelCfg(H, Hq, Hkv, D, F, V, NL), weights, quantized=True)))
     Lm = 640
     cos_t, sin_t = ds.rope_tables(Lm, D, 5.0e5)
     cos_d, sin_d = torch.from_numpy(cos_t).to(dev), torch.from_numpy(sin_t).to(dev)
-    rows = []
-    for B in (1, 8, 64):
-        st = model.new_state(B, Lm, cos_d, sin_d)
-        st.tokens.copy_(torch.from_numpy(ds.uniform_int(s + 900, (B,), 0, V - 1)).to(dev))
-        idx = torch.empty(B, dtype=torch.int32, device=dev)
-        for k in st.kcache + st.vcache:
-            k.copy_(ds.normal_bf16_torch(s + 901, tuple(k.shape), 1.0, 0.0, dev))
-        st.positions.fill_(511)
-        for _ in range(3):
-            st.forward()
-            det.det_argmax(st.logits, idx)
-        torch.cuda.synchronize()
-        n = 30
-        t0 = time.perf_counter()
-        for _ in range(n):
-            st.forward()
-            det.det_argmax(st.logits, idx)
-        torch.cuda.synchronize()
-        dt = (time.perf_counter() - t0) / n
-        rows.append({"B": B, "context": 512, "ms_per_step": round(dt * 1e3, 3), "tokens_per_s": round(B / dt, 1)})
-        del st
-    out["model_8_layer_step"] = rows
+    for key, model in models:
+        rows = []
+        for B in (1, 8, 64):
+            st = model.new_state(B, Lm, cos_d, sin_d)
+            st.tokens.copy_(torch.from_numpy(ds.uniform_int(s + 900, (B,), 0, V - 1)).to(dev))
+            idx = torch.empty(B, dtype=torch.int32, device=dev)
+            for k in st.kcache + st.vcache:
+                k.copy_(ds.normal_bf16_torch(s + 901, tuple(k.shape), 1.0, 0.0, dev))
+            st.positions.fill_(511)
+            for _ in range(3):
+                st.forward()
+                det.det_argmax(st.logits, idx)
+            torch.cuda.synchronize()
+            n = 30
+            t0 = time.perf_counter()
+            for _ in range(n):
+                st.forward()
+                det.det_argmax(st.logits, idx)
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / n
+            rows.append({"B": B, "context": 512, "ms_per_step": round(dt * 1e3, 3), "tokens_per_s": round(B / dt, 1)})
+            del st
+        out[key] = rows
     return out
 
 

@@ -266,8 +266,13 @@ __global__ __launch_bounds__(64 * (kQWaves + kQLoaders)) void qgemm_kernel(
             const uint32_t wlen = (uint32_t)(s_cnt * WST);
             const int nwu = (int)(wrun(s_cnt) >> 10);
             const char* wsrc = wbytes + (size_t)s0 * WST;
-            for (int u = lrank; u < nwu; u += nload) {
-                const uint32_t off = (uint32_t)u << 10;
+            // the whole units as one run of loads (three instructions each: the loaders' own instruction
+            // stream is on the critical path of small tiles), the short last unit by the wave whose turn it is
+            const int nfull = (int)(wlen >> 10);
+            dma_run(wsrc, lane16 + (uint32_t)lrank * 1024u, (uint32_t)nload * 1024u, slot_addr + (uint32_t)lrank * 1024u,
+                    (uint32_t)nload * 1024u, strided(nfull));
+            if (nwu > nfull && nfull - nload * (int)(((uint32_t)nfull * tp.inv_nload) >> 20) == lrank) {
+                const uint32_t off = (uint32_t)nfull << 10;
                 if (off + lane16 < wlen) dma_block(wsrc + off, lane16, slot_addr + off);
             }
             // activation tiles; rows past M load nothing

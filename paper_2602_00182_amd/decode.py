@@ -32,26 +32,46 @@ class ModelCfg:
 
 
 class DecodeModel:
-    """Weights of a Llama-style decoder, packed for det_gemm_bf16.
+    """Weights of a Llama-style decoder, packed for det_gemm_bf16, or with quantized=True block-quantized
+    to 4 bits and packed for det_qgemm_w4a8 (every projection, the lm_head included; embedding and norm
+    weights stay bf16).
 
     `weights` holds logical row-major bf16 tensors on the GPU:
         embed [V,H], lm_head [H,V], final_norm [H], and per layer i:
         layers[i] = dict(norm1 [H], wqkv [H,(Hq+2Hkv)D], wo [Hq*D,H], norm2 [H], wgu [H,2F], wdown [F,H])
     """
 
-    def __init__(self, cfg: ModelCfg, weights: dict):
+    def __init__(self, cfg: ModelCfg, weights: dict, quantized: bool = False):
         self.cfg = cfg
+        self.quantized = quantized
+        pack = api.quant_pack_weight if quantized else api.pack_weight
+        pack_gu = api.quant_pack_gate_up if quantized else api.pack_gate_up
         self.embed = weights["embed"].contiguous()
         self.final_norm = weights["final_norm"].contiguous()
-        self.lm_head = api.pack_weight(weights["lm_head"])
+        self.lm_head = pack(weights["lm_head"])
         self.layers = []
         for lw in weights["layers"]:
-            packed = dict(norm1=lw["norm1"].contiguous(), wqkv=api.pack_weight(lw["wqkv"]),
-                          wo=api.pack_weight(lw["wo"]), norm2=lw["norm2"].contiguous(),
-                          wgu=api.pack_gate_up(lw["wgu"]), wdown=api.pack_weight(lw["wdown"]))
+            packed = dict(norm1=lw["norm1"].contiguous(), wqkv=pack(lw["wqkv"]),
+                          wo=pack(lw["wo"]), norm2=lw["norm2"].contiguous(),
+                          wgu=pack_gu(lw["wgu"]), wdown=pack(lw["wdown"]))
             struct = api.layer_weights(packed["norm1"], packed["wqkv"], packed["wo"], packed["norm2"],
                                        packed["wgu"], packed["wdown"])
             self.layers.append((packed, struct))
+
+    def layer_workspace_bytes(self, lcfg, rows: int) -> int:
+        if self.quantized:
+            return api.det_qdecoder_layer_workspace_bytes(lcfg, rows)
+        return api.det_decoder_layer_workspace_bytes(lcfg, rows)
+
+    def layer(self, struct, lcfg, x, kcache, vcache, positions, slots, rope_cos, rope_sin, ws, stream=None):
+        """One decoder layer on rows x; slots None: row r is the sequence in cache slot r."""
+        if self.quantized:
+            api.det_qdecoder_layer(struct, lcfg, x, kcache, vcache, positions, slots, rope_cos, rope_sin, ws, stream)
+        elif slots is None:
+            api.det_decoder_layer(struct, lcfg, x, kcache, vcache, positions, rope_cos, rope_sin, ws, stream)
+        else:
+            api.det_decoder_layer_rows(struct, lcfg, x, kcache, vcache, positions, slots, rope_cos, rope_sin, ws,
+                                       stream)
 
     def new_state(self, B: int, Lmax: int, rope_cos: torch.Tensor, rope_sin: torch.Tensor):
         return DecodeState(self, B, Lmax, rope_cos, rope_sin)
@@ -71,9 +91,12 @@ class DecodeState:
         self.kcache = [torch.zeros((B, c.Hkv, Lmax, c.D), dtype=torch.bfloat16, device=dev)
                        for _ in range(c.n_layers)]
         self.vcache = [torch.zeros_like(k) for k in self.kcache]
-        self.ws = torch.empty(api.det_decoder_layer_workspace_bytes(self.lcfg, B), dtype=torch.uint8, device=dev)
+        self.ws = torch.empty(model.layer_workspace_bytes(self.lcfg, B), dtype=torch.uint8, device=dev)
         self.x = torch.empty((B, c.H), dtype=torch.bfloat16, device=dev)
         self.xn = torch.empty((B, c.H), dtype=torch.bfloat16, device=dev)
+        if model.quantized:  # the final norm's output as activation codes for the quantized lm_head
+            self.xn_codes = torch.empty((B, c.H), dtype=torch.int8, device=dev)
+            self.xn_scales = torch.empty(api.det_quant_act_scales_bytes(B, c.H) // 4, dtype=torch.float32, device=dev)
         self.logits = torch.empty((B, c.V), dtype=torch.float32, device=dev)
         self.tokens = torch.empty(B, dtype=torch.int32, device=dev)
         self.positions = torch.empty(B, dtype=torch.int32, device=dev)
@@ -83,10 +106,19 @@ class DecodeState:
         m, c = self.model, self.model.cfg
         api.det_embed_gather(m.embed, self.tokens, self.x, stream)
         for i, (_, struct) in enumerate(m.layers):
-            api.det_decoder_layer(struct, self.lcfg, self.x, self.kcache[i], self.vcache[i], self.positions,
-                                  self.rope_cos, self.rope_sin, self.ws, stream)
-        api.det_rmsnorm(self.x, m.final_norm, self.xn, c.eps, stream)
-        api.det_gemm_bf16(self.xn, m.lm_head, self.logits, c.V, c.H, stream)
+            m.layer(struct, self.lcfg, self.x, self.kcache[i], self.vcache[i], self.positions, None, self.rope_cos,
+                    self.rope_sin, self.ws, stream)
+        self.head(stream)
+
+    def head(self, stream=None):
+        """Final RMSNorm and lm_head on self.x; fp32 logits in self.logits."""
+        m, c = self.model, self.model.cfg
+        if m.quantized:
+            api.det_rmsnorm_quant_q8(self.x, m.final_norm, self.xn_codes, self.xn_scales, c.eps, stream)
+            api.det_qgemm_w4a8(self.xn_codes, self.xn_scales, m.lm_head, self.logits, c.V, stream)
+        else:
+            api.det_rmsnorm(self.x, m.final_norm, self.xn, c.eps, stream)
+            api.det_gemm_bf16(self.xn, m.lm_head, self.logits, c.V, c.H, stream)
 
 
 @dataclass
@@ -182,14 +214,13 @@ def _prefill_decode(model, prompts, prompt_lens, n_new, rope_cos, rope_sin, stre
     last_rows = (starts + lens_host - 1).to(torch.int32).to(dev)
 
     xr = torch.empty((R, c.H), dtype=torch.bfloat16, device=dev)
-    ws = torch.empty(api.det_decoder_layer_workspace_bytes(st.lcfg, R), dtype=torch.uint8, device=dev)
+    ws = torch.empty(model.layer_workspace_bytes(st.lcfg, R), dtype=torch.uint8, device=dev)
     api.det_embed_gather(model.embed, row_tokens, xr, stream)
     for i, (_, struct) in enumerate(model.layers):
-        api.det_decoder_layer_rows(struct, st.lcfg, xr, st.kcache[i], st.vcache[i], row_pos, row_slots,
-                                   st.rope_cos, st.rope_sin, ws, stream)
+        model.layer(struct, st.lcfg, xr, st.kcache[i], st.vcache[i], row_pos, row_slots, st.rope_cos, st.rope_sin, ws,
+                    stream)
     api.det_embed_gather(xr, last_rows, st.x, stream)  # row gather: the last token of each sequence
-    api.det_rmsnorm(st.x, model.final_norm, st.xn, c.eps, stream)
-    api.det_gemm_bf16(st.xn, model.lm_head, st.logits, c.V, c.H, stream)
+    st.head(stream)
 
     gen = torch.zeros((n_new, B), dtype=torch.int32, device=dev)
     kept = []

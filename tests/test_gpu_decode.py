@@ -15,9 +15,7 @@ N_PROMPTS, N_NEW = 64, 128
 
 
 @pytest.fixture(scope="module")
-def model():
-    from paper_2602_00182_amd.decode import DecodeModel, ModelCfg
-
+def weights():
     s = ds.tensor_seed(5, 0)
     g = lambda i, shape, std=0.02, mean=0.0: ds.normal_bf16_torch(s + i, shape, std, mean, DEV)
     layers = []
@@ -26,8 +24,21 @@ def model():
         layers.append(dict(norm1=g(o, (H,), 0.0, 1.0), wqkv=g(o + 1, (H, (HQ + 2 * HKV) * D)),
                            wo=g(o + 2, (HQ * D, H)), norm2=g(o + 3, (H,), 0.0, 1.0), wgu=g(o + 4, (H, 2 * F)),
                            wdown=g(o + 5, (F, H))))
-    weights = dict(embed=g(1, (V, H), 1.0), lm_head=g(2, (H, V)), final_norm=g(3, (H,), 0.0, 1.0), layers=layers)
+    return dict(embed=g(1, (V, H), 1.0), lm_head=g(2, (H, V)), final_norm=g(3, (H,), 0.0, 1.0), layers=layers)
+
+
+@pytest.fixture(scope="module")
+def model(weights):
+    from paper_2602_00182_amd.decode import DecodeModel, ModelCfg
+
     return DecodeModel(ModelCfg(H, HQ, HKV, D, F, V, NL), weights)
+
+
+@pytest.fixture(scope="module")
+def qmodel(weights):
+    from paper_2602_00182_amd.decode import DecodeModel, ModelCfg
+
+    return DecodeModel(ModelCfg(H, HQ, HKV, D, F, V, NL), weights, quantized=True)
 
 
 @pytest.fixture(scope="module")
@@ -179,3 +190,39 @@ def test_receipts_identical_across_batchings(model, prompts, orc):
     step("receipts, batch of 3 and one prompt alone")
     assert run([41, 30, 35])[0] == [full[11], full[0], full[5]]
     assert run([33])[0] == [full[3]]
+
+
+def test_quantized_model_streams_across_batchings_and_prefill(qmodel, model, prompts):
+    """The same model with every projection block-quantized (4-bit weights, 8-bit activations): token
+    streams and logits bytes of a prompt are identical alone, in a batch of 12, in another order, and
+    between token-by-token decoding and one-pass prefill; they differ from the bf16 model's."""
+    from paper_2602_00182_amd.decode import greedy_decode, prefill_decode
+
+    toks, lens = prompts
+    n_new = 20
+    cos_t, sin_t = ds.rope_tables(512 + n_new, D, 5.0e5)
+    cos_d, sin_d = up(cos_t), up(sin_t)
+    ids = list(range(20, 32))
+    step("quantized model: prefill + decode of 12 prompts")
+    full, full_logits = prefill_decode(qmodel, up(toks[ids]), up(lens[ids]), n_new, cos_d, sin_d, keep_logits=True)
+    torch.cuda.synchronize()
+    full = full.cpu().numpy()
+    assert len({tuple(r) for r in full}) > 6
+    step("quantized model: token-by-token decode of 4 of them")
+    sub = [3, 0, 7, 11]
+    sub_ids = [ids[i] for i in sub]
+    keep = tuple(int(lens[i]) - 1 + j for i in sub_ids for j in (0, n_new - 1))
+    tbt, tbt_logits = greedy_decode(qmodel, up(toks[sub_ids]), up(lens[sub_ids]), n_new, cos_d, sin_d, keep_logits_at=keep)
+    torch.cuda.synchronize()
+    assert np.array_equal(tbt.cpu().numpy(), full[sub])
+    for row, i in enumerate(sub_ids):
+        for j in (0, n_new - 1):
+            a = tbt_logits[int(lens[i]) - 1 + j][row].cpu().numpy().view(np.uint32)
+            b = full_logits[j][sub[row]].cpu().numpy().view(np.uint32)
+            assert np.array_equal(a, b), f"logits differ: prompt {i}, generated token {j}"
+    step("quantized model: one prompt alone, prefill")
+    alone, _ = prefill_decode(qmodel, up(toks[[ids[5]]]), up(lens[[ids[5]]]), n_new, cos_d, sin_d)
+    assert np.array_equal(alone.cpu().numpy()[0], full[5])
+    step("bf16 model on the same prompts")
+    ref, _ = prefill_decode(model, up(toks[ids]), up(lens[ids]), n_new, cos_d, sin_d)
+    assert not np.array_equal(ref.cpu().numpy(), full)
