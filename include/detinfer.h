@@ -297,6 +297,12 @@ int det_qgemm_w4a8_swiglu(const void *codes, const void *scales, const void *pac
                           int ldy, int M, int F, int K, void *stream);
 int det_rmsnorm_quant_q8(const void *x, const void *w, void *codes, void *scales, int M, int H, float eps,
                          void *stream);
+/* det_attn_decode_quant_q8: det_quant_act_q8 of the [R, Hq*D] output of det_attn_decode_rows (slots may be
+ *   NULL: row r reads cache slot r, as det_attn_decode), written as codes int8 [R, Hq*D] and scales for
+ *   (M = R, K = Hq*D); other arguments and errors as det_attn_decode_rows. */
+int det_attn_decode_quant_q8(const void *q, const void *kcache, const void *vcache, const int32_t *seqlens,
+                             const int32_t *slots, void *codes, void *scales, void *ws, size_t ws_bytes,
+                             int R, int Hq, int Hkv, int D, int Lmax, float scale, void *stream);
 
 /* The decoder layer with every projection block-quantized (the engine the paper measures runs
  * quantized models, section 6.4): the steps of det_decoder_layer in the same order, each projection

@@ -22,7 +22,7 @@ __all__ = [
     "det_quant_unpack_w4", "det_quant_act_codes_bytes", "det_quant_act_scales_bytes", "det_quant_act_q8",
     "det_qgemm_w4a8", "quant_pack_weight", "quant_activations", "det_qgemm_w4a8_residual",
     "det_qgemm_w4a8_swiglu", "det_quant_pack_w4_gate_up", "quant_pack_gate_up", "det_rmsnorm_quant_q8",
-    "det_qdecoder_layer_workspace_bytes", "det_qdecoder_layer",
+    "det_qdecoder_layer_workspace_bytes", "det_qdecoder_layer", "det_attn_decode_quant_q8",
 ]
 
 _CODES = {1: "DET_EINVAL", 2: "DET_ESHAPE", 3: "DET_EALIGN", 4: "DET_EWORKSPACE", 5: "DET_EHIP"}
@@ -146,6 +146,21 @@ def det_rmsnorm_quant_q8(x, w, codes, scales, eps: float, stream=None) -> None:
     _check("det_rmsnorm_quant_q8", lib().det_rmsnorm_quant_q8(
         _contig(x, torch.bfloat16), _contig(w, torch.bfloat16), _contig(codes, torch.int8),
         _contig(scales, torch.float32), M, H, eps, _stream(stream)))
+
+
+def det_attn_decode_quant_q8(q, kcache, vcache, seqlens, slots, codes, scales, ws, scale: float, stream=None) -> None:
+    """Attention output [R, Hq*D] written as activation codes and scales; slots may be None."""
+    R, Hq, D = q.shape
+    _, Hkv, Lmax, D2 = kcache.shape
+    if D2 != D or vcache.shape != kcache.shape or seqlens.shape != (R,) or codes.shape != (R, Hq * D):
+        raise ValueError("bad attention shapes")
+    if scales.numel() * 4 < det_quant_act_scales_bytes(R, Hq * D) or (slots is None and kcache.shape[0] < R):
+        raise ValueError("bad attention shapes")
+    _check("det_attn_decode_quant_q8", lib().det_attn_decode_quant_q8(
+        _contig(q, torch.bfloat16), _contig(kcache, torch.bfloat16), _contig(vcache, torch.bfloat16),
+        _contig(seqlens, torch.int32), None if slots is None else _contig(slots, torch.int32),
+        _contig(codes, torch.int8), _contig(scales, torch.float32), _contig(ws), ws.numel() * ws.element_size(),
+        R, Hq, Hkv, D, Lmax, scale, _stream(stream)))
 
 
 def quant_pack_weight(b_kn: torch.Tensor) -> torch.Tensor:

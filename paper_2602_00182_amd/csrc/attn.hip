@@ -189,12 +189,18 @@ __global__ __launch_bounds__(256) void attn_chunk_kernel(const uint16_t* __restr
 // the threads (max is exact, so order free), the weights w_c = det_expf(m_c - m) are computed one
 // chunk per thread into LDS, and each thread then folds L and its own O[d] over the chunks in
 // ascending order with the loads of 8 chunks in flight at a time.
+// QUANT: instead of the bf16 output row the kernel writes its 8-bit block quantization (the bytes
+// det_quant_act_q8 makes of it): a wave's 64 values are one block, so the block maximum is a wave
+// reduction; `out` is then the int8 code array [B, Hq*128] and `scales` the block-major scale array
+// with row stride ldd.
+template <bool QUANT>
 __global__ __launch_bounds__(128) void attn_combine_kernel(const int32_t* __restrict__ seqlens,
                                                            const float* __restrict__ ws_m,
                                                            const float* __restrict__ ws_l,
                                                            const float* __restrict__ ws_o,
-                                                           uint16_t* __restrict__ out, int Hq, int Lmax,
-                                                           int ncmax, int len_offset)
+                                                           void* __restrict__ out, int Hq, int Lmax,
+                                                           int ncmax, int len_offset, float* __restrict__ scales,
+                                                           int ldd)
 {
     __shared__ float s_w[128];
     __shared__ float s_l[128];
@@ -202,9 +208,27 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const int32_t* __rest
     const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
     int len = seqlens[b] + len_offset;
     len = len > Lmax ? Lmax : len;
-    uint16_t* dst = out + ((size_t)b * Hq + h) * kD;
-    if (len <= 0) {
-        dst[d] = 0;
+    const size_t o_idx = ((size_t)b * Hq + h) * kD + d;
+    auto store = [&](uint16_t y) {
+        if constexpr (!QUANT) {
+            static_cast<uint16_t*>(out)[o_idx] = y;
+        } else {
+            const float a = bf16_to_f32(y);
+            float amax = fabsf(a);
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, kWave));
+            const float df = amax / 127.0f;
+            int v = 0;
+            if (df != 0.0f) {
+                const float r = rintf(a / df);
+                v = r < -127.0f ? -127 : (r > 127.0f ? 127 : (int)r);
+            }
+            static_cast<int8_t*>(out)[o_idx] = (int8_t)v;
+            if ((d & 63) == 0) scales[(size_t)(2 * h + (d >> 6)) * ldd + b] = df;
+        }
+    };
+    if (len <= 0) {  // uniform over the workgroup
+        store(0);
         return;
     }
     const int nc = (len + kChunk - 1) / kChunk;
@@ -249,7 +273,7 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const int32_t* __rest
             O = O + wo;
         }
     }
-    dst[d] = f32_to_bf16_rne(O / L);
+    store(f32_to_bf16_rne(O / L));
 }
 
 // ------------------------------------------------------------------ softmax on given scores
@@ -329,7 +353,7 @@ extern "C" size_t det_attn_decode_workspace_bytes(int B, int Hq, int D, int Lmax
 
 int det::attn_decode_impl(const void* q, const void* kcache, const void* vcache, const int32_t* seqlens,
                           const int32_t* slots, int len_offset, void* out, void* ws, size_t ws_bytes, int B, int Hq, int Hkv, int D,
-                          int Lmax, float scale, hipStream_t s)
+                          int Lmax, float scale, hipStream_t s, void* qscales)
 {
     if (!q || !kcache || !vcache || !seqlens || !out || !ws || B < 1 || Hq < 1 || Hkv < 1 || Lmax < 1)
         return DET_EINVAL;
@@ -370,8 +394,14 @@ int det::attn_decode_impl(const void* q, const void* kcache, const void* vcache,
 #undef DET_LAUNCH_ATTN
     int rc = check_launch();
     if (rc != DET_OK) return rc;
-    hipLaunchKernelGGL(attn_combine_kernel, dim3(Hq, B), dim3(128), 0, s, seqlens, ws_m, ws_l, ws_o,
-                       static_cast<uint16_t*>(out), Hq, Lmax, ncmax, len_offset);
+    if (qscales) {
+        if (!aligned16(qscales)) return DET_EALIGN;
+        hipLaunchKernelGGL(attn_combine_kernel<true>, dim3(Hq, B), dim3(128), 0, s, seqlens, ws_m, ws_l, ws_o, out, Hq,
+                           Lmax, ncmax, len_offset, static_cast<float*>(qscales), (B + 3) & ~3);
+    } else {
+        hipLaunchKernelGGL(attn_combine_kernel<false>, dim3(Hq, B), dim3(128), 0, s, seqlens, ws_m, ws_l, ws_o, out, Hq,
+                           Lmax, ncmax, len_offset, nullptr, 0);
+    }
     return check_launch();
 }
 
@@ -390,6 +420,15 @@ extern "C" int det_attn_decode_rows(const void* q, const void* kcache, const voi
     if (!slots) return DET_EINVAL;
     return attn_decode_impl(q, kcache, vcache, seqlens, slots, 0, out, ws, ws_bytes, R, Hq, Hkv, D, Lmax, scale,
                             static_cast<hipStream_t>(stream));
+}
+
+extern "C" int det_attn_decode_quant_q8(const void* q, const void* kcache, const void* vcache, const int32_t* seqlens,
+                                        const int32_t* slots, void* codes, void* scales, void* ws, size_t ws_bytes,
+                                        int R, int Hq, int Hkv, int D, int Lmax, float scale, void* stream)
+{
+    if (!scales) return DET_EINVAL;
+    return attn_decode_impl(q, kcache, vcache, seqlens, slots, 0, codes, ws, ws_bytes, R, Hq, Hkv, D, Lmax, scale,
+                            static_cast<hipStream_t>(stream), scales);
 }
 
 extern "C" int det_softmax_f32(const float* s, const int32_t* lens, float* p, float* m_out, float* l_out,

@@ -34,7 +34,7 @@ static LayerWs layer_ws(const det_layer_cfg& c, int B)
 // Workspace of the quantized layer: the bf16 buffers of the plain one that are still needed, plus one
 // set of activation codes and scales (the widest projection input), reused by the four projections.
 struct QLayerWs {
-    size_t qkv, qbuf, att, mm, codes, scales, attn, attn_bytes, total;
+    size_t qkv, qbuf, mm, codes, scales, attn, attn_bytes, total;
 };
 
 static QLayerWs qlayer_ws(const det_layer_cfg& c, int R)
@@ -51,7 +51,6 @@ static QLayerWs qlayer_ws(const det_layer_cfg& c, int R)
     const int kmax = c.H > nq ? (c.H > c.F ? c.H : c.F) : (nq > c.F ? nq : c.F);
     w.qkv = take(2 * (size_t)R * nqkv);
     w.qbuf = take(2 * (size_t)R * nq);
-    w.att = take(2 * (size_t)R * nq);
     w.mm = take(2 * (size_t)R * c.F);
     w.codes = take(det_quant_act_codes_bytes(R, kmax));
     w.scales = take(det_quant_act_scales_bytes(R, kmax));
@@ -158,7 +157,6 @@ extern "C" int det_qdecoder_layer(const det_layer_weights* w, const det_layer_cf
     char* base = static_cast<char*>(ws);
     void* qkv = base + l.qkv;
     void* qbuf = base + l.qbuf;
-    void* att = base + l.att;
     void* mm = base + l.mm;
     void* codes = base + l.codes;
     void* scales = base + l.scales;
@@ -176,9 +174,8 @@ extern "C" int det_qdecoder_layer(const det_layer_weights* w, const det_layer_cf
     DET_TRY(det_qgemm_w4a8(codes, scales, w->wqkv, qkv, nqkv, R, nqkv, c.H, DET_BF16, stream));
     DET_TRY(rope_append(qkv, qbuf, kcache, vcache, positions, slots, rope_cos, rope_sin, R, c.Hq, c.Hkv, c.D, c.Lmax,
                         s));
-    DET_TRY(attn_decode_impl(qbuf, kcache, vcache, positions, slots, 1, att, aws, l.attn_bytes, R, c.Hq, c.Hkv, c.D,
-                             c.Lmax, c.scale, s));
-    DET_TRY(det_quant_act_q8(att, nq, codes, scales, R, nq, stream));
+    DET_TRY(attn_decode_impl(qbuf, kcache, vcache, positions, slots, 1, codes, aws, l.attn_bytes, R, c.Hq, c.Hkv, c.D,
+                             c.Lmax, c.scale, s, scales));
     DET_TRY(det_qgemm_w4a8_residual(codes, scales, w->wo, x_inout, c.H, x_inout, c.H, R, c.H, nq, stream));
     DET_TRY(det_rmsnorm_quant_q8(x_inout, w->w_norm2, codes, scales, R, c.H, c.eps, stream));
     DET_TRY(det_qgemm_w4a8_swiglu(codes, scales, w->wgu, mm, c.F, R, c.F, c.H, stream));

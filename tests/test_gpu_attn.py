@@ -189,3 +189,35 @@ def test_rows_variant_slots(d, orc):
         assert np.array_equal(got[r], one[3])
     ref, refabs = orc.attn_decode_f64(qr[250:251], k[3:4], v[3:4], [251], SCALE)
     assert within_bound(bits_to_f64(got[250:251]), ref, refabs).all()
+
+
+def test_quantized_output_equals_quantizer_of_the_output(d, orc):
+    """det_attn_decode_quant_q8 writes the activation codes and scales of the attention output: the
+    oracle's quantizer applied to the bytes det_attn_decode returns (which the tests above hold to the
+    attention bound), with and without slots, ragged lengths, a zero-length row."""
+    B, Hq, Hkv, Lmax = 5, 16, 4, 700
+    q, k, v = inputs(ds.tensor_seed(3, 60), B, Hq, Hkv, Lmax)
+    lens = np.asarray([700, 1, 257, 0, 512], dtype=np.int32)
+    step("attention with quantized output")
+    plain = run_attn(d, q, k, v, lens)
+    ws = torch.empty(d.det_attn_decode_workspace_bytes(B, Hq, 128, Lmax), dtype=torch.uint8, device=DEV)
+    ws.fill_(0xFF)
+    codes = torch.full((B, Hq * 128), 99, dtype=torch.int8, device=DEV)
+    scales = torch.full((d.det_quant_act_scales_bytes(B, Hq * 128) // 4,), float("nan"), dtype=torch.float32, device=DEV)
+    d.det_attn_decode_quant_q8(up_bf16(q), up_bf16(k), up_bf16(v), up(lens), None, codes, scales, ws, SCALE)
+    torch.cuda.synchronize()
+    po, do = orc.quant_a8(plain.reshape(B, Hq * 128))
+    ldd = (B + 3) & ~3
+    got_d = np.ascontiguousarray(scales.cpu().numpy().reshape(Hq * 2, ldd)[:, :B].T)
+    assert np.array_equal(codes.cpu().numpy(), po) and np.array_equal(got_d.view(np.uint32), do.view(np.uint32))
+    step("attention with quantized output, rows on permuted slots")
+    slots = np.asarray([3, 0, 4, 1, 2], dtype=np.int32)
+    codes2 = torch.empty_like(codes)
+    scales2 = torch.empty_like(scales)
+    d.det_attn_decode_quant_q8(up_bf16(q[slots]), up_bf16(k), up_bf16(v), up(lens[slots]), up(slots), codes2, scales2, ws,
+                               SCALE)
+    torch.cuda.synchronize()
+    # row r now attends with the query and length of sequence slots[r] over cache slot slots[r]
+    assert np.array_equal(codes2.cpu().numpy(), po[slots])
+    got_d2 = np.ascontiguousarray(scales2.cpu().numpy().reshape(Hq * 2, ldd)[:, :B].T)
+    assert np.array_equal(got_d2.view(np.uint32), do[slots].view(np.uint32))
