@@ -16,7 +16,9 @@
 // matrix-core operand order, then 16 scales), so a chunk's weights are one contiguous run copied as
 // it lies.  And the eight computing waves split the tile by column block first (wave w: column block
 // w % CB, row blocks w / CB, w / CB + 8/CB, ...): at small M the work per stage is the unpacking of
-// the codes, which a single wave could not do at the rate the weights stream in.
+// the codes, which a single wave could not do at the rate the weights stream in.  Tiles of at most 8
+// rows and 2 column blocks go further and split the stages of a chunk over the waves (run_sp below):
+// only the accumulation chain has a defined order, and it keeps it.
 #include <type_traits>
 
 #include "common.h"
@@ -223,9 +225,8 @@ __global__ __launch_bounds__(64 * (kQWaves + kQLoaders)) void qgemm_kernel(
     const uint32_t ring_addr = (uint32_t)(uintptr_t)(lds_char_t*)ring;
     auto chunk_stages = [&](int c) { return c < nchunks - 1 ? SPC : (c == nchunks - 1 ? tp.last_cnt : 0); };
     // LDS layout of a chunk of s_cnt stages: the weight run (s_cnt*WST bytes as they lie in memory,
-    // rounded up to 1 KB), then s_cnt*RB activation tiles of 1 KB (stage, row block: 16 rows x 64
-    // codes, the four 16-byte pieces of row i swizzled: piece t at slot t ^ ((i/4)%4)), then s_cnt
-    // blocks of 1 KB with the activation scales of the tile's rows for the stage.
+    // rounded up to 1 KB), then the activation tiles (stage, row block: rows x 64 codes, the four
+    // 16-byte pieces of row i swizzled: piece t at slot t ^ ((i/4)%4)), then the activation scales.
     auto wrun = [&](int s_cnt) { return (uint32_t)((s_cnt * WST + 1023) & ~1023); };
     // The activation tiles of a chunk follow its weight run and the activation scales follow the tiles:
     // tile (stage, row block) has TB bytes (16 rows of 64 codes; a single row block of at most 8 or 4
@@ -488,6 +489,11 @@ __global__ __launch_bounds__(64 * (kQWaves + kQLoaders)) void qgemm_kernel(
             auto stages = [&](int sl, auto uu_tag) {
                 constexpr int UU = decltype(uu_tag)::value;
                 constexpr int G = NR < 4 ? NR : 4;  // row blocks at a time
+                // With one or two row blocks the wave's time goes into vector instructions, not the matrix
+                // core: the stored nibbles q + 8 are then used as they are and the matrix core starts from
+                // -8 * (sum of the block's activation codes), one more matrix instruction per row block
+                // instead of twelve vector instructions per stage; the integer is the same.
+                constexpr bool kBias = NR <= 2;
                 auto expand = [](uint32_t x) { return (((x & 0x0F0F0F0Fu) | 0x80808080u) - 0x08080808u) ^ 0x80808080u; };
                 v4i wq[UU];
                 float sc[UU][4];
@@ -496,11 +502,18 @@ __global__ __launch_bounds__(64 * (kQWaves + kQLoaders)) void qgemm_kernel(
                     const char* wst = slot + (sl + u) * WST;
                     const uint2 codes = *reinterpret_cast<const uint2*>(wst + j * 512 + lane * 8);
                     const uint2 sraw = *reinterpret_cast<const uint2*>(wst + 512 * CB + j * 32 + g * 8);
-                    // 16 codes -> 16 signed bytes: per byte (u | 0x80) - 8, then the top bit flipped back
-                    wq[u][0] = (int)expand(codes.x);
-                    wq[u][1] = (int)expand(codes.x >> 4);
-                    wq[u][2] = (int)expand(codes.y);
-                    wq[u][3] = (int)expand(codes.y >> 4);
+                    if constexpr (kBias) {
+                        wq[u][0] = (int)(codes.x & 0x0F0F0F0Fu);
+                        wq[u][1] = (int)((codes.x >> 4) & 0x0F0F0F0Fu);
+                        wq[u][2] = (int)(codes.y & 0x0F0F0F0Fu);
+                        wq[u][3] = (int)((codes.y >> 4) & 0x0F0F0F0Fu);
+                    } else {
+                        // 16 codes -> 16 signed bytes: per byte (u | 0x80) - 8, then the top bit flipped back
+                        wq[u][0] = (int)expand(codes.x);
+                        wq[u][1] = (int)expand(codes.x >> 4);
+                        wq[u][2] = (int)expand(codes.y);
+                        wq[u][3] = (int)expand(codes.y >> 4);
+                    }
                     sc[u][0] = bf16lo_to_f32(sraw.x);
                     sc[u][1] = bf16hi_to_f32(sraw.x);
                     sc[u][2] = bf16lo_to_f32(sraw.y);
@@ -518,7 +531,13 @@ __global__ __launch_bounds__(64 * (kQWaves + kQLoaders)) void qgemm_kernel(
                                                                          64 * lrc + 16 * (g ^ ((lrc >> 2) & 3)));
                             dv[u][r] = *reinterpret_cast<const float*>(scales + (size_t)(sl + u) * RB * 64 +
                                                                        (16 * rbs[r0 + r] + lr) * 4);
-                            pr[u][r] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wq[u], xa, v4i{0, 0, 0, 0}, 0, 0, 0);
+                            if constexpr (kBias) {
+                                const int m8 = (int)0xF8F8F8F8u;
+                                const v4i base = __builtin_amdgcn_mfma_i32_16x16x64_i8(v4i{m8, m8, m8, m8}, xa, v4i{0, 0, 0, 0}, 0, 0, 0);
+                                pr[u][r] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wq[u], xa, base, 0, 0, 0);
+                            } else {
+                                pr[u][r] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wq[u], xa, v4i{0, 0, 0, 0}, 0, 0, 0);
+                            }
                         }
 #pragma unroll
                     for (int u = 0; u < UU; ++u)
