@@ -300,6 +300,14 @@ int det_rmsnorm_quant_q8(const void *x, const void *w, void *codes, void *scales
 /* det_attn_decode_quant_q8: det_quant_act_q8 of the [R, Hq*D] output of det_attn_decode_rows (slots may be
  *   NULL: row r reads cache slot r, as det_attn_decode), written as codes int8 [R, Hq*D] and scales for
  *   (M = R, K = Hq*D); other arguments and errors as det_attn_decode_rows. */
+/* det_qgemm_w4a8_swiglu_quant: det_quant_act_q8 of the [M, F] output of det_qgemm_w4a8_swiglu, written as codes_out
+ *   int8 [M, F] and scales_out for (M, K = F), without the bf16 round trip.  Only where the kernel's tile
+ *   is 128 packed columns wide (then a tile row is exactly one 64-output block):
+ *   det_qgemm_w4a8_swiglu_quant_supported(F, K) != 0, else DET_ESHAPE; F % 64 == 0.  codes_out / scales_out
+ *   must not be the input codes / scales. */
+int det_qgemm_w4a8_swiglu_quant_supported(int F, int K);
+int det_qgemm_w4a8_swiglu_quant(const void *codes, const void *scales, const void *packed_gate_up,
+                                void *codes_out, void *scales_out, int M, int F, int K, void *stream);
 int det_attn_decode_quant_q8(const void *q, const void *kcache, const void *vcache, const int32_t *seqlens,
                              const int32_t *slots, void *codes, void *scales, void *ws, size_t ws_bytes,
                              int R, int Hq, int Hkv, int D, int Lmax, float scale, void *stream);

@@ -62,6 +62,8 @@ SIGNATURES = {
     "det_qgemm_w4a8_residual": (_i, [_vp, _vp, _vp, _vp, _i, _vp, _i, _i, _i, _i, _vp]),
     "det_qgemm_w4a8_swiglu": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),
     "det_rmsnorm_quant_q8": (_i, [_vp, _vp, _vp, _vp, _i, _i, _f, _vp]),
+    "det_qgemm_w4a8_swiglu_quant_supported": (_i, [_i, _i]),
+    "det_qgemm_w4a8_swiglu_quant": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _vp]),
     "det_attn_decode_quant_q8": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _i, _i, _i, _i, _i, _f, _vp]),
     "det_qdecoder_layer_workspace_bytes": (_sz, [C.POINTER(LayerCfg), _i]),
     "det_qdecoder_layer": (_i, [C.POINTER(LayerWeights), C.POINTER(LayerCfg), _vp, _vp, _vp, _vp, _vp, _vp, _vp,

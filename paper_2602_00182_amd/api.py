@@ -23,6 +23,7 @@ __all__ = [
     "det_qgemm_w4a8", "quant_pack_weight", "quant_activations", "det_qgemm_w4a8_residual",
     "det_qgemm_w4a8_swiglu", "det_quant_pack_w4_gate_up", "quant_pack_gate_up", "det_rmsnorm_quant_q8",
     "det_qdecoder_layer_workspace_bytes", "det_qdecoder_layer", "det_attn_decode_quant_q8",
+    "det_qgemm_w4a8_swiglu_quant_supported", "det_qgemm_w4a8_swiglu_quant",
 ]
 
 _CODES = {1: "DET_EINVAL", 2: "DET_ESHAPE", 3: "DET_EALIGN", 4: "DET_EWORKSPACE", 5: "DET_EHIP"}
@@ -123,6 +124,19 @@ def det_qgemm_w4a8_swiglu(codes, scales, packed_gate_up, y, F: int, stream=None)
     _check("det_qgemm_w4a8_swiglu", lib().det_qgemm_w4a8_swiglu(
         _contig(codes, torch.int8), _contig(scales, torch.float32), _contig(packed_gate_up),
         _ptr(y, torch.bfloat16), _ld(y, F), M, F, K, _stream(stream)))
+
+
+def det_qgemm_w4a8_swiglu_quant_supported(F: int, K: int) -> bool:
+    return bool(lib().det_qgemm_w4a8_swiglu_quant_supported(F, K))
+
+
+def det_qgemm_w4a8_swiglu_quant(codes, scales, packed_gate_up, codes_out, scales_out, F: int, stream=None) -> None:
+    M, K = codes.shape
+    if codes_out.shape != (M, F) or scales_out.numel() * 4 < det_quant_act_scales_bytes(M, F):
+        raise ValueError("bad output shape")
+    _check("det_qgemm_w4a8_swiglu_quant", lib().det_qgemm_w4a8_swiglu_quant(
+        _contig(codes, torch.int8), _contig(scales, torch.float32), _contig(packed_gate_up),
+        _contig(codes_out, torch.int8), _contig(scales_out, torch.float32), M, F, K, _stream(stream)))
 
 
 def det_quant_pack_w4_gate_up(b_kn, packed, stream=None) -> None:

@@ -107,6 +107,9 @@ __device__ __forceinline__ float block_max(float v, float* scratch)
 // plain GEMM followed by the SwiGLU step.  C (and R) may alias nothing the kernel reads except that C
 // may be R itself: an output element is read and written by the same lane only.
 constexpr int kEpiStore = 0, kEpiResidual = 1, kEpiSwiglu = 2;
+// kEpiSwigluQuant (quantized GEMM with 128-column tiles only): the SwiGLU epilogue's bf16 values written as
+// their 8-bit block quantization; a tile row holds exactly one block of 64 outputs.
+constexpr int kEpiSwigluQuant = 3;
 
 __device__ __forceinline__ float silu_mul(float gate, float up)
 {

@@ -34,7 +34,7 @@ static LayerWs layer_ws(const det_layer_cfg& c, int B)
 // Workspace of the quantized layer: the bf16 buffers of the plain one that are still needed, plus one
 // set of activation codes and scales (the widest projection input), reused by the four projections.
 struct QLayerWs {
-    size_t qkv, qbuf, mm, codes, scales, attn, attn_bytes, total;
+    size_t qkv, qbuf, mm, codes, scales, codes2, scales2, attn, attn_bytes, total;
 };
 
 static QLayerWs qlayer_ws(const det_layer_cfg& c, int R)
@@ -54,6 +54,9 @@ static QLayerWs qlayer_ws(const det_layer_cfg& c, int R)
     w.mm = take(2 * (size_t)R * c.F);
     w.codes = take(det_quant_act_codes_bytes(R, kmax));
     w.scales = take(det_quant_act_scales_bytes(R, kmax));
+    // the SwiGLU output's codes, written by the gate/up projection while it still reads the first set
+    w.codes2 = take(det_quant_act_codes_bytes(R, c.F));
+    w.scales2 = take(det_quant_act_scales_bytes(R, c.F));
     w.attn_bytes = det_attn_decode_workspace_bytes(R, c.Hq, c.D, c.Lmax);
     w.attn = take(w.attn_bytes);
     w.total = off;
@@ -160,6 +163,8 @@ extern "C" int det_qdecoder_layer(const det_layer_weights* w, const det_layer_cf
     void* mm = base + l.mm;
     void* codes = base + l.codes;
     void* scales = base + l.scales;
+    void* codes2 = base + l.codes2;
+    void* scales2 = base + l.scales2;
     void* aws = base + l.attn;
     const int nqkv = (c.Hq + 2 * c.Hkv) * c.D;
     const int nq = c.Hq * c.D;
@@ -178,9 +183,13 @@ extern "C" int det_qdecoder_layer(const det_layer_weights* w, const det_layer_cf
                              c.Lmax, c.scale, s, scales));
     DET_TRY(det_qgemm_w4a8_residual(codes, scales, w->wo, x_inout, c.H, x_inout, c.H, R, c.H, nq, stream));
     DET_TRY(det_rmsnorm_quant_q8(x_inout, w->w_norm2, codes, scales, R, c.H, c.eps, stream));
-    DET_TRY(det_qgemm_w4a8_swiglu(codes, scales, w->wgu, mm, c.F, R, c.F, c.H, stream));
-    DET_TRY(det_quant_act_q8(mm, c.F, codes, scales, R, c.F, stream));
-    DET_TRY(det_qgemm_w4a8_residual(codes, scales, w->wdown, x_inout, c.H, x_inout, c.H, R, c.H, c.F, stream));
+    if (det_qgemm_w4a8_swiglu_quant_supported(c.F, c.H)) {
+        DET_TRY(det_qgemm_w4a8_swiglu_quant(codes, scales, w->wgu, codes2, scales2, R, c.F, c.H, stream));
+    } else {
+        DET_TRY(det_qgemm_w4a8_swiglu(codes, scales, w->wgu, mm, c.F, R, c.F, c.H, stream));
+        DET_TRY(det_quant_act_q8(mm, c.F, codes2, scales2, R, c.F, stream));
+    }
+    DET_TRY(det_qgemm_w4a8_residual(codes2, scales2, w->wdown, x_inout, c.H, x_inout, c.H, R, c.H, c.F, stream));
 #undef DET_TRY
     return DET_OK;
 }

@@ -206,9 +206,11 @@ static qgemm_plan make_qgemm_plan(int mrem, int cb, int K)
 template <int CB, int EPI>
 __global__ __launch_bounds__(64 * (kQWaves + kQLoaders)) void qgemm_kernel(
     const int8_t* __restrict__ qa, int K, const float* __restrict__ da, int ldd, const uint8_t* __restrict__ wp, void* C,
-    int ldc, const uint16_t* R, int ldr, int out_f32, qgemm_plan plan_full, qgemm_plan plan_tail)
+    int ldc, const uint16_t* R, int ldr, int out_f32, qgemm_plan plan_full, qgemm_plan plan_tail, float* qscales_out)
 {
     __shared__ uint4 ring[kQRing * 64];
+    __shared__ float rowmax[EPI == kEpiSwigluQuant ? 8 * 256 : 1];  // row maxima of the eight waves, that epilogue only
+    static_assert(EPI != kEpiSwigluQuant || CB == 8, "a 128-column tile holds one 64-output block per row");
     constexpr int RG = 8 / CB;        // row groups: wave w computes column block w % CB for row group w / CB
     constexpr int MAXR = 16 / RG;     // most row blocks a wave can own
     constexpr int WST = qstage_w_bytes(CB);
@@ -330,6 +332,7 @@ __global__ __launch_bounds__(64 * (kQWaves + kQLoaders)) void qgemm_kernel(
             slot_c = slot_c + 1 == nslots ? 0 : slot_c + 1;
         }
         if (tp.SG > 1) __builtin_amdgcn_s_barrier();  // the barrier after which the last chunk's results are read
+        if constexpr (EPI == kEpiSwigluQuant) __builtin_amdgcn_s_barrier();  // the epilogue's exchange of row maxima
         return;
     }
 
@@ -557,6 +560,48 @@ __global__ __launch_bounds__(64 * (kQWaves + kQLoaders)) void qgemm_kernel(
 
         // Lane holds C[row = 16*rb + lr][n0 + 16j + 4g + v], v = 0..3.
         const int n = blockIdx.x * (16 * CB) + 16 * j + 4 * g;
+        if constexpr (EPI == kEpiSwigluQuant) {
+            // Columns are gate/up pairs: the lane holds outputs 8j + 2g and 8j + 2g + 1 of the tile's 64, the
+            // tile row is one quantization block.  Its maximum: the lane's two values, the four lanes
+            // of a row (g), then the eight waves (j) through LDS.  Here CB = 8: every wave owns all
+            // row blocks (rbs[r] = r) and all of them take part in the barrier.
+            float y[NR][2];
+#pragma unroll
+            for (int r = 0; r < NR; ++r) {
+                const float g0 = bf16_to_f32(f32_to_bf16_rne(acc[r][0])), u0 = bf16_to_f32(f32_to_bf16_rne(acc[r][1]));
+                const float g1 = bf16_to_f32(f32_to_bf16_rne(acc[r][2])), u1 = bf16_to_f32(f32_to_bf16_rne(acc[r][3]));
+                y[r][0] = bf16_to_f32(f32_to_bf16_rne(silu_mul(g0, u0)));
+                y[r][1] = bf16_to_f32(f32_to_bf16_rne(silu_mul(g1, u1)));
+                float mx = fmaxf(fabsf(y[r][0]), fabsf(y[r][1]));
+                mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+                mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+                if (g == 0) rowmax[wave * 256 + 16 * rbs[r] + lr] = mx;
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+#pragma unroll
+            for (int r = 0; r < NR; ++r) {
+                const int rowl = 16 * rbs[r] + lr;
+                float amax = rowmax[rowl];
+#pragma unroll
+                for (int w = 1; w < 8; ++w) amax = fmaxf(amax, rowmax[w * 256 + rowl]);
+                const float df = amax / 127.0f;
+                uint32_t c2 = 0;
+                if (df != 0.0f) {
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        const float qv = rintf(y[r][e] / df);
+                        const int iv = qv < -127.0f ? -127 : (qv > 127.0f ? 127 : (int)qv);
+                        c2 |= (uint32_t)(iv & 0xFF) << (8 * e);
+                    }
+                }
+                if (r < cnt && rowl < mrem) {
+                    const size_t row = (size_t)(m0 + rowl);
+                    *reinterpret_cast<uint16_t*>(static_cast<int8_t*>(C) + row * ldc + (n >> 1)) = (uint16_t)c2;
+                    if (j == 0 && g == 0) qscales_out[(size_t)blockIdx.x * ldr + row] = df;
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int r = 0; r < NR; ++r) {
             const int rowl = 16 * rbs[r] + lr;
@@ -585,14 +630,14 @@ static int q_ldd(int M) { return (M + 3) & ~3; }
 
 template <int CB, int EPI>
 static void launch_qgemm(const void* qa, const void* da, int ldd, const void* wp, void* C, int ldc, const void* R, int ldr,
-                         int M, int N, int K, int out_f32, hipStream_t s)
+                         int M, int N, int K, int out_f32, hipStream_t s, float* qscales_out = nullptr)
 {
     dim3 grid(N / (16 * CB), (M + 255) / 256);
     const qgemm_plan full = make_qgemm_plan(256, CB, K);
     const qgemm_plan tail = make_qgemm_plan(M - 256 * ((M - 1) / 256), CB, K);
     hipLaunchKernelGGL((qgemm_kernel<CB, EPI>), grid, dim3(64 * (kQWaves + kQLoaders)), 0, s,
                        static_cast<const int8_t*>(qa), K, static_cast<const float*>(da), ldd, static_cast<const uint8_t*>(wp),
-                       C, ldc, static_cast<const uint16_t*>(R), ldr, out_f32, full, tail);
+                       C, ldc, static_cast<const uint16_t*>(R), ldr, out_f32, full, tail, qscales_out);
 }
 
 // N: columns of the packed matrix (2F for the SwiGLU epilogue).
@@ -713,4 +758,24 @@ extern "C" int det_qgemm_w4a8_swiglu(const void* codes, const void* scales, cons
     if (rc != DET_OK) return rc;
     return qgemm_dispatch<kEpiSwiglu>(codes, scales, packed_gate_up, Y, ldy, nullptr, 0, M, 2 * F, K, 0,
                                       static_cast<hipStream_t>(stream));
+}
+
+extern "C" int det_qgemm_w4a8_swiglu_quant_supported(int F, int K)
+{
+    return F >= 8 && F % 8 == 0 && F <= (1 << 29) && qgemm_shape_ok(2 * F, K) && qgemm_cols_per_block(2 * F) == 8;
+}
+
+extern "C" int det_qgemm_w4a8_swiglu_quant(const void* codes, const void* scales, const void* packed_gate_up, void* codes_out,
+                                           void* scales_out, int M, int F, int K, void* stream)
+{
+    if (!scales_out) return DET_EINVAL;
+    if (F < 1 || F % 64 != 0 || F > (1 << 29)) return DET_ESHAPE;
+    const int rc = qgemm_args_ok(codes, scales, packed_gate_up, codes_out, F, M, 2 * F, F, K);
+    if (rc != DET_OK) return rc;
+    if (!det_qgemm_w4a8_swiglu_quant_supported(F, K)) return DET_ESHAPE;
+    if (!aligned16(scales_out)) return DET_EALIGN;
+    // the kernel's ldr argument carries the row stride of the output scales
+    launch_qgemm<8, kEpiSwigluQuant>(codes, scales, q_ldd(M), packed_gate_up, codes_out, F, nullptr, q_ldd(M), M, 2 * F, K, 0,
+                                     static_cast<hipStream_t>(stream), static_cast<float*>(scales_out));
+    return check_launch();
 }

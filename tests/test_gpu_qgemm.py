@@ -180,3 +180,35 @@ def test_qgemm_swiglu_epilogue_matches_oracle(d, orc, M, K, F):
     gu = orc.qlinear(a, *orc.quant_w4(w))
     want = orc.swiglu(np.ascontiguousarray(gu[:, :F]), np.ascontiguousarray(gu[:, F:]))
     assert np.array_equal(down_bf16(y), want)
+
+
+@pytest.mark.parametrize("M,K,F", [(1, 256, 14336), (19, 512, 14336), (70, 256, 16000 * 2 // 2), (200, 256, 12288), (300, 256, 14336)])
+def test_qgemm_swiglu_quant_epilogue_matches_oracle(d, orc, M, K, F):
+    """The SwiGLU epilogue that writes activation codes: the oracle's quantizer applied to the oracle's
+    SwiGLU of the quantized projection, code for code and scale bit for bit."""
+    assert d.det_qgemm_w4a8_swiglu_quant_supported(F, K)
+    a = ds.normal_bf16(ds.tensor_seed(6, 80) + M, (M, K), 1.0, 0.0)
+    w = ds.normal_bf16(ds.tensor_seed(6, 81) + F, (K, 2 * F), 0.05, 0.0)
+    w[:, 64:128] = 0                                # an all-zero output block: scale 0, codes 0
+    step(f"qgemm swiglu+quant epilogue M={M} K={K} F={F}")
+    packed = d.quant_pack_gate_up(up_bf16(w))
+    codes, scales = d.quant_activations(up_bf16(a))
+    co = torch.full((M, F), 99, dtype=torch.int8, device=DEV)
+    so = torch.full((d.det_quant_act_scales_bytes(M, F) // 4,), float("nan"), dtype=torch.float32, device=DEV)
+    d.det_qgemm_w4a8_swiglu_quant(codes, scales, packed, co, so, F)
+    torch.cuda.synchronize()
+    gu = orc.qlinear(a, *orc.quant_w4(w))
+    mm = orc.swiglu(np.ascontiguousarray(gu[:, :F]), np.ascontiguousarray(gu[:, F:]))
+    po, do = orc.quant_a8(mm)
+    ldd = (M + 3) & ~3
+    got_d = np.ascontiguousarray(so.cpu().numpy().reshape(F // 64, ldd)[:, :M].T)
+    assert np.array_equal(co.cpu().numpy(), po) and np.array_equal(got_d.view(np.uint32), do.view(np.uint32))
+
+
+def test_qgemm_swiglu_quant_unsupported_shapes(d):
+    from paper_2602_00182_amd._lib import lib
+    assert not d.det_qgemm_w4a8_swiglu_quant_supported(5632, 2048)      # 32-column tiles
+    buf = torch.zeros(1 << 16, dtype=torch.uint8, device=DEV)
+    p = buf.data_ptr()
+    assert lib().det_qgemm_w4a8_swiglu_quant(p, p, p, p, p, 1, 5632, 2048, None) == 2
+    assert lib().det_qgemm_w4a8_swiglu_quant(p, p, p, p, None, 1, 14336, 256, None) == 1
