@@ -221,7 +221,57 @@ def main():
         result["attention"] = attention_numbers(torch, det, ds, dev)
         result["decode"] = decode_numbers(torch, det, ds, dev)
         result["qgemm_w4a8"] = qgemm_numbers(torch, det, ds, dev)
+        result["library_gemm"] = library_gemm(torch, ds, dev, sweep_cold)
     print(json.dumps(result))
+
+
+def library_gemm(torch, ds, dev, sweep_cold):
+    """Context for the cost of determinism (the paper's section 6.5 quotes its kernels at 95-98 % of the
+    vendor library): torch.matmul, i.e. the platform's default bf16 GEMM with no ordering guarantee, on the
+    same shapes and M with the same rotation over three weight sets.  det_over_library = this library's
+    cold time / the default GEMM's time (below 1: the deterministic kernel is faster).  Not part of `value`."""
+    ours = {(r["K"], r["N"], r["M"]): r["us"] for r in sweep_cold}
+    rows = []
+    for (K, N) in SHAPES:
+        ws = [ds.normal_bf16_torch(ds.tensor_seed(2, 50 + si) + K // 64 + N, (K, N), 0.02, 0.0, dev) for si in range(N_SETS)]
+        x = ds.normal_bf16_torch(ds.tensor_seed(2, 7), (256, K), 1.0, 0.0, dev)
+        c = torch.empty((256, N), dtype=torch.bfloat16, device=dev)
+        for M in MS:
+            n = 12
+
+            def launches():
+                for i in range(n):
+                    torch.matmul(x[:M], ws[i % N_SETS], out=c[:M])
+
+            launches()
+            torch.cuda.synchronize()
+            # The twelve launches are replayed from a captured graph so that the host's dispatch time (10-20 us
+            # a call, more than the small kernels take) is not charged to the library; eager timing otherwise.
+            timed, how = launches, "eager"
+            try:
+                side = torch.cuda.Stream()
+                with torch.cuda.stream(side):
+                    launches()
+                torch.cuda.synchronize()
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph):
+                    launches()
+                graph.replay()
+                torch.cuda.synchronize()
+                timed, how = graph.replay, "graph"
+            except Exception:
+                torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            timed()
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) / n * 1e3
+            rows.append({"K": K, "N": N, "M": M, "us": round(us, 2), "timed": how,
+                         "det_over_library": round(ours[(K, N, M)] / us, 3)})
+        del ws, x, c
+        torch.cuda.empty_cache()
+    return rows
 
 
 def warm_sweep(torch, det, weights, X, C, table):
