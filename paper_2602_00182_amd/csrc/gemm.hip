@@ -551,6 +551,17 @@ static int gemm_dispatch(const void* A, int lda, const void* Bp, void* C, int ld
     // packed as they are (the workgroup streams 4/cb adjacent slabs).  The arithmetic of an output
     // element is the same chain of matrix-core steps in either tiling, so its bytes do not depend on
     // which ran; the thresholds are where the measured times cross.
+    // Launches with enough rows that 128-column tiles of 256 rows still give every compute unit a workgroup
+    // (prefill): the widest tile moves the fewest bytes per flop through the memory pipe, whatever the packing.
+    if (!small && cb < 8 && 8 % cb == 0 && N % 128 == 0 && (long long)((M + 255) / 256) * (N / 128) >= 256) {
+        if (cb == 1)
+            launch_gemm<8, kRingBig, EPI, 8, 4, 1>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s);
+        else if (cb == 2)
+            launch_gemm<8, kRingBig, EPI, 8, 4, 2>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s);
+        else
+            launch_gemm<8, kRingBig, EPI, 8, 4, 4>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s);
+        return check_launch();
+    }
     if (!small && N % 64 == 0 && ((cb == 1 && M >= 96) || (cb == 2 && M >= 192))) {
         const int row_tiles = 256 / (N / 64) > 0 ? 256 / (N / 64) : 1;
         // a tile holds at most 256 rows (16 row blocks); longer launches take several rounds of those

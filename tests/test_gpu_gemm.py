@@ -168,6 +168,36 @@ def test_tile_shape_switch_points_keep_bytes(d, orc, K, N):
     assert within_bound(bits_to_f64(full[rows, cols]), ref, refabs).all()
 
 
+@pytest.mark.parametrize("K,N", [(512, 1024), (256, 2048), (128, 6144), (128, 12288)])
+def test_prefill_sized_launch_keeps_bytes(d, orc, K, N):
+    """Launches with thousands of rows use 128-column tiles whatever the packing (16-, 32- or 64-column
+    slabs): rows keep the bytes of the launches that compute them in small groups, and a sample agrees
+    with fp64."""
+    tiles = -(-256 // (N // 128))          # row tiles that make 256 workgroups of 128 columns
+    M = 256 * (tiles - 1) + 77
+    X = ds.normal_bf16(ds.tensor_seed(3, K + 1), (M, K))
+    W = ds.normal_bf16(ds.tensor_seed(3, N + 1), (K, N), 0.05)
+    Wp = d.pack_weight(up_bf16(W))
+    Xd = up_bf16(X)
+
+    def gemm(lo, hi):
+        C = torch.empty((hi - lo, N), dtype=torch.bfloat16, device=DEV)
+        d.det_gemm_bf16(Xd[lo:hi], Wp, C, N, K)
+        torch.cuda.synchronize()
+        return down_bf16(C)
+
+    step(f"gemm prefill-sized K={K} N={N} M={M}")
+    full = gemm(0, M)
+    for lo, hi in [(0, 1), (0, 64), (255, 300), (M - 100, M), (M - 1, M), (M // 2, M // 2 + 256)]:
+        assert np.array_equal(gemm(lo, hi), full[lo:hi]), (lo, hi)
+    rng = np.random.default_rng(K + N)
+    rows = rng.integers(0, M, 2048).astype(np.int32)
+    cols = rng.integers(0, N, 2048).astype(np.int32)
+    rows[:8] = M - 1
+    ref, refabs = orc.gemm_f64_sample(X, W, rows, cols)
+    assert within_bound(bits_to_f64(full[rows, cols]), ref, refabs).all()
+
+
 def test_rows_do_not_see_each_other(d, orc):
     """Row i's bytes are unchanged when the other rows are replaced, when row i moves to another
     slot, and when M is not a multiple of the row block."""
