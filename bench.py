@@ -518,6 +518,22 @@ def decode_numbers(torch, det, ds, dev):
             rows.append({"B": B, "context": 512, "ms_per_step": round(dt * 1e3, 3), "tokens_per_s": round(B / dt, 1)})
             del st
         out[key] = rows
+    # the whole config-5 job: 64 prompts of 16..512 tokens, 128 new tokens each, greedy, one batch:
+    # one-pass prefill, then 127 decode steps (generated tokens per second of wall time, job total)
+    from paper_2602_00182_amd.decode import prefill_decode
+    lens = ds.uniform_int(ds.tensor_seed(5, 500), (64,), 16, 512)
+    toks = ds.uniform_int(ds.tensor_seed(5, 501), (64, 512), 0, V - 1)
+    toks_d, lens_d = torch.from_numpy(toks).to(dev), torch.from_numpy(lens).to(dev)
+    for key, model in models:
+        prefill_decode(model, toks_d[:4], lens_d[:4], 4, cos_d, sin_d)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        gen, _ = prefill_decode(model, toks_d, lens_d, 128, cos_d, sin_d)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        out["job_64_prompts" + key[len("model_8_layer_step"):]] = {
+            "prompts": 64, "prompt_tokens": int(lens.sum()), "new_tokens": 64 * 128, "seconds": round(dt, 4),
+            "generated_tokens_per_s": round(64 * 128 / dt, 1)}
     return out
 
 
