@@ -56,7 +56,7 @@ __global__ __launch_bounds__(256) void attn_chunk_kernel(const uint16_t* __restr
 {
     __shared__ float sc[G][kChunk];       // scores, then e_j
     __shared__ float po[4][G][kD];        // per-wave partial outputs
-    __shared__ float scratch[4];
+    __shared__ float scratch[G][4];
     __shared__ uint4 vbuf[VLDS ? 4 : 1][VLDS ? 16 : 1][64];  // the chunk's V rows: wave, block of 4 tokens, lane
 
     const int c = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
@@ -122,14 +122,48 @@ __global__ __launch_bounds__(256) void attn_chunk_kernel(const uint16_t* __restr
 
     const bool valid = t0 + tid < len;
     const size_t part = ((size_t)b * Hq + (size_t)kvh * G) * ncmax + c;  // + h*ncmax
+    // chunk_stats for the G heads at once: the heads' reductions are independent of each other, so they
+    // share the barriers (4 instead of 4G); per head the operations and their order are chunk_stats'.
+    {
+        float sv[G], red[G];
 #pragma unroll
-    for (int h = 0; h < G; ++h) {
-        float m_c, e, l_c;
-        chunk_stats(sc[h][tid], valid, scratch, m_c, e, l_c);
-        sc[h][tid] = e;  // only this thread reads or writes slot tid until the barrier below
-        if (tid == 0) {
-            ws_m[part + (size_t)h * ncmax] = m_c;
-            ws_l[part + (size_t)h * ncmax] = l_c;
+        for (int h = 0; h < G; ++h) {
+            sv[h] = valid ? sc[h][tid] : -INFINITY;
+            red[h] = sv[h];
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1)
+#pragma unroll
+            for (int h = 0; h < G; ++h) red[h] = fmaxf(red[h], __shfl_xor(red[h], off, kWave));
+        if (lane == 0)
+#pragma unroll
+            for (int h = 0; h < G; ++h) scratch[h][wave] = red[h];
+        __syncthreads();
+        float m_c[G], e[G];
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            m_c[h] = fmaxf(fmaxf(scratch[h][0], scratch[h][1]), fmaxf(scratch[h][2], scratch[h][3]));
+            e[h] = valid ? det_expf(sv[h] - m_c[h]) : 0.0f;
+            red[h] = e[h];
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1)
+#pragma unroll
+            for (int h = 0; h < G; ++h) red[h] = red[h] + __shfl_down(red[h], off, kWave);
+        __syncthreads();  // the maxima in scratch have been read
+        if (lane == 0)
+#pragma unroll
+            for (int h = 0; h < G; ++h) scratch[h][wave] = red[h];
+        __syncthreads();
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            sc[h][tid] = e[h];  // only this thread reads or writes slot tid until the barrier below
+            if (tid == 0) {
+                const float qa = scratch[h][0] + scratch[h][2];
+                const float qb = scratch[h][1] + scratch[h][3];
+                ws_m[part + (size_t)h * ncmax] = m_c[h];
+                ws_l[part + (size_t)h * ncmax] = qa + qb;
+            }
         }
     }
     __syncthreads();
