@@ -542,17 +542,15 @@ static int gemm_dispatch(const void* A, int lda, const void* Bp, void* C, int ld
 {
     const int cb = gemm_cols_per_block(N);
     const bool small = gemm_small_ring(N);
-    // Tall launches of narrow matrices.  A workgroup reads every row of its tile of A and every column
-    // of its tile of the weights once, and what bounds a tall tile is the bytes through the compute
-    // unit's memory pipe, so a 256-row x 16- or 32-column tile (all of A for a sliver of the weights) is
-    // the wrong shape from about a hundred rows on: 64-column tiles of M/row_tiles rows, with row_tiles
-    // chosen so that the grid still fits the chip in one round, move up to half as many bytes per
-    // compute unit (measured: K = 14336, N = 4096 at M = 256 in 63 us instead of 112).  The weights stay
-    // packed as they are (the workgroup streams 4/cb adjacent slabs).  The arithmetic of an output
-    // element is the same chain of matrix-core steps in either tiling, so its bytes do not depend on
-    // which ran; the thresholds are where the measured times cross.
-    // Launches with enough rows that 128-column tiles of 256 rows still give every compute unit a workgroup
-    // (prefill): the widest tile moves the fewest bytes per flop through the memory pipe, whatever the packing.
+    // What bounds a launch with many rows is the bytes each workgroup pulls through its compute unit's
+    // memory pipe: every row of its tile of A and every column of its tile of the weights, once per K.
+    // The tiling below picks, per (M, N), the tile shape that keeps that sum small while every compute
+    // unit still gets a workgroup.  The packing is untouched (a workgroup streams as many adjacent slabs
+    // as its tile is wide), and so is the arithmetic of an output element: the same chain of matrix-core
+    // steps over ascending K in every instantiation, so its bytes do not depend on which ran.
+    //
+    // (1) Launches with enough rows that 128-column tiles of 256 rows still fill the chip (prefill): the
+    //     widest tile moves the fewest bytes per flop, whatever the packing.
     if (!small && cb < 8 && 8 % cb == 0 && N % 128 == 0 && (long long)((M + 255) / 256) * (N / 128) >= 256) {
         if (cb == 1)
             launch_gemm<8, kRingBig, EPI, 8, 4, 1>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s);
@@ -562,11 +560,35 @@ static int gemm_dispatch(const void* A, int lda, const void* Bp, void* C, int ld
             launch_gemm<8, kRingBig, EPI, 8, 4, 4>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s);
         return check_launch();
     }
-    if (!small && N % 64 == 0 && ((cb == 1 && M >= 96) || (cb == 2 && M >= 192))) {
-        const int row_tiles = 256 / (N / 64) > 0 ? 256 / (N / 64) : 1;
-        // a tile holds at most 256 rows (16 row blocks); longer launches take several rounds of those
-        const int even = 16 * (((M + 15) / 16 + row_tiles - 1) / row_tiles);
-        const int rows = even < 256 ? even : 256;
+    // (2) Matrices too narrow to give every compute unit a column tile (N / (16 cb) < 256): the rows are
+    //     cut into as many tiles as fill the chip, which also shortens each workgroup's pass over A.
+    const int row_blocks = (M + 15) / 16;
+    int base_rows = 256;
+    {
+        const int fit = 256 / (N / (16 * cb));
+        if (!small && fit >= 2 && row_blocks >= 2) {
+            const int row_tiles = row_blocks < fit ? row_blocks : fit;
+            const int rows = 16 * ((row_blocks + row_tiles - 1) / row_tiles);
+            base_rows = rows < 256 ? rows : 256;
+        }
+    }
+    // (3) Tall launches of 16- or 32-column packings: a 256-row x 16-column tile (all of A for a sliver of
+    //     the weights) is the wrong shape from about a hundred rows on; 64-column tiles of M/row_tiles rows
+    //     move up to half as many bytes (measured: K = 14336, N = 4096 at M = 256 in 63 us instead of 112).
+    //     Taken from the row counts where the measured times cross, and only where the 64-column tiles
+    //     move clearly fewer bytes per compute unit than the tiles of (2).
+    const int sq_row_tiles = N % 64 == 0 && 256 / (N / 64) > 0 ? 256 / (N / 64) : 1;
+    const int sq_even = 16 * ((row_blocks + sq_row_tiles - 1) / sq_row_tiles);
+    const int sq_rows = sq_even < 256 ? sq_even : 256;  // a tile holds at most 16 row blocks
+    const int base_live = base_rows < 16 * row_blocks ? base_rows : 16 * row_blocks;
+    // bytes per compute unit ~ (rows + columns of a tile) x rounds of 256 workgroups
+    auto rounds = [](long long wgs) { return (wgs + 255) / 256; };
+    const long long sq_cost = (long long)(sq_rows + 64) * rounds((long long)(N / 64) * ((M + sq_rows - 1) / sq_rows));
+    const long long base_cost =
+        (long long)(base_live + 16 * cb) * rounds((long long)(N / (16 * cb)) * ((M + base_rows - 1) / base_rows));
+    const bool sq_pays = 115 * sq_cost <= 100 * base_cost;
+    if (!small && N % 64 == 0 && sq_pays && ((cb == 1 && M >= 96) || (cb == 2 && M >= 192))) {
+        const int rows = sq_rows;
         if (cb == 1)
             launch_gemm<4, kRingBig, EPI, 8, 4, 1>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s, rows);
         else
@@ -581,7 +603,7 @@ static int gemm_dispatch(const void* A, int lda, const void* Bp, void* C, int ld
                 break;                                                                                      \
             }                                                                                               \
         }                                                                                                   \
-        launch_gemm<CBV, kRingBig, EPI, gemm_waves(CBV), gemm_loader_waves(CBV, false)>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s);                       \
+        launch_gemm<CBV, kRingBig, EPI, gemm_waves(CBV), gemm_loader_waves(CBV, false)>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s, base_rows);            \
         break;
     switch (cb) {
         DET_GEMM_CASE(1)
@@ -592,7 +614,7 @@ static int gemm_dispatch(const void* A, int lda, const void* Bp, void* C, int ld
         DET_GEMM_CASE(6)
         DET_GEMM_CASE(7)
         default:
-            launch_gemm<8, kRingBig, EPI, gemm_waves(8), gemm_loader_waves(8, false)>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s);
+            launch_gemm<8, kRingBig, EPI, gemm_waves(8), gemm_loader_waves(8, false)>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s, base_rows);
             break;
     }
 #undef DET_GEMM_CASE
