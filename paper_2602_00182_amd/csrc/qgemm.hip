@@ -219,7 +219,7 @@ __global__ __launch_bounds__(64 * (kQWaves + kQLoaders)) void qgemm_kernel(
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 4, lr = lane & 15;
-    const int m0 = blockIdx.y * 256;
+    const int m0 = blockIdx.y * plan_full.mrem;  // full tiles hold plan_full.mrem rows (256 unless the rows are cut, see launch_qgemm)
     const qgemm_plan& tp = blockIdx.y + 1 == gridDim.y ? plan_tail : plan_full;
     const int mrem = tp.mrem, RB = tp.RB, SPC = tp.SPC, nslots = tp.nslots, nchunks = tp.nchunks;
     const int P = nslots - 1;
@@ -632,9 +632,19 @@ template <int CB, int EPI>
 static void launch_qgemm(const void* qa, const void* da, int ldd, const void* wp, void* C, int ldc, const void* R, int ldr,
                          int M, int N, int K, int out_f32, hipStream_t s, float* qscales_out = nullptr)
 {
-    dim3 grid(N / (16 * CB), (M + 255) / 256);
-    const qgemm_plan full = make_qgemm_plan(256, CB, K);
-    const qgemm_plan tail = make_qgemm_plan(M - 256 * ((M - 1) / 256), CB, K);
+    // Matrices too narrow to give every compute unit a column tile: the rows are cut into as many tiles as
+    // fill the chip (a tile's rows are whole 16-row blocks; which tile a row falls in does not touch its
+    // arithmetic).
+    int tile_rows = 256;
+    const int col_tiles = N / (16 * CB), row_blocks = (M + 15) / 16, fit = 256 / col_tiles;
+    if (fit >= 2 && row_blocks >= 2) {
+        const int row_tiles = row_blocks < fit ? row_blocks : fit;
+        const int rows = 16 * ((row_blocks + row_tiles - 1) / row_tiles);
+        tile_rows = rows < 256 ? rows : 256;
+    }
+    dim3 grid(N / (16 * CB), (M + tile_rows - 1) / tile_rows);
+    const qgemm_plan full = make_qgemm_plan(tile_rows, CB, K);
+    const qgemm_plan tail = make_qgemm_plan(M - tile_rows * ((M - 1) / tile_rows), CB, K);
     hipLaunchKernelGGL((qgemm_kernel<CB, EPI>), grid, dim3(64 * (kQWaves + kQLoaders)), 0, s,
                        static_cast<const int8_t*>(qa), K, static_cast<const float*>(da), ldd, static_cast<const uint8_t*>(wp),
                        C, ldc, static_cast<const uint16_t*>(R), ldr, out_f32, full, tail, qscales_out);

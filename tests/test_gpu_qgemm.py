@@ -62,6 +62,7 @@ def test_activation_quantizer_matches_oracle(d, orc, M, K):
     (256, 4096, 4096), (256, 1024, 28672), (300, 512, 2048), (7, 14336, 256), (128, 2048, 32000),
     (257, 256, 4096), (260, 512, 6144), (8, 4096, 6144), (4, 2048, 3072), (2, 14336, 4096),
     (8, 128, 32), (5, 192, 6144), (3, 64, 4096), (9, 2048, 4096), (16, 14336, 4096), (48, 1024, 6144),
+    (64, 5632, 2048), (40, 512, 1024), (130, 256, 2048), (33, 2048, 3072),
 ])
 def test_qgemm_bytes_match_oracle(d, orc, M, K, N):
     a = ds.normal_bf16(ds.tensor_seed(6, 30) + M, (M, K), 1.0, 0.0)
