@@ -527,10 +527,12 @@ def decode_numbers(torch, det, ds, dev):
     for key, model in models:
         prefill_decode(model, toks_d[:4], lens_d[:4], 4, cos_d, sin_d)
         torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        gen, _ = prefill_decode(model, toks_d, lens_d, 128, cos_d, sin_d)
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
+        dt = float("inf")
+        for _ in range(2):   # the better of two runs: the job is short enough for host jitter to show
+            t0 = time.perf_counter()
+            gen, _ = prefill_decode(model, toks_d, lens_d, 128, cos_d, sin_d)
+            torch.cuda.synchronize()
+            dt = min(dt, time.perf_counter() - t0)
         out["job_64_prompts" + key[len("model_8_layer_step"):]] = {
             "prompts": 64, "prompt_tokens": int(lens.sum()), "new_tokens": 64 * 128, "seconds": round(dt, 4),
             "generated_tokens_per_s": round(64 * 128 / dt, 1)}

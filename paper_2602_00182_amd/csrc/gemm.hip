@@ -46,13 +46,15 @@ namespace det {
 
 
 // Columns-per-workgroup factor: the largest CB in 1..8 that divides N/16 and still leaves at least
-// 192 workgroups across N (three quarters of the 256 compute units); 1 if there is none.
+// 160 workgroups across N; 1 if there is none.  160 compute units pulling weights keep HBM busy, and
+// anything between 257 and 383 narrower tiles would run as a full round of workgroups plus a thin one
+// (N = 11264: 176 tiles of 64 columns take 11.1 us at M = 1, 352 tiles of 32 columns 14.8 us).
 int gemm_cols_per_block(int N)
 {
     const int nb = N / 16;
     int best = 1;
     for (int cb = 1; cb <= 8; ++cb)
-        if (nb % cb == 0 && nb / cb >= 192) best = cb;
+        if (nb % cb == 0 && nb / cb >= 160) best = cb;
     return best;
 }
 

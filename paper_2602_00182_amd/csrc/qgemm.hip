@@ -32,13 +32,13 @@ constexpr int kQRing = 144;   // KB of LDS ring
 constexpr int kQWaves = 8;    // waves that can compute
 constexpr int kQLoaders = 4;  // waves that only load
 
-// Columns-per-workgroup factor: the largest of 8, 4, 2, 1 that divides N/16 and leaves at least 192
-// workgroups; 1 if there is none.
+// Columns-per-workgroup factor: the largest of 8, 4, 2, 1 that divides N/16 and leaves at least 160
+// workgroups (see gemm_cols_per_block); 1 if there is none.
 int qgemm_cols_per_block(int N)
 {
     const int nb = N / 16;
     for (int cb = 8; cb > 1; cb >>= 1)
-        if (nb % cb == 0 && nb / cb >= 192) return cb;
+        if (nb % cb == 0 && nb / cb >= 160) return cb;
     return 1;
 }
 
