@@ -6,10 +6,11 @@
 // Shape of the kernel
 //   * A workgroup owns BN = 16*CB output columns and up to 256 rows; grid.x = N/BN, grid.y =
 //     ceil(M/256).  It has NW (4 or 8) wavefronts that can compute plus NL (2 or 4) that only load.
-//     CB, the LDS ring size and the wave counts are functions of N alone.  Tall launches of narrow
-//     matrices (16- or 32-column tiles, from 96 or 192 rows on) use 64-column tiles of fewer rows
-//     instead, see gemm_dispatch.  The tiling decides which workgroup and wave computes an element,
-//     never the element's arithmetic, so its bytes are the same whichever ran.
+//     The packing (CB), the matrix-core shape and the K order are functions of N alone.  The tile a
+//     launch cuts C into also looks at M (gemm_dispatch: narrow matrices cut their rows so that every
+//     compute unit gets a workgroup, tall launches of narrow packings take 64- or 128-column tiles
+//     over several slabs).  The tiling decides which workgroup and wave computes an element, never
+//     the element's arithmetic, so its bytes are the same whichever ran.
 //   * K is cut into 64-deep stages.  Operands travel as 1 KB blocks.  A weight block is already in
 //     the operand order of v_mfma_f32_16x16x32_bf16 (lane l holds 8 consecutive k of column l%16, k
 //     group l/16); an activation block is 8 rows x 64 k as they lie in A (whole 128-byte lines),
@@ -537,7 +538,7 @@ static void launch_gemm(const void* A, int lda, const void* Bp, void* C, int ldc
                        static_cast<const uint16_t*>(R), ldr, K, out_f32, full, tail);
 }
 
-// Picks the kernel configuration from N alone and launches it.
+// Picks the kernel configuration (packing from N, tiling from N and M) and launches it.
 template <int EPI>
 static int gemm_dispatch(const void* A, int lda, const void* Bp, void* C, int ldc, const void* R, int ldr, int M,
                          int N, int K, int f32, hipStream_t s)
