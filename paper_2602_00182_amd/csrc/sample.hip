@@ -11,7 +11,9 @@
 // The order is total (index breaks ties), so the k kept candidates and their ranks are unique and any
 // selection / sorting network gives them: here an 8-bit radix select on the 64-bit key
 // (order-preserving image of z, then ~index) with integer LDS histograms, and a bitonic sort of the
-// k survivors.  Every floating-point step is done by one thread in rank order.
+// k survivors.  The prefix sums are one thread's adds in rank order.  sample_kernel reads the row once
+// per radix pass and serves any V; sample_kernel_reg (rows of at most 65536 logits) keeps the keys in
+// registers.
 #include <math.h>
 
 #include "common.h"
@@ -150,6 +152,182 @@ __global__ __launch_bounds__(256) void sample_kernel(const float* __restrict__ l
     }
 }
 
+// The same selection for rows of at most 1024*KPT logits, with the row read once: 1024 threads, each
+// keeps the z keys of its KPT candidates (j = tid + 1024 i) in registers, so the radix passes, the
+// gather and the division by the temperature touch no memory but the LDS histogram.  The sort and the
+// exponentials use all threads; the prefix sums stay one thread's sequential adds in rank order (their
+// order is part of the definition), the two searches over them are minimum reductions (the first
+// index that satisfies a condition does not depend on how it is found).
+constexpr int kSampleThreads = 1024;
+template <int KPT>
+__global__ __launch_bounds__(kSampleThreads) void sample_kernel_reg(const float* __restrict__ logits, int V,
+                                                                    float temperature, int top_k, float top_p,
+                                                                    uint64_t seed, const int32_t* __restrict__ seq_ids,
+                                                                    const int32_t* __restrict__ steps,
+                                                                    int32_t* __restrict__ tokens)
+{
+    constexpr int T = kSampleThreads;
+    __shared__ uint32_t hist[256];
+    __shared__ uint64_t sel[kMaxTopK];
+    __shared__ float ebuf[kMaxTopK];
+    __shared__ int s_digit, s_need, s_bin, s_count, s_n, s_pick;
+    __shared__ float s_cut, s_target;
+    __shared__ uint32_t s_tmp[256], wave_tot[4];
+
+    const int tid = threadIdx.x;
+    const float* row = logits + (size_t)blockIdx.x * V;
+    const int k = top_k < V ? top_k : V;
+
+    uint32_t zk[KPT];  // high half of candidate_key; the low half is 0xFFFFFFFF - j
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) {
+        const int j = tid + T * i;
+        zk[i] = j < V ? (uint32_t)(candidate_key(row[j], temperature, j) >> 32) : 0u;
+    }
+    auto key_of = [&](int i) { return ((uint64_t)zk[i] << 32) | (uint64_t)(0xFFFFFFFFu - (uint32_t)(tid + T * i)); };
+
+    // ---- radix select, as in sample_kernel
+    uint64_t prefix = 0;
+    int need = k;
+    int shift = 56;
+    bool all_of_bin = false;
+    for (int pass = 0; pass < 8; ++pass, shift -= 8) {
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < KPT; ++i) {
+            const bool in = tid + T * i < V;
+            const uint64_t key = key_of(i);
+            const uint32_t digit = (uint32_t)(key >> shift) & 255u;
+            if (in && (pass == 0 || (key >> (shift + 8)) == prefix)) {
+                atomicAdd(&hist[digit], 1u);
+            }
+        }
+        __syncthreads();
+        if (tid < 256) {
+            // above = keys with the prefix and a larger digit than tid: suffix sums inside each wave (its 64
+            // bins), then the totals of the higher waves
+            const uint32_t mine = hist[tid];
+            uint32_t incl = mine;
+            const int l = tid & (kWave - 1);
+#pragma unroll
+            for (int off = 1; off < kWave; off <<= 1) {
+                const uint32_t other = (uint32_t)__shfl_down((int)incl, off, kWave);
+                if (l + off < kWave) incl += other;
+            }
+            if (l == 0) wave_tot[tid >> 6] = incl;  // the wave's 64 bins
+            s_tmp[tid] = incl - mine;               // larger digits inside the wave
+        }
+        __syncthreads();
+        if (tid < 256) {
+            uint32_t above = s_tmp[tid];
+            for (int w = (tid >> 6) + 1; w < 4; ++w) above += wave_tot[w];
+            const uint32_t mine = hist[tid];
+            if ((int)above < need && need <= (int)(above + mine)) {
+                s_digit = tid;
+                s_need = need - (int)above;
+                s_bin = (int)mine;
+            }
+        }
+        __syncthreads();
+        prefix = (prefix << 8) | (uint64_t)s_digit;
+        need = s_need;
+        all_of_bin = s_bin == need;
+        __syncthreads();
+        if (all_of_bin) break;
+    }
+    const uint64_t threshold = all_of_bin ? (prefix << shift) : prefix;
+
+    // ---- gather the k survivors (any order), pad to a power of two, sort descending
+    if (tid == 0) s_count = 0;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) {
+        if (tid + T * i < V) {
+            const uint64_t key = key_of(i);
+            if (key >= threshold) sel[atomicAdd(&s_count, 1)] = key;
+        }
+    }
+    int kp = 1;
+    while (kp < k) kp <<= 1;
+    __syncthreads();
+    for (int i = k + tid; i < kp; i += T) sel[i] = 0;  // below every real key
+    __syncthreads();
+    for (int size = 2; size <= kp; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int i = tid; i < (kp >> 1); i += T) {
+                const int lo = 2 * i - (i & (stride - 1));
+                const int hi = lo + stride;
+                const bool desc = (lo & size) == 0;
+                const uint64_t a = sel[lo], b = sel[hi];
+                if ((a < b) == desc) {
+                    sel[lo] = b;
+                    sel[hi] = a;
+                }
+            }
+            __syncthreads();
+        }
+    }
+
+    // ---- probabilities in rank order
+    const float z0 = order_key_inv((uint32_t)(sel[0] >> 32));
+    for (int i = tid; i < k; i += T) ebuf[i] = det_expf(order_key_inv((uint32_t)(sel[i] >> 32)) - z0);
+    __syncthreads();
+    if (tid == 0) {
+        float acc = 0.0f;
+        int i = 0;
+        for (; i + 8 <= k; i += 8) {  // eight reads in flight, then their adds in order
+            float e[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) e[u] = ebuf[i + u];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                acc = acc + e[u];
+                e[u] = acc;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) ebuf[i + u] = e[u];  // c_i
+        }
+        for (; i < k; ++i) {
+            acc = acc + ebuf[i];
+            ebuf[i] = acc;
+        }
+        s_cut = top_p * ebuf[k - 1];
+        s_n = k;
+    }
+    __syncthreads();
+    {   // n = 1 + the first i with c_i >= cut (k if rounding leaves none)
+        const float cut = s_cut;
+        int best = k;
+        for (int i = tid; i < k; i += T)
+            if (ebuf[i] >= cut) {
+                best = i + 1;
+                break;
+            }
+        if (best < k) atomicMin(&s_n, best);
+    }
+    __syncthreads();
+    const int n = s_n;
+    if (tid == 0) {
+        const uint64_t ctr = ((uint64_t)(uint32_t)seq_ids[blockIdx.x] << 32) | (uint64_t)(uint32_t)steps[blockIdx.x];
+        const uint64_t r = splitmix64_mix(seed + (ctr + 1) * 0x9E3779B97F4A7C15ull);
+        const float u = (float)(uint32_t)(r >> 40) * 0x1p-24f;
+        s_target = u * ebuf[n - 1];
+        s_pick = n - 1;
+    }
+    __syncthreads();
+    {   // the first i < n with c_i > target (n-1 if rounding leaves none)
+        const float target = s_target;
+        for (int i = tid; i < n; i += T)
+            if (ebuf[i] > target) {
+                atomicMin(&s_pick, i);
+                break;
+            }
+    }
+    __syncthreads();
+    if (tid == 0) tokens[blockIdx.x] = (int32_t)(0xFFFFFFFFu - (uint32_t)sel[s_pick]);
+}
+
 }  // namespace det
 
 using namespace det;
@@ -161,7 +339,15 @@ extern "C" int det_sample(const float* logits, int B, int V, float temperature, 
     if (!logits || !seq_ids || !steps || !tokens || B < 1 || V < 1) return DET_EINVAL;
     if (!(temperature > 0.0f) || !(top_p > 0.0f) || !(top_p <= 1.0f)) return DET_EINVAL;
     if (top_k < 1 || top_k > kMaxTopK) return DET_ESHAPE;
-    hipLaunchKernelGGL(sample_kernel, dim3(B), dim3(256), 0, static_cast<hipStream_t>(stream), logits, V,
-                       temperature, top_k, top_p, seed, seq_ids, steps, tokens);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (V <= kSampleThreads * 32)
+        hipLaunchKernelGGL(sample_kernel_reg<32>, dim3(B), dim3(kSampleThreads), 0, s, logits, V, temperature, top_k, top_p,
+                           seed, seq_ids, steps, tokens);
+    else if (V <= kSampleThreads * 64)
+        hipLaunchKernelGGL(sample_kernel_reg<64>, dim3(B), dim3(kSampleThreads), 0, s, logits, V, temperature, top_k, top_p,
+                           seed, seq_ids, steps, tokens);
+    else
+        hipLaunchKernelGGL(sample_kernel, dim3(B), dim3(256), 0, s, logits, V, temperature, top_k, top_p, seed, seq_ids,
+                           steps, tokens);
     return check_launch();
 }
