@@ -222,7 +222,41 @@ def main():
         result["decode"] = decode_numbers(torch, det, ds, dev)
         result["qgemm_w4a8"] = qgemm_numbers(torch, det, ds, dev)
         result["library_gemm"] = library_gemm(torch, ds, dev, sweep_cold)
+        result["token_selection"] = selection_numbers(torch, det, ds, dev)
     print(json.dumps(result))
+
+
+def selection_numbers(torch, det, ds, dev):
+    """det_argmax and det_sample (seeded temperature / top-k / top-p) on V = 32000 fp32 logits, GPU time per
+    call from marshalled calls."""
+    from paper_2602_00182_amd._lib import lib as _det_lib
+    L = _det_lib()
+    V = 32000
+    stream = torch.cuda.current_stream().cuda_stream
+    rows = []
+    for B in (1, 64):
+        logits = ds.normal_bf16_torch(ds.tensor_seed(5, 700), (B, V), 3.0, 0.0, dev).float().contiguous()
+        out = torch.empty(B, dtype=torch.int32, device=dev)
+        ids = torch.arange(B, dtype=torch.int32, device=dev)
+        steps = torch.zeros(B, dtype=torch.int32, device=dev)
+        cases = [("argmax", lambda: L.det_argmax(logits.data_ptr(), out.data_ptr(), B, V, 1, stream))]
+        for (T, k, p) in ((1.0, 50, 0.9), (0.7, 1024, 1.0)):
+            cases.append((f"sample T={T} top_k={k} top_p={p}",
+                          lambda T=T, k=k, p=p: L.det_sample(logits.data_ptr(), B, V, T, k, p, 1234, ids.data_ptr(),
+                                                             steps.data_ptr(), out.data_ptr(), stream)))
+        for name, call in cases:
+            for _ in range(3):
+                if call() != 0:
+                    raise RuntimeError(name + " failed")
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(20):
+                call()
+            e1.record()
+            torch.cuda.synchronize()
+            rows.append({"B": B, "op": name, "us": round(e0.elapsed_time(e1) / 20 * 1e3, 1)})
+    return rows
 
 
 def library_gemm(torch, ds, dev, sweep_cold):
