@@ -327,3 +327,39 @@ def test_fused_swiglu_epilogue_equals_unfused_bytes(d, orc, M, K, F):
     assert torch.equal(fused.view(torch.int16), unfused.view(torch.int16))
     guh = down_bf16(gu)
     assert np.array_equal(down_bf16(fused), orc.swiglu(np.ascontiguousarray(guh[:, :F]), np.ascontiguousarray(guh[:, F:])))
+
+
+def test_seeded_shape_sweep_both_gemms(d, orc):
+    """Thirty seeded (M, N, K) drawn across every tiling rule (narrow and wide packings, row-cut, 64- and
+    128-column tiles, several row tiles, ragged M): a sample of each product within the fp64 bound, one
+    row equal to its M = 1 launch, and the quantized GEMM of the same operands equal to the oracle's."""
+    rng = np.random.default_rng(20260200182)
+    widths = [16, 48, 64, 128, 320, 1024, 1536, 2048, 2560, 3072, 4096, 5120, 6144, 7168, 9216, 11264, 12288, 16384]
+    heights = [1, 3, 8, 9, 16, 17, 40, 64, 95, 96, 130, 191, 192, 255, 256, 257, 300, 700, 1500, 4500]
+    for it in range(30):
+        N, K, M = int(rng.choice(widths)), 64 * int(rng.integers(1, 40)), int(rng.choice(heights))
+        if M * N * K > 2e10:
+            M = max(1, int(2e10 / (N * K)))
+        step(f"sweep gemm M={M} N={N} K={K}")
+        X = ds.normal_bf16(ds.tensor_seed(3, 100 + it), (M, K))
+        W = ds.normal_bf16(ds.tensor_seed(3, 200 + it), (K, N), 0.05)
+        Wp, Xd = d.pack_weight(up_bf16(W)), up_bf16(X)
+        C = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+        d.det_gemm_bf16(Xd, Wp, C, N, K)
+        r = int(rng.integers(0, M))
+        C1 = torch.empty((1, N), dtype=torch.bfloat16, device=DEV)
+        d.det_gemm_bf16(Xd[r:r + 1], Wp, C1, N, K)
+        torch.cuda.synchronize()
+        full = down_bf16(C)
+        assert np.array_equal(down_bf16(C1)[0], full[r]), (M, N, K, r)
+        rows = rng.integers(0, M, 512).astype(np.int32)
+        cols = rng.integers(0, N, 512).astype(np.int32)
+        ref, refabs = orc.gemm_f64_sample(X, W, rows, cols)
+        assert within_bound(bits_to_f64(full[rows, cols]), ref, refabs).all(), (M, N, K)
+        if M <= 600 and M * N * K < 3e9:
+            step(f"sweep qgemm M={M} N={N} K={K}")
+            codes, scales = d.quant_activations(Xd)
+            c = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+            d.det_qgemm_w4a8(codes, scales, d.quant_pack_weight(up_bf16(W)), c, N)
+            torch.cuda.synchronize()
+            assert np.array_equal(down_bf16(c), orc.qlinear(X, *orc.quant_w4(W))), (M, N, K)
