@@ -13,7 +13,7 @@
 // (order-preserving image of z, then ~index) with integer LDS histograms, and a bitonic sort of the
 // k survivors.  The prefix sums are one thread's adds in rank order.  sample_kernel reads the row once
 // per radix pass and serves any V; sample_kernel_reg (rows of at most 65536 logits) keeps the keys in
-// registers.
+// registers and takes wider digits.
 #include <math.h>
 
 #include "common.h"
@@ -167,12 +167,12 @@ __global__ __launch_bounds__(kSampleThreads) void sample_kernel_reg(const float*
                                                                     int32_t* __restrict__ tokens)
 {
     constexpr int T = kSampleThreads;
-    __shared__ uint32_t hist[256];
+    __shared__ uint32_t hist2[2][2 * kSampleThreads];  // the histogram of pass p is hist2[p & 1]; the other one is cleared meanwhile
     __shared__ uint64_t sel[kMaxTopK];
     __shared__ float ebuf[kMaxTopK];
     __shared__ int s_digit, s_need, s_bin, s_count, s_n, s_pick;
     __shared__ float s_cut, s_target;
-    __shared__ uint32_t s_tmp[256], wave_tot[4];
+    __shared__ uint32_t wave_tot[kSampleThreads / kWave];
 
     const int tid = threadIdx.x;
     const float* row = logits + (size_t)blockIdx.x * V;
@@ -186,56 +186,67 @@ __global__ __launch_bounds__(kSampleThreads) void sample_kernel_reg(const float*
     }
     auto key_of = [&](int i) { return ((uint64_t)zk[i] << 32) | (uint64_t)(0xFFFFFFFFu - (uint32_t)(tid + T * i)); };
 
-    // ---- radix select, as in sample_kernel
+    // ---- radix select as in sample_kernel, with digits of 11, 11, 10 bits for each half of the key: the
+    // top byte of a float (sign and seven exponent bits) takes a handful of values over a row of logits
+    // and the increments of a pass would queue up on those few counters; three more bits spread them.
+    // Thread t owns bins 2t and 2t+1 of the 2048.
     uint64_t prefix = 0;
     int need = k;
-    int shift = 56;
+    int shift = 64;
     bool all_of_bin = false;
-    for (int pass = 0; pass < 8; ++pass, shift -= 8) {
-        if (tid < 256) hist[tid] = 0;
-        __syncthreads();
+    hist2[0][2 * tid] = 0;
+    hist2[0][2 * tid + 1] = 0;
+    __syncthreads();
+    for (int pass = 0; pass < 6; ++pass) {
+        const int width = (pass % 3 == 2) ? 10 : 11;
+        shift -= width;
+        const uint32_t dmask = (1u << width) - 1u;
+        uint32_t* hist = hist2[pass & 1];
 #pragma unroll
         for (int i = 0; i < KPT; ++i) {
             const bool in = tid + T * i < V;
             const uint64_t key = key_of(i);
-            const uint32_t digit = (uint32_t)(key >> shift) & 255u;
-            if (in && (pass == 0 || (key >> (shift + 8)) == prefix)) {
-                atomicAdd(&hist[digit], 1u);
-            }
+            if (in && (pass == 0 || (key >> (shift + width)) == prefix)) atomicAdd(&hist[(uint32_t)(key >> shift) & dmask], 1u);
         }
         __syncthreads();
-        if (tid < 256) {
-            // above = keys with the prefix and a larger digit than tid: suffix sums inside each wave (its 64
-            // bins), then the totals of the higher waves
-            const uint32_t mine = hist[tid];
-            uint32_t incl = mine;
+        // above(b) = keys with the prefix and a larger digit than b: suffix sums of the threads' pair sums inside
+        // each wave, then the totals of the higher waves
+        const uint32_t h_lo = hist[2 * tid], h_hi = hist[2 * tid + 1];
+        uint32_t incl = h_lo + h_hi;
+        {
             const int l = tid & (kWave - 1);
 #pragma unroll
             for (int off = 1; off < kWave; off <<= 1) {
                 const uint32_t other = (uint32_t)__shfl_down((int)incl, off, kWave);
                 if (l + off < kWave) incl += other;
             }
-            if (l == 0) wave_tot[tid >> 6] = incl;  // the wave's 64 bins
-            s_tmp[tid] = incl - mine;               // larger digits inside the wave
+            if (l == 0) wave_tot[tid >> 6] = incl;
         }
+        hist2[(pass + 1) & 1][2 * tid] = 0;  // next pass's histogram
+        hist2[(pass + 1) & 1][2 * tid + 1] = 0;
         __syncthreads();
-        if (tid < 256) {
-            uint32_t above = s_tmp[tid];
-            for (int w = (tid >> 6) + 1; w < 4; ++w) above += wave_tot[w];
-            const uint32_t mine = hist[tid];
-            if ((int)above < need && need <= (int)(above + mine)) {
-                s_digit = tid;
-                s_need = need - (int)above;
-                s_bin = (int)mine;
+        {
+            uint32_t above_hi = incl - (h_lo + h_hi);  // pairs of higher threads of this wave
+            for (int w = (tid >> 6) + 1; w < T / kWave; ++w) above_hi += wave_tot[w];
+            const uint32_t above_lo = above_hi + h_hi;
+            if ((int)above_hi < need && need <= (int)(above_hi + h_hi)) {
+                s_digit = 2 * tid + 1;
+                s_need = need - (int)above_hi;
+                s_bin = (int)h_hi;
+            } else if ((int)above_lo < need && need <= (int)(above_lo + h_lo)) {
+                s_digit = 2 * tid;
+                s_need = need - (int)above_lo;
+                s_bin = (int)h_lo;
             }
         }
         __syncthreads();
-        prefix = (prefix << 8) | (uint64_t)s_digit;
+        // (s_digit, s_need, s_bin and wave_tot are next written a barrier or more into the next pass)
+        prefix = (prefix << width) | (uint64_t)s_digit;
         need = s_need;
-        all_of_bin = s_bin == need;
-        __syncthreads();
+        all_of_bin = s_bin == need;  // every key of this bin is wanted: no need to look at lower bits
         if (all_of_bin) break;
     }
+    // all 64 bits decided (shift == 0) or the rest left open
     const uint64_t threshold = all_of_bin ? (prefix << shift) : prefix;
 
     // ---- gather the k survivors (any order), pad to a power of two, sort descending
