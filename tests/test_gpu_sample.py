@@ -25,9 +25,10 @@ def run(d, x, T, k, p, seed, ids, steps):
 @pytest.mark.parametrize("V,T,k,p", [
     (32000, 1.0, 40, 0.95), (32000, 0.7, 1, 1.0), (32000, 1.3, 1024, 1.0), (32000, 0.05, 64, 0.5),
     (32000, 8.0, 500, 0.999), (1000, 1.0, 1024, 0.9), (7, 1.0, 5, 1.0), (1, 1.0, 3, 1.0), (257, 2.0, 256, 0.3),
+    (50000, 1.0, 100, 0.9), (65536, 0.9, 7, 1.0), (70000, 1.0, 30, 0.95), (131072, 1.1, 1024, 1.0),
 ])
 def test_sample_matches_oracle(d, orc, V, T, k, p):
-    B = 64
+    B = 64 if V <= 32000 else 6   # above 32768 / 65536 logits a row: the wider and the any-length kernels
     x = (ds.bf16_bits_to_f32(ds.normal_bf16(800 + V + k, (B, V))) * np.float32(2.5)).astype(np.float32)
     x += np.float32(1e-4) * np.arange(V, dtype=np.float32)[None, :] / max(V, 1)   # fp32, not only bf16 values
     ids = ds.uniform_int(801, (B,), 0, 2 ** 31 - 1)
