@@ -59,7 +59,11 @@ __global__ __launch_bounds__(256) void attn_chunk_kernel(const uint16_t* __restr
     __shared__ float scratch[G][4];
     __shared__ uint4 vbuf[VLDS ? 4 : 1][VLDS ? 16 : 1][64];  // the chunk's V rows: wave, block of 4 tokens, lane
 
-    const int c = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+    // blockIdx.y names a group of G consecutive query heads; its KV head is the one those heads share.  A
+    // launch with G = heads per KV head has one group per KV head; a launch with G = 1 on a model with
+    // more gives every query head a workgroup of its own (same arithmetic per head, more workgroups).
+    const int c = blockIdx.x, hgrp = blockIdx.y, b = blockIdx.z;
+    const int kvh = (hgrp * G) / (Hq / Hkv);
     int len = seqlens[b] + len_offset;
     len = len > Lmax ? Lmax : len;
     const int t0 = c * kChunk;
@@ -91,7 +95,7 @@ __global__ __launch_bounds__(256) void attn_chunk_kernel(const uint16_t* __restr
 #pragma unroll
     for (int i = 0; i < 4; ++i) qf[i] = make_uint4(0, 0, 0, 0);
     if (lr < G) {
-        const uint4* qp = reinterpret_cast<const uint4*>(q + ((size_t)b * Hq + (size_t)kvh * G + lr) * kD + 32 * g);
+        const uint4* qp = reinterpret_cast<const uint4*>(q + ((size_t)b * Hq + (size_t)hgrp * G + lr) * kD + 32 * g);
 #pragma unroll
         for (int i = 0; i < 4; ++i) qf[i] = qp[i];
     }
@@ -121,7 +125,7 @@ __global__ __launch_bounds__(256) void attn_chunk_kernel(const uint16_t* __restr
     __syncthreads();
 
     const bool valid = t0 + tid < len;
-    const size_t part = ((size_t)b * Hq + (size_t)kvh * G) * ncmax + c;  // + h*ncmax
+    const size_t part = ((size_t)b * Hq + (size_t)hgrp * G) * ncmax + c;  // + h*ncmax
     // chunk_stats for the G heads at once: the heads' reductions are independent of each other, so they
     // share the barriers (4 instead of 4G); per head the operations and their order are chunk_stats'.
     {
@@ -403,13 +407,16 @@ int det::attn_decode_impl(const void* q, const void* kcache, const void* vcache,
     float* ws_m = static_cast<float*>(ws);
     float* ws_l = ws_m + n;
     float* ws_o = ws_l + n;
-    const dim3 grid(ncmax, Hkv, B);
+    // Launches of a few dozen workgroups (one sequence, short context) are all latency: every query head
+    // then gets a workgroup of its own, which divides the statistics and the PV fold of a workgroup by G.
+    const bool split_heads = G > 1 && (size_t)ncmax * Hkv * B <= 128;
+    const dim3 grid(ncmax, split_heads ? Hq : Hkv, B);
     const uint16_t* qq = static_cast<const uint16_t*>(q);
     const uint16_t* kk = static_cast<const uint16_t*>(kcache);
     const uint16_t* vv = static_cast<const uint16_t*>(vcache);
     // Which of the two data paths for V is a matter of time only: the arithmetic and its order are the
     // same, so a row's bytes do not depend on it.  At most two workgroups per compute unit: latency bound.
-    const bool vlds = (size_t)ncmax * Hkv * B <= 512;
+    const bool vlds = (size_t)grid.x * grid.y * grid.z <= 512;
 #define DET_LAUNCH_ATTN(GG)                                                                                      \
     do {                                                                                                         \
         if (vlds)                                                                                                \
@@ -419,7 +426,7 @@ int det::attn_decode_impl(const void* q, const void* kcache, const void* vcache,
             hipLaunchKernelGGL((attn_chunk_kernel<GG, false>), grid, dim3(256), 0, s, qq, kk, vv, seqlens, slots,\
                                ws_m, ws_l, ws_o, Hq, Hkv, Lmax, ncmax, scale, len_offset);                      \
     } while (0)
-    switch (G) {
+    switch (split_heads ? 1 : G) {
         case 1: DET_LAUNCH_ATTN(1); break;
         case 2: DET_LAUNCH_ATTN(2); break;
         case 4: DET_LAUNCH_ATTN(4); break;
