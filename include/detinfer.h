@@ -133,6 +133,22 @@ int det_attn_decode_rows(const void *q, const void *kcache, const void *vcache, 
                          const int32_t *slots, void *out, void *ws, size_t ws_bytes, int R, int Hq,
                          int Hkv, int D, int Lmax, float scale, void *stream);
 
+/* det_attn_decode for callers that cannot provide or allocate a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid allocation): the chunk partials live in a fixed array of
+ * DET_ATTN_STATIC_WS_BYTES inside the library's code object, one copy per device, held until the
+ * process ends.  The call allocates nothing (no hipMalloc / hipFree, no allocating library routine); its
+ * first call on a device looks up that device's copy of the array (hipGetSymbolAddress), so the device
+ * `stream` belongs to must be the current device.  Output bytes are those of det_attn_decode.
+ *   Limit: det_attn_decode_workspace_bytes(B, Hq, D, Lmax) <= DET_ATTN_STATIC_WS_BYTES, i.e.
+ *   B * Hq * ceil(Lmax/256) <= 64527; DET_EWORKSPACE beyond it (nothing is launched).
+ *   All calls on one device share the array, which keeps the previous call's partials; nothing in it
+ *   needs clearing (each call overwrites what it later reads), but two calls that overlap in time on
+ *   one device (different streams) race on it: serialise them.
+ *   Other arguments and errors as det_attn_decode. */
+#define DET_ATTN_STATIC_WS_BYTES (32u << 20)
+int det_attn_decode_static(const void *q, const void *kcache, const void *vcache, const int32_t *seqlens,
+                           void *out, int B, int Hq, int Hkv, int D, int Lmax, float scale, void *stream);
+
 /* Test hook: the softmax statistics of det_attn_decode on caller-provided fp32 scores, computed by
  * the same device code.  s, p [R, Lmax] fp32; lens [R]; m_out, l_out [R] fp32.
  * p_j = (w_c * e_j) / L for j < lens[r]; entries at or past lens[r] are not written.

@@ -37,6 +37,7 @@ SIGNATURES = {
     "det_rmsnorm": (_i, [_vp, _vp, _vp, _i, _i, _f, _vp]),
     "det_attn_decode_workspace_bytes": (_sz, [_i, _i, _i, _i]),
     "det_attn_decode": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _sz, _i, _i, _i, _i, _i, _f, _vp]),
+    "det_attn_decode_static": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _vp]),
     "det_attn_decode_rows": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _i, _i, _i, _i, _i, _f, _vp]),
     "det_softmax_f32": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _vp]),
     "det_argmax": (_i, [_vp, _vp, _i, _i, _i, _vp]),

@@ -13,7 +13,7 @@ from ._lib import LayerCfg, LayerWeights, Sha256Ctx, lib
 __all__ = [
     "DetError", "det_gemm_bf16", "det_gemm_packed_b_bytes", "det_gemm_pack_b", "det_gemm_bf16_residual",
     "det_gemm_pack_gate_up", "det_gemm_swiglu_bf16", "pack_gate_up", "det_rmsnorm",
-    "det_attn_decode_workspace_bytes", "det_attn_decode", "det_attn_decode_rows", "det_decoder_layer_rows",
+    "det_attn_decode_workspace_bytes", "det_attn_decode", "det_attn_decode_static", "det_attn_decode_rows", "det_decoder_layer_rows",
     "det_softmax_f32", "det_argmax", "det_sample", "det_rope",
     "det_swiglu", "det_residual_add", "det_embed_gather", "det_decoder_layer_workspace_bytes",
     "det_decoder_layer", "det_next_token", "det_fingerprint", "det_last_hip_error", "layer_cfg",
@@ -360,6 +360,17 @@ def det_attn_decode(q, kcache, vcache, seqlens, out, ws, scale: float, stream=No
         _contig(q, torch.bfloat16), _contig(kcache, torch.bfloat16), _contig(vcache, torch.bfloat16),
         _contig(seqlens, torch.int32), _contig(out, torch.bfloat16), _contig(ws),
         ws.numel() * ws.element_size(), B, Hq, Hkv, D, Lmax, scale, _stream(stream)))
+
+
+def det_attn_decode_static(q, kcache, vcache, seqlens, out, scale: float, stream=None) -> None:
+    """det_attn_decode with the chunk partials in the library's fixed per-device array (allocates nothing)."""
+    B, Hq, D = q.shape
+    B2, Hkv, Lmax, D2 = kcache.shape
+    if (B2, D2) != (B, D) or vcache.shape != kcache.shape or out.shape != q.shape or seqlens.shape != (B,):
+        raise ValueError("bad attention shapes")
+    _check("det_attn_decode_static", lib().det_attn_decode_static(
+        _contig(q, torch.bfloat16), _contig(kcache, torch.bfloat16), _contig(vcache, torch.bfloat16),
+        _contig(seqlens, torch.int32), _contig(out, torch.bfloat16), B, Hq, Hkv, D, Lmax, scale, _stream(stream)))
 
 
 def det_attn_decode_rows(q, kcache, vcache, seqlens, slots, out, ws, scale: float, stream=None) -> None:

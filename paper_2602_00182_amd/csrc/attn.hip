@@ -5,6 +5,8 @@
 // arithmetic depends on nothing but that sequence's own cache rows and length.
 #include <math.h>
 
+#include <atomic>
+
 #include "internal.h"
 #include "stream.h"
 
@@ -379,6 +381,37 @@ static size_t attn_ws_floats(int B, int Hq, int Lmax)
     return (size_t)B * Hq * nc * (2 + kD);
 }
 
+// Chunk partials for det_attn_decode_static: a fixed array in the code object instead of a buffer the
+// caller brings.  Every device the library runs on holds its own copy at its own address; in host code
+// the name `scratch` is only a handle for hipGetSymbolAddress, never a pointer to pass to a kernel.
+static __device__ __align__(256) unsigned char scratch[DET_ATTN_STATIC_WS_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Address of the current device's copy of `scratch`, looked up on the first call on that device.
+static int static_scratch_ptr(void** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) {
+        set_last_hip_error((int)e);
+        return DET_EHIP;
+    }
+    if (dev < 0 || dev >= kMaxDevices) return DET_ESHAPE;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            set_last_hip_error((int)e);
+            return DET_EHIP;
+        }
+        g_scratch_ptr[dev].store(p, std::memory_order_release);  // two racing first calls store the same address
+    }
+    *out = p;
+    return DET_OK;
+}
+
 }  // namespace det
 
 using namespace det;
@@ -452,6 +485,19 @@ extern "C" int det_attn_decode(const void* q, const void* kcache, const void* vc
 {
     return attn_decode_impl(q, kcache, vcache, seqlens, nullptr, 0, out, ws, ws_bytes, B, Hq, Hkv, D, Lmax, scale,
                             static_cast<hipStream_t>(stream));
+}
+
+extern "C" int det_attn_decode_static(const void* q, const void* kcache, const void* vcache, const int32_t* seqlens,
+                                      void* out, int B, int Hq, int Hkv, int D, int Lmax, float scale, void* stream)
+{
+    const size_t need = det_attn_decode_workspace_bytes(B, Hq, D, Lmax);
+    if (need == 0) return (B < 1 || Hq < 1 || Lmax < 1) ? DET_EINVAL : DET_ESHAPE;
+    if (need > (size_t)DET_ATTN_STATIC_WS_BYTES) return DET_EWORKSPACE;
+    void* ws = nullptr;
+    const int rc = static_scratch_ptr(&ws);
+    if (rc != DET_OK) return rc;
+    return attn_decode_impl(q, kcache, vcache, seqlens, nullptr, 0, out, ws, DET_ATTN_STATIC_WS_BYTES, B, Hq, Hkv, D,
+                            Lmax, scale, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int det_attn_decode_rows(const void* q, const void* kcache, const void* vcache, const int32_t* seqlens,
