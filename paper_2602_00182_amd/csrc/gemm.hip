@@ -79,9 +79,18 @@ bool gemm_small_ring(int N)
 
 // LDS reads the compiler does not see.  Its own bookkeeping of the LDS counter waits for every read in
 // flight before the first use of any of them once reads cross a loop back edge; written by hand, the
-// wait before a matrix-core step can leave the reads of the following step in flight.  tie() makes a
-// register an output of an (empty) instruction placed after the wait, so that no use of it can be
-// scheduled above the wait.
+// wait before a matrix-core step can leave the reads of the following steps in flight.
+//
+// To the compiler the destination of such a read holds its value the moment the instruction is issued.
+// Two rules follow, and every read in this file obeys both:
+//   * the value is first used through tie(), an (empty) instruction placed after the wait that covers the
+//     read, so that no use can be scheduled above the wait;
+//   * EVERY read is tied that way, also one whose value is never fed to the matrix core.  A destination
+//     that is dead right after the read is a free register to the compiler, which may then park an
+//     address or a loop variable in it while the read is still in flight, and the returning data lands
+//     on top of that value.  (Seen as rare wrong tiles when other kernels kept the compute unit's LDS
+//     busy: the late return overwrote the address of the next chunk's first reads, which then read out
+//     of range, i.e. zeros.)
 template <int OFF>
 __device__ __forceinline__ bf16x8 lds_read_b128(uint32_t addr)
 {
@@ -146,6 +155,15 @@ static gemm_tile_plan make_tile_plan(int mrem, int cb, int ringb, int nw, int nl
     t.inv_nload = (1u << 20) / (uint32_t)t.nload + 1u;
     t.inv_hb = (1u << 20) / (uint32_t)t.HB + 1u;
     return t;
+}
+
+// Most loads one loading wave can have outstanding under a plan: its share of the nslots-1 chunks in flight
+// (2*cb weight blocks and HB half blocks a stage, each kind dealt round-robin).  Must stay below the load
+// counter's "do not wait" value (see wait_loads_then_barrier).
+static bool plan_fits_load_counter(const gemm_tile_plan& t, int cb)
+{
+    const int per_chunk = (t.SPC * 2 * cb + t.nload - 1) / t.nload + t.SPC * ((t.HB + t.nload - 1) / t.nload) + 1;
+    return (t.nslots - 1) * per_chunk <= 62;
 }
 
 // PCB: column blocks per slab of the packed weights.  PCB == CB: the workgroup's weights are one slab.
@@ -367,17 +385,14 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
         auto open_chunk = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
 
         if constexpr (CB * NRB >= 6) {
-            // One two-deep pipeline over the whole K range: the operands of a chunk's first step are read
-            // while the last step of the chunk before is in the matrix core, so that no LDS latency is
-            // exposed at a chunk boundary (a chunk is a single stage for the tallest tiles).  The barrier
-            // that opens chunk c+1 therefore sits before the last step of chunk c; the wave has issued,
-            // and waited for, all its reads of chunk c-1 by then, which is what the loaders rely on.
-            // The reads of a step are issued before the wait for the step before it, which leaves exactly
-            // these CB+NRB reads in flight (LDS reads return in order).
+            // One two-deep pipeline over the whole K range: the operands of a step are read while the step
+            // before it is in the matrix core, also across a chunk boundary (a chunk is a single stage for the
+            // tallest tiles), so that no LDS latency is exposed.  The barrier that opens chunk c+1 therefore
+            // sits before the last step of chunk c; the wave has issued, and waited for, all its reads of
+            // chunk c-1 by then, which is what the loaders rely on.
             using wseq = std::make_integer_sequence<int, CB>;
             using xseq = std::make_integer_sequence<int, NRB>;
-            constexpr int kReads = CB + NRB;
-            static_assert(kReads <= 15, "the LDS counter holds 0..15");
+            static_assert(CB + NRB <= 14, "outstanding LDS reads must stay below the counter's no-wait value");
             Frags f0, f1;
             int slot_c = 0;
             int s_cnt = chunk_stages(0);
@@ -389,11 +404,12 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
             for (int c = 0; c < nchunks; ++c) {
                 int next_cnt = 0;
                 for (int sl = 0; sl < s_cnt; ++sl) {
-                    read_frags<NW>(f1, wa + 1024u, xa + x1, wseq{}, xseq{});
-                    wait_lds_reads<kReads>();
+                    wait_lds_reads<0>();
                     tie_frags(f0, wseq{}, xseq{});
+                    read_frags<NW>(f1, wa + 1024u, xa + x1, wseq{}, xseq{});
                     mm(f0);
-                    bool more = true;
+                    wait_lds_reads<0>();
+                    tie_frags(f1, wseq{}, xseq{});
                     if (sl + 1 < s_cnt) {
                         wa += (uint32_t)(2 * CB) * 1024u;
                         xa += (uint32_t)nA * 1024u;
@@ -405,27 +421,24 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
                         wa = ring_addr + (uint32_t)(slot_c * slot_blocks) * 1024u + (uint32_t)lane * 16u;
                         xa = ring_addr + (uint32_t)(slot_c * slot_blocks + next_cnt * 2 * CB) * 1024u;
                         read_frags<NW>(f0, wa, xa + x0, wseq{}, xseq{});
-                    } else {
-                        more = false;
                     }
-                    if (more)
-                        wait_lds_reads<kReads>();
-                    else
-                        wait_lds_reads<0>();
-                    tie_frags(f1, wseq{}, xseq{});
                     mm(f1);
                 }
                 s_cnt = next_cnt;
             }
         } else {
-            // Small tiles: a step has too few matrix-core instructions to cover the LDS latency, so the
-            // reads run DS-1 steps ahead, one pipeline per chunk (a chunk has many stages here).  The wait
-            // before a step leaves the reads of the DS-1 steps after it in flight, so DS-1 times the reads
-            // of a step must fit the LDS counter (0..15).  Reads past the chunk's last stage are redirected
-            // to the last stage: in bounds and unused, which keeps the counts the same in every iteration.
+            // Small tiles: a step has too few matrix-core instructions to cover the LDS latency, so the reads
+            // run kAhead steps ahead, one pipeline per chunk (a chunk has many stages here).  The wait before a
+            // step leaves the reads of the kAhead-1 steps after it in flight; the step's own look-ahead read is
+            // issued after that wait, so at most kAhead*kReads <= 15 reads are ever outstanding and every wait
+            // names a count below the counter's no-wait value.  Reads past the chunk's last stage are
+            // redirected to the last stage: in bounds and never fed to the matrix core, which keeps the
+            // counts the same in every iteration.  Their registers are tied after the wait that ends the
+            // chunk like any other read's (see lds_read_b128).
             constexpr int kReads = CB + NRB;
             constexpr int kAhead = 15 / kReads >= 7 ? 7 : (15 / kReads >= 5 ? 5 : (15 / kReads >= 3 ? 3 : 1));
             constexpr int DS = kAhead + 1;  // even, so that the parity of a step is static in the unrolled loop
+            static_assert(kAhead * kReads <= 15 && (kAhead - 1) * kReads <= 14, "LDS counter");
             using wseq = std::make_integer_sequence<int, CB>;
             using xseq = std::make_integer_sequence<int, NRB>;
             const uint32_t x0 = (uint32_t)a0_off * 16u, x1 = (uint32_t)a1_off * 16u;
@@ -449,13 +462,16 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
 #pragma unroll
                     for (int k = 0; k < DS; ++k) {
                         if (u0 + k < nsteps) {
-                            rd_step(f[(k + DS - 1) % DS], u0 + k + DS - 1, (k + DS - 1) & 1);
-                            wait_lds_reads<kAhead * kReads>();
+                            wait_lds_reads<(kAhead - 1) * kReads>();
                             tie_frags(f[k], wseq{}, xseq{});
+                            rd_step(f[(k + DS - 1) % DS], u0 + k + DS - 1, (k + DS - 1) & 1);
                             mm(f[k]);
                         }
                     }
                 }
+                wait_lds_reads<0>();
+#pragma unroll
+                for (int d = 0; d < DS; ++d) tie_frags(f[d], wseq{}, xseq{});
                 slot_c = slot_c + 1 == nslots ? 0 : slot_c + 1;
             }
         }
@@ -526,16 +542,18 @@ __global__ __launch_bounds__(256) void gemm_pack_kernel(const uint16_t* __restri
 }
 
 template <int CB, int RINGB, int EPI, int NW, int NL, int PCB = CB>
-static void launch_gemm(const void* A, int lda, const void* Bp, void* C, int ldc, const void* R, int ldr, int M,
+static bool launch_gemm(const void* A, int lda, const void* Bp, void* C, int ldc, const void* R, int ldr, int M,
                         int N, int K, int out_f32, hipStream_t s, int tile_rows = 256)
 {
     // tile_rows: a multiple of 16 in 16..256 (the kernel handles 1..16 row blocks of 16 rows)
     dim3 grid(N / (16 * CB), (M + tile_rows - 1) / tile_rows);
     const gemm_tile_plan full = make_tile_plan(tile_rows, CB, RINGB, NW, NL, K);
     const gemm_tile_plan tail = make_tile_plan(M - tile_rows * ((M - 1) / tile_rows), CB, RINGB, NW, NL, K);
+    if (!plan_fits_load_counter(full, CB) || !plan_fits_load_counter(tail, CB)) return false;
     hipLaunchKernelGGL((gemm_kernel<CB, RINGB, EPI, NW, NL, PCB>), grid, dim3(64 * (NW + NL)), 0, s,
                        static_cast<const uint16_t*>(A), lda, static_cast<const uint4*>(Bp), C, ldc,
                        static_cast<const uint16_t*>(R), ldr, K, out_f32, full, tail);
+    return true;
 }
 
 // Picks the kernel configuration (packing from N, tiling from N and M) and launches it.
@@ -543,6 +561,7 @@ template <int EPI>
 static int gemm_dispatch(const void* A, int lda, const void* Bp, void* C, int ldc, const void* R, int ldr, int M,
                          int N, int K, int f32, hipStream_t s)
 {
+    bool ok = true;  // false: the schedule would overrun the kernel's load counter (no supported shape does)
     const int cb = gemm_cols_per_block(N);
     const bool small = gemm_small_ring(N);
     // What bounds a launch with many rows is the bytes each workgroup pulls through its compute unit's
@@ -556,12 +575,12 @@ static int gemm_dispatch(const void* A, int lda, const void* Bp, void* C, int ld
     //     widest tile moves the fewest bytes per flop, whatever the packing.
     if (!small && cb < 8 && 8 % cb == 0 && N % 128 == 0 && (long long)((M + 255) / 256) * (N / 128) >= 256) {
         if (cb == 1)
-            launch_gemm<8, kRingBig, EPI, 8, 4, 1>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s);
+            ok = launch_gemm<8, kRingBig, EPI, 8, 4, 1>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s);
         else if (cb == 2)
-            launch_gemm<8, kRingBig, EPI, 8, 4, 2>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s);
+            ok = launch_gemm<8, kRingBig, EPI, 8, 4, 2>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s);
         else
-            launch_gemm<8, kRingBig, EPI, 8, 4, 4>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s);
-        return check_launch();
+            ok = launch_gemm<8, kRingBig, EPI, 8, 4, 4>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s);
+        return ok ? check_launch() : DET_ESHAPE;
     }
     // (2) Matrices too narrow to give every compute unit a column tile (N / (16 cb) < 256): the rows are
     //     cut into as many tiles as fill the chip, which also shortens each workgroup's pass over A.
@@ -593,20 +612,20 @@ static int gemm_dispatch(const void* A, int lda, const void* Bp, void* C, int ld
     if (!small && N % 64 == 0 && sq_pays && ((cb == 1 && M >= 96) || (cb == 2 && M >= 192))) {
         const int rows = sq_rows;
         if (cb == 1)
-            launch_gemm<4, kRingBig, EPI, 8, 4, 1>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s, rows);
+            ok = launch_gemm<4, kRingBig, EPI, 8, 4, 1>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s, rows);
         else
-            launch_gemm<4, kRingBig, EPI, 8, 4, 2>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s, rows);
-        return check_launch();
+            ok = launch_gemm<4, kRingBig, EPI, 8, 4, 2>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s, rows);
+        return ok ? check_launch() : DET_ESHAPE;
     }
 #define DET_GEMM_CASE(CBV)                                                                                  \
     case CBV:                                                                                               \
         if constexpr (CBV <= 3) {                                                                           \
             if (small) {                                                                                    \
-                launch_gemm<CBV, gemm_small_ring_blocks(CBV), EPI, gemm_waves(CBV), gemm_loader_waves(CBV, true)>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s); \
+                ok = launch_gemm<CBV, gemm_small_ring_blocks(CBV), EPI, gemm_waves(CBV), gemm_loader_waves(CBV, true)>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s); \
                 break;                                                                                      \
             }                                                                                               \
         }                                                                                                   \
-        launch_gemm<CBV, kRingBig, EPI, gemm_waves(CBV), gemm_loader_waves(CBV, false)>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s, base_rows);            \
+        ok = launch_gemm<CBV, kRingBig, EPI, gemm_waves(CBV), gemm_loader_waves(CBV, false)>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s, base_rows);            \
         break;
     switch (cb) {
         DET_GEMM_CASE(1)
@@ -617,11 +636,11 @@ static int gemm_dispatch(const void* A, int lda, const void* Bp, void* C, int ld
         DET_GEMM_CASE(6)
         DET_GEMM_CASE(7)
         default:
-            launch_gemm<8, kRingBig, EPI, gemm_waves(8), gemm_loader_waves(8, false)>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s, base_rows);
+            ok = launch_gemm<8, kRingBig, EPI, gemm_waves(8), gemm_loader_waves(8, false)>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s, base_rows);
             break;
     }
 #undef DET_GEMM_CASE
-    return check_launch();
+    return ok ? check_launch() : DET_ESHAPE;
 }
 
 static bool gemm_shape_ok(int N, int K) { return N > 0 && K > 0 && N % 16 == 0 && K % 64 == 0; }

@@ -58,15 +58,17 @@ __device__ __forceinline__ void dma_run(const void* base, uint32_t lane_off, uin
     for (; n > 0; --n) dma_run_next(base, lane_off, src_stride, lds_stride);
 }
 
-// Waits until at most n of this wave's loads are outstanding (the counter holds 0..63; anything
-// above falls back to waiting for all of them), then the workgroup barrier.  The count is an
+// Waits until at most n of this wave's loads are outstanding, then the workgroup barrier.  The load
+// counter of the wait instruction has six bits and its largest value, 63, means "do not wait", so 63 and
+// anything above fall back to waiting for all loads; a wave must also never let more than 62 loads pile
+// up (the host checks the schedule it hands to the kernels for that).  The count is an
 // immediate of the wait instruction, so the wait is picked by a computed jump into a table of
 // 64 two-instruction entries (8 bytes each): two taken branches where a compare tree takes six.
 #define DET_W1(n) "s_waitcnt vmcnt(" #n ")\n\ts_branch .Ldet_wend%=\n\t"
 #define DET_W8(a, b, c, d, e, f, g, h) DET_W1(a) DET_W1(b) DET_W1(c) DET_W1(d) DET_W1(e) DET_W1(f) DET_W1(g) DET_W1(h)
 __device__ __forceinline__ void wait_loads_then_barrier(int n)
 {
-    uint32_t off = (uint32_t)(n > 63 ? 0 : n) << 3;
+    uint32_t off = (uint32_t)(n > 62 ? 0 : n) << 3;
     asm volatile(
         "s_getpc_b64 s[98:99]\n"
         ".Ldet_wbase%=:\n\t"
