@@ -264,6 +264,12 @@ int det_next_token(const int32_t *prompts, int Tp, const int32_t *prompt_lens,
                    const int32_t *last_sampled, int32_t *tokens_out, int32_t *positions_out,
                    int32_t *history, int Th, int t, int B, void *stream);
 
+/* The same bookkeeping after a one-pass prefill, where every sequence sits at its own position (section
+ * 6.6's loop with per-sequence step counters): tokens_out[b] = last_sampled[b];
+ * positions_out[b] = base_positions[b] + j.  All arrays [B] int32; j >= 0. */
+int det_decode_advance(const int32_t *last_sampled, const int32_t *base_positions, int j, int32_t *tokens_out,
+                       int32_t *positions_out, int B, void *stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Deterministic block-quantized GEMM (the paper's primary kernel family is the quantized one, section
  * 6.4 and Table 5; it gives no format, so one is defined here).

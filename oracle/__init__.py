@@ -295,12 +295,13 @@ def qlinear(a_bits, q, s) -> np.ndarray:
     return qgemm_w4a8(p, d, q, s)[1]
 
 
-def qdecoder_layer(x, w, kcache, vcache, positions, cos_t, sin_t, cfg):
+def qdecoder_layer(x, w, kcache, vcache, positions, cos_t, sin_t, cfg, intermediates=None):
     """One decoder layer with every projection block-quantized: the steps of decoder_layer in the same
     order, each projection replaced by qlinear on the bf16 activations it would have taken.  `w` holds
     norm1, norm2 (bf16 bits) and wqkv, wo, wgu, wdown as (codes int8 [K,N], scales bf16 bits [K/64,N])
     pairs from quant_w4 of the logical weights (wgu columns: F gate then F up).  Attention is the fp64
-    reference rounded once to bf16.  Returns the new x; the caches are updated in place."""
+    reference rounded once to bf16.  Returns the new x; the caches are updated in place.  `intermediates`, if
+    a dict, receives the branch values o, x1, dn (for the element-wise bound of oracle.model.layer_bound)."""
     x = _u16(x).copy()
     B, H = x.shape
     positions, cos_t, sin_t = _i32(positions), _f32(cos_t), _f32(sin_t)
@@ -317,11 +318,15 @@ def qdecoder_layer(x, w, kcache, vcache, positions, cos_t, sin_t, cfg):
         vcache[b, :, positions[b]] = v_new[b]
     att, _ = attn_decode_f64(q_rot, kcache, vcache, positions + 1, cfg["scale"])
     att = bf16_from_f64(att).reshape(B, Hq * D)
-    x = residual(x, qlinear(att, *w["wo"]))
+    o = qlinear(att, *w["wo"])
+    x = residual(x, o)
     h = rmsnorm(x, w["norm2"], cfg["eps"])
     gu = qlinear(h, *w["wgu"])
     mm = swiglu(np.ascontiguousarray(gu[:, :F]), np.ascontiguousarray(gu[:, F:]))
-    return residual(x, qlinear(mm, *w["wdown"]))
+    dn = qlinear(mm, *w["wdown"])
+    if intermediates is not None:
+        intermediates.update(o=o, x1=x, dn=dn)
+    return residual(x, dn)
 
 
 def commit_sha256(prompt: bytes, logits: bytes, tokens: bytes) -> bytes:

@@ -16,7 +16,7 @@ __all__ = [
     "det_attn_decode_workspace_bytes", "det_attn_decode", "det_attn_decode_static", "det_attn_decode_rows", "det_decoder_layer_rows",
     "det_softmax_f32", "det_argmax", "det_sample", "det_rope",
     "det_swiglu", "det_residual_add", "det_embed_gather", "det_decoder_layer_workspace_bytes",
-    "det_decoder_layer", "det_next_token", "det_fingerprint", "det_last_hip_error", "layer_cfg",
+    "det_decoder_layer", "det_next_token", "det_decode_advance", "det_fingerprint", "det_last_hip_error", "layer_cfg",
     "layer_weights", "pack_weight", "det_sha256_init", "det_sha256_update", "det_sha256_final",
     "det_commit_sha256", "det_sha256_force_portable", "det_qgemm_packed_w_bytes", "det_quant_pack_w4",
     "det_quant_unpack_w4", "det_quant_act_codes_bytes", "det_quant_act_scales_bytes", "det_quant_act_q8",
@@ -523,6 +523,16 @@ def det_qdecoder_layer(w: LayerWeights, cfg: LayerCfg, x, kcache, vcache, positi
         _contig(vcache, torch.bfloat16), _contig(positions, torch.int32), sl,
         _contig(rope_cos, torch.float32), _contig(rope_sin, torch.float32), _contig(ws),
         ws.numel() * ws.element_size(), R, _stream(stream)))
+
+
+def det_decode_advance(last_sampled, base_positions, j: int, tokens_out, positions_out, stream=None) -> None:
+    B = last_sampled.shape[0]
+    for a in (last_sampled, base_positions, tokens_out, positions_out):
+        if a.shape != (B,):
+            raise ValueError("bad decode_advance shapes")
+    _check("det_decode_advance", lib().det_decode_advance(
+        _contig(last_sampled, torch.int32), _contig(base_positions, torch.int32), j,
+        _contig(tokens_out, torch.int32), _contig(positions_out, torch.int32), B, _stream(stream)))
 
 
 def det_next_token(prompts, prompt_lens, last_sampled, tokens_out, positions_out, history, t: int,

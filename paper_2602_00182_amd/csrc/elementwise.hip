@@ -140,6 +140,18 @@ __global__ __launch_bounds__(256) void next_token_kernel(const int32_t* __restri
     history[(size_t)b * Th + t] = tok;
 }
 
+// Decode after a one-pass prefill: sequence b sits at its own position.
+__global__ __launch_bounds__(256) void advance_kernel(const int32_t* __restrict__ last_sampled,
+                                                      const int32_t* __restrict__ base_positions, int j,
+                                                      int32_t* __restrict__ tokens_out,
+                                                      int32_t* __restrict__ positions_out, int B)
+{
+    const int b = blockIdx.x * 256 + threadIdx.x;
+    if (b >= B) return;
+    tokens_out[b] = last_sampled[b];
+    positions_out[b] = base_positions[b] + j;
+}
+
 }  // namespace det
 
 using namespace det;
@@ -217,5 +229,14 @@ extern "C" int det_next_token(const int32_t* prompts, int Tp, const int32_t* pro
     hipLaunchKernelGGL(next_token_kernel, dim3((B + 255) / 256), dim3(256), 0,
                        static_cast<hipStream_t>(stream), prompts, Tp, prompt_lens, last_sampled, tokens_out,
                        positions_out, history, Th, t, B);
+    return check_launch();
+}
+
+extern "C" int det_decode_advance(const int32_t* last_sampled, const int32_t* base_positions, int j,
+                                  int32_t* tokens_out, int32_t* positions_out, int B, void* stream)
+{
+    if (!last_sampled || !base_positions || !tokens_out || !positions_out || B < 1 || j < 0) return DET_EINVAL;
+    hipLaunchKernelGGL(advance_kernel, dim3((B + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       last_sampled, base_positions, j, tokens_out, positions_out, B);
     return check_launch();
 }

@@ -143,6 +143,13 @@ def greedy_decode(model: DecodeModel, prompts: torch.Tensor, prompt_lens: torch.
     Returns (generated [B, n_new] int32 on the device, {step: logits [B, V] fp32 clone}).
     Step t feeds prompt token t while t < len, else the token sampled at step t-1; sequence b's
     generated tokens are the samples of steps len_b-1 .. len_b+n_new-2."""
+    # allocations, clones and the final gather are torch operations: they follow torch's current stream,
+    # which is made the library's stream for the whole run
+    with torch.cuda.stream(stream) if stream is not None else contextlib.nullcontext():
+        return _greedy_decode(model, prompts, prompt_lens, n_new, rope_cos, rope_sin, keep_logits_at, stream, policy)
+
+
+def _greedy_decode(model, prompts, prompt_lens, n_new, rope_cos, rope_sin, keep_logits_at, stream, policy):
     B, Tp = prompts.shape
     lens_host = prompt_lens.cpu()
     T = int(lens_host.max()) + n_new - 1
@@ -225,13 +232,13 @@ def _prefill_decode(model, prompts, prompt_lens, n_new, rope_cos, rope_sin, stre
 
     gen = torch.zeros((n_new, B), dtype=torch.int32, device=dev)
     kept = []
-    st.positions.copy_((lens_host - 1).to(torch.int32))
+    base_pos = (lens_host - 1).to(torch.int32).to(dev)   # position of each sequence's last prompt token
+    st.positions.copy_(base_pos)
     _select(policy, st.logits, st.positions, gen[0], stream)
     if keep_logits:
         kept.append(st.logits.clone())
     for j in range(1, n_new):
-        st.tokens.copy_(gen[j - 1])
-        st.positions.add_(1)
+        api.det_decode_advance(gen[j - 1], base_pos, j, st.tokens, st.positions, stream)
         st.forward(stream)
         _select(policy, st.logits, st.positions, gen[j], stream)
         if keep_logits:

@@ -363,3 +363,35 @@ def test_seeded_shape_sweep_both_gemms(d, orc):
             d.det_qgemm_w4a8(codes, scales, d.quant_pack_weight(up_bf16(W)), c, N)
             torch.cuda.synchronize()
             assert np.array_equal(down_bf16(c), orc.qlinear(X, *orc.quant_w4(W))), (M, N, K)
+
+
+@pytest.mark.parametrize("K,N", [(4096, 4096), (4096, 6144), (4096, 28672), (14336, 4096), (2048, 32000), (5632, 2048)])
+def test_every_m_from_1_to_256_keeps_row_bytes(d, orc, K, N):
+    """Exhaustive over the batch sizes of the contract: for every M in 1..256 the launch on the first M rows
+    gives rows 0..M-1 of the M = 256 launch byte for byte, for the bf16 GEMM and the quantized GEMM (whose
+    tile shape, loader split and stage schedule are all picked from M).  Compared on the device."""
+    X = ds.normal_bf16_torch(ds.tensor_seed(2, 7) + K, (256, K), 1.0, 0.0, DEV)
+    W = ds.normal_bf16_torch(ds.tensor_seed(2, 900) + K // 64 + N, (K, N), 0.02, 0.0, DEV)
+    Wp, Wq = d.pack_weight(W), d.quant_pack_weight(W)
+    del W
+    step(f"gemm every M, K={K} N={N}: M=256 reference launches")
+    full = torch.empty((256, N), dtype=torch.bfloat16, device=DEV)
+    d.det_gemm_bf16(X, Wp, full, N, K)
+    codes, scales = d.quant_activations(X)
+    qfull = torch.empty((256, N), dtype=torch.bfloat16, device=DEV)
+    d.det_qgemm_w4a8(codes, scales, Wq, qfull, N)
+    torch.cuda.synchronize()
+    bad = []
+    for M in range(1, 257):
+        if M % 32 == 1:
+            step(f"gemm every M, K={K} N={N}: M={M}..")
+        C = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=DEV)
+        d.det_gemm_bf16(X[:M], Wp, C, N, K)
+        cm, sm = d.quant_activations(X[:M])
+        Cq = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=DEV)
+        d.det_qgemm_w4a8(cm, sm, Wq, Cq, N)
+        if not torch.equal(C.view(torch.int16), full[:M].view(torch.int16)):
+            bad.append(("bf16", M))
+        if not torch.equal(Cq.view(torch.int16), qfull[:M].view(torch.int16)):
+            bad.append(("w4a8", M))
+    assert not bad, bad[:10]

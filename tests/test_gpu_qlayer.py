@@ -75,19 +75,27 @@ def test_qlayer_vs_oracle(d, orc, layer):
     rotation are bit-exact against the oracle, so the new K and V rows must match it byte for byte.
     After attention (fp32 on the GPU, fp64 rounded once in the oracle) the two sides may differ by
     one bf16 ulp in a few attention outputs, which moves the codes of those 64-element blocks; the
-    output is held to the bound of the bf16 layer test."""
+    output is held to the element-wise bound of the bf16 layer test (oracle.model.layer_bound)."""
     seq_ids, positions = [0, 1, 2], [2047, 1000, 0]
     step("quantized decoder layer B=3 vs oracle")
     x, kc, vc = run_layer(d, layer, seq_ids, positions)
     x0, kc0, vc0 = (down_bf16(t) for t in batch_inputs(seq_ids))
     w = {k: (down_bf16(v) if v.dim() == 1 else orc.quant_w4(down_bf16(v))) for k, v in layer["logical"].items()}
+    from oracle import model as om
+
+    inter = {}
     ref = orc.qdecoder_layer(x0, w, kc0, vc0, np.asarray(positions, dtype=np.int32), layer["cos_h"],
-                             layer["sin_h"], CFG)
+                             layer["sin_h"], CFG, intermediates=inter)
     assert np.array_equal(down_bf16(kc), kc0) and np.array_equal(down_bf16(vc), vc0)   # oracle updated its copies
     got, reff = bits_to_f64(down_bf16(x)), bits_to_f64(ref)
-    rms = np.sqrt((reff ** 2).mean())
     err = np.abs(got - reff)
-    assert (err <= 2.0 ** -6 * np.abs(reff) + 2.0 ** -5 * rms).all(), (err.max(), rms)
+    # the four roundings on an output's path (o, x1, dn, x2) one ulp each; the carried term is twice the
+    # bf16 layer's because a one-ulp flip of an activation also re-rounds the 8-bit codes of its 64-element
+    # block (each code by at most one step d = amax/127)
+    bound = om.layer_bound(ref, inter, carried_rel=2.0 ** -7)
+    print(f"[measured] quantized decoder layer vs oracle: max err/bound = {(err / bound).max():.3f}, "
+          f"outputs that differ: {(err > 0).mean():.5f}", flush=True)
+    assert (err <= bound).all(), (err / bound).max()
     assert (down_bf16(x) == ref).mean() > 0.9
 
 

@@ -69,6 +69,20 @@ def test_sample_ties_nan_and_batch_invariance(d, orc):
     assert cnt[4:].sum() == 0 and np.all(np.abs(cnt[:4] - 1024) < 5 * np.sqrt(1024 * 0.75))
 
 
+def test_sample_cut_and_pick_boundaries(d, orc):
+    """The hand-worked boundary cases (targets and cuts exactly on a prefix sum and just beside it): the
+    GPU gives the tokens derived from integers in sample_cases.py."""
+    import sample_cases as sc
+
+    logits, steps, want, ids = sc.pick_boundary_case()
+    step("sample: target exactly on / just under a prefix sum")
+    assert np.array_equal(run(d, logits, 1.0, 1024, 1.0, 0xC0FFEE, ids, steps), want)
+    cases, logits, steps, ids = sc.cut_boundary_case()
+    for top_p, want in cases:
+        step(f"sample: cut on / beside a prefix sum, top_p={top_p}")
+        assert np.array_equal(run(d, logits, 1.0, 4, top_p, 0xBEEF, ids, steps), want)
+
+
 def test_sample_error_codes(d):
     x = torch.zeros((2, 16), dtype=torch.float32, device=DEV)
     i = torch.zeros(2, dtype=torch.int32, device=DEV)

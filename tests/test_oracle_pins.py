@@ -557,6 +557,58 @@ def test_decoder_layer_rows_independent(orc):
     assert np.array_equal(full[1], one[0])
 
 
+def test_python_composed_layer_equals_the_c_layer_and_bound_is_sane(orc):
+    """oracle.model.layer (the composition that also returns intermediates) gives the bytes of
+    orc.decoder_layer, which the test above pins to numpy's matmul; its element-wise bound is at least one
+    ulp of the output and far below the output's magnitude."""
+    from oracle import model as om
+
+    cfg, w, x, kc, vc, pos, cos_t, sin_t = _layer_setup(seed=101)
+    kc1, vc1, kc2, vc2 = kc.copy(), vc.copy(), kc.copy(), vc.copy()
+    want = orc.decoder_layer(x, w, kc1, vc1, pos, cos_t, sin_t, cfg)
+    got, inter = om.layer(x, w, kc2, vc2, pos, cos_t, sin_t, cfg)
+    assert np.array_equal(got, want) and np.array_equal(kc1, kc2) and np.array_equal(vc1, vc2)
+    bound = om.layer_bound(got, inter)
+    f = np.abs(ds.bf16_bits_to_f32(got).astype(np.float64))
+    assert (bound >= om.ulp_bf16(got)).all() and np.median(bound / np.maximum(f, 1e-30)) < 0.1
+    # ulp_bf16 against the definition: the distance to the next bf16 value of the same sign
+    vals = ds.f32_to_bf16_bits(np.array([1.0, 1.5, 0.75, 3.0, 100.0, 2.0 ** -20], dtype=np.float32))
+    nxt = ds.bf16_bits_to_f32(vals + 1).astype(np.float64) - ds.bf16_bits_to_f32(vals).astype(np.float64)
+    assert np.array_equal(om.ulp_bf16(vals), nxt)
+
+
+def test_model_step_glue(orc):
+    """oracle.model.model_step: with the attention and MLP branches zeroed the logits are the lm_head
+    product of the normalised embedding row of each token (embedding gather, final norm, lm_head
+    orientation); rows are independent; and a second step at position 1 sees the cache row the first wrote."""
+    from oracle import model as om
+
+    cfg, w, x, kc, vc, pos, cos_t, sin_t = _layer_setup(seed=111)
+    H, V = cfg["H"], 48
+    Wt = dict(embed=ds.normal_bf16(120, (30, H)), lm_head=ds.normal_bf16(121, (H, V), 0.1),
+              final_norm=ds.normal_bf16(122, (H,), 0.1, 1.0), layers=[w, w])
+    zero = dict(w, wo=np.zeros_like(w["wo"]), wdown=np.zeros_like(w["wdown"]))
+    Wz = dict(Wt, layers=[zero, zero])
+    shape = (2, cfg["Hkv"], cfg["Lmax"], cfg["D"])
+    new = lambda: [np.zeros(shape, dtype=np.uint16) for _ in range(2)]
+    toks = np.array([7, 29])
+    lg = om.model_step(Wz, cfg, toks, [0, 0], new(), new(), cos_t, sin_t)
+    xn = ds.bf16_bits_to_f32(orc.rmsnorm(Wt["embed"][toks], Wt["final_norm"], cfg["eps"])).astype(np.float64)
+    assert np.array_equal(lg, xn @ ds.bf16_bits_to_f32(Wt["lm_head"]).astype(np.float64))
+    # full model: rows independent, and step 1 reads what step 0 wrote at cache row 0
+    kcs, vcs = new(), new()
+    l0 = om.model_step(Wt, cfg, toks, [0, 0], kcs, vcs, cos_t, sin_t)
+    k1, v1 = [k[1:2].copy() * 0 for k in kcs], [v[1:2].copy() * 0 for v in vcs]
+    assert np.array_equal(om.model_step(Wt, cfg, toks[1:], [0], k1, v1, cos_t, sin_t)[0], l0[1])
+    assert all(np.array_equal(a[0], b[1]) for a, b in zip(k1, kcs))
+    l1 = om.model_step(Wt, cfg, [3, 4], [1, 1], kcs, vcs, cos_t, sin_t)
+    wiped = [k.copy() for k in kcs]
+    for k in wiped:
+        k[:, :, 0] = 0                                     # forget the first token's keys: the logits must change
+    l1w = om.model_step(Wt, cfg, [3, 4], [1, 1], wiped, [v.copy() for v in vcs], cos_t, sin_t)
+    assert not np.array_equal(l1, l1w)
+
+
 # ------------------------------------------------------------------ input generator
 
 def test_generator_host_and_torch_paths_agree():
@@ -642,3 +694,21 @@ def test_sample_closed_forms(orc):
     xn = x.copy()
     xn[:, ::2] = np.nan
     assert np.all(orc.sample(xn, 1.0, 64, 1.0, 1, ids, st) % 2 == 1)
+
+
+def test_sample_cut_and_pick_comparisons_are_pinned_on_their_boundaries(orc):
+    """Targets and cuts that land exactly on a prefix sum, and just beside it: the strictness of
+    'c_i >= cut' and 'c_i > target' decides the token, and the expected tokens are worked out from
+    integers in tests/sample_cases.py, not by the oracle."""
+    import sample_cases as sc
+
+    logits, steps, want, ids = sc.pick_boundary_case()
+    assert len(set(want.tolist())) > 3 and want.min() >= 0
+    got = orc.sample(logits, 1.0, 1024, 1.0, 0xC0FFEE, ids, steps)
+    assert np.array_equal(got, want)
+    cases, logits, steps, ids = sc.cut_boundary_case()
+    for top_p, want in cases:
+        assert 0 < (want == want.max()).sum() < want.size      # both sides of each threshold occur
+        got = orc.sample(logits, 1.0, 4, top_p, 0xBEEF, ids, steps)
+        assert np.array_equal(got, want), top_p
+    assert cases[1][1].max() == 2 and cases[0][1].max() == 1
