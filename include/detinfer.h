@@ -117,7 +117,11 @@ int det_rmsnorm(const void *x, const void *w, void *y, int M, int H, float eps, 
  *   q, out   [B, Hq, D] bf16
  *   kcache, vcache [B, Hkv, Lmax, D] bf16
  *   seqlens  [B] int32, 0 <= seqlens[b] <= Lmax (values above Lmax are clamped to Lmax)
- *   ws       det_attn_decode_workspace_bytes(B, Hq, D, Lmax) bytes
+ *   ws       det_attn_decode_workspace_bytes(B, Hq, D, Lmax) bytes.  After the call it holds the chunk
+ *            partials, fp32, nc = ceil(Lmax/256): m_c [B, Hq, nc], then l_c [B, Hq, nc], then the
+ *            unnormalised chunk outputs o_c [B, Hq, nc, D]; entries of chunks at or past the sequence's
+ *            length are not written.  (Tests read m_c and l_c there and compare them bit for bit with
+ *            the reference statistics of the same scores.)
  *   Shapes: D == 128, Hq % Hkv == 0, Hq/Hkv in {1, 2, 4, 8}.
  */
 size_t det_attn_decode_workspace_bytes(int B, int Hq, int D, int Lmax);
@@ -149,8 +153,10 @@ int det_attn_decode_rows(const void *q, const void *kcache, const void *vcache, 
 int det_attn_decode_static(const void *q, const void *kcache, const void *vcache, const int32_t *seqlens,
                            void *out, int B, int Hq, int Hkv, int D, int Lmax, float scale, void *stream);
 
-/* Test hook: the softmax statistics of det_attn_decode on caller-provided fp32 scores, computed by
- * the same device code.  s, p [R, Lmax] fp32; lens [R]; m_out, l_out [R] fp32.
+/* Test hook: the softmax statistics of det_attn_decode on caller-provided fp32 scores.  The per-chunk
+ * statistics (m_c, e_j, l_c) come from the one device routine the attention kernel itself calls; the
+ * combination over chunks is the same ascending fold, written for one row per workgroup.
+ * s, p [R, Lmax] fp32; lens [R]; m_out, l_out [R] fp32.
  * p_j = (w_c * e_j) / L for j < lens[r]; entries at or past lens[r] are not written.
  * lens[r] = 0 gives m = -inf, L = 0.  Lmax <= 262144. */
 int det_softmax_f32(const float *s, const int32_t *lens, float *p, float *m_out, float *l_out, int R,

@@ -15,15 +15,56 @@ namespace det {
 constexpr int kChunk = 256;
 constexpr int kD = 128;
 
-// Softmax statistics of one chunk, one token per thread (leaf = threadIdx.x).
+// Softmax statistics of one chunk for G independent rows at once (the G query heads of a KV group in the
+// attention kernel, G = 1 in the softmax entry point), one token per thread (leaf = threadIdx.x):
 //   m_c = max of the valid scores;  e = det_expf(s - m_c) for a valid token, 0 otherwise;
-//   l_c = canonical tree sum of e.   `scratch`: 4 floats of LDS.
-__device__ __forceinline__ void chunk_stats(float s, bool valid, float* scratch, float& m_c, float& e,
-                                            float& l_c)
+//   l_c = the 256-leaf sum of e: inside a wavefront lane i takes lane i+off for off = 32, 16, .., 1, and
+//         the four wave sums q0..q3 combine as (q0+q2)+(q1+q3).
+// The G reductions are independent and share the barriers.  `scratch`: G x 4 floats of LDS; kScratchIdle
+// says that no thread can still be reading it from an earlier call (saves the leading barrier).
+// This is the only implementation of these statistics in the library: the attention kernel and
+// det_softmax_f32 both call it.
+template <int G, bool kScratchIdle>
+__device__ __forceinline__ void chunk_stats(const float (&s)[G], bool valid, float (*scratch)[4], float (&m_c)[G],
+                                            float (&e)[G], float (&l_c)[G])
 {
-    m_c = block_max(valid ? s : -INFINITY, scratch);
-    e = valid ? det_expf(s - m_c) : 0.0f;
-    l_c = block_tree_sum(e, scratch);
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    float sv[G], red[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        sv[h] = valid ? s[h] : -INFINITY;
+        red[h] = sv[h];
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1)
+#pragma unroll
+        for (int h = 0; h < G; ++h) red[h] = fmaxf(red[h], __shfl_xor(red[h], off, kWave));
+    if constexpr (!kScratchIdle) __syncthreads();
+    if (lane == 0)
+#pragma unroll
+        for (int h = 0; h < G; ++h) scratch[h][wave] = red[h];
+    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        m_c[h] = fmaxf(fmaxf(scratch[h][0], scratch[h][1]), fmaxf(scratch[h][2], scratch[h][3]));
+        e[h] = valid ? det_expf(sv[h] - m_c[h]) : 0.0f;
+        red[h] = e[h];
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1)
+#pragma unroll
+        for (int h = 0; h < G; ++h) red[h] = red[h] + __shfl_down(red[h], off, kWave);
+    __syncthreads();  // the maxima in scratch have been read
+    if (lane == 0)
+#pragma unroll
+        for (int h = 0; h < G; ++h) scratch[h][wave] = red[h];
+    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        const float qa = scratch[h][0] + scratch[h][2];
+        const float qb = scratch[h][1] + scratch[h][3];
+        l_c[h] = qa + qb;
+    }
 }
 
 // Combination of chunk statistics in ascending chunk order:
@@ -128,47 +169,17 @@ __global__ __launch_bounds__(256) void attn_chunk_kernel(const uint16_t* __restr
 
     const bool valid = t0 + tid < len;
     const size_t part = ((size_t)b * Hq + (size_t)hgrp * G) * ncmax + c;  // + h*ncmax
-    // chunk_stats for the G heads at once: the heads' reductions are independent of each other, so they
-    // share the barriers (4 instead of 4G); per head the operations and their order are chunk_stats'.
     {
-        float sv[G], red[G];
+        float sv[G], m_c[G], e[G], l_c[G];
 #pragma unroll
-        for (int h = 0; h < G; ++h) {
-            sv[h] = valid ? sc[h][tid] : -INFINITY;
-            red[h] = sv[h];
-        }
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1)
-#pragma unroll
-            for (int h = 0; h < G; ++h) red[h] = fmaxf(red[h], __shfl_xor(red[h], off, kWave));
-        if (lane == 0)
-#pragma unroll
-            for (int h = 0; h < G; ++h) scratch[h][wave] = red[h];
-        __syncthreads();
-        float m_c[G], e[G];
-#pragma unroll
-        for (int h = 0; h < G; ++h) {
-            m_c[h] = fmaxf(fmaxf(scratch[h][0], scratch[h][1]), fmaxf(scratch[h][2], scratch[h][3]));
-            e[h] = valid ? det_expf(sv[h] - m_c[h]) : 0.0f;
-            red[h] = e[h];
-        }
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1)
-#pragma unroll
-            for (int h = 0; h < G; ++h) red[h] = red[h] + __shfl_down(red[h], off, kWave);
-        __syncthreads();  // the maxima in scratch have been read
-        if (lane == 0)
-#pragma unroll
-            for (int h = 0; h < G; ++h) scratch[h][wave] = red[h];
-        __syncthreads();
+        for (int h = 0; h < G; ++h) sv[h] = sc[h][tid];
+        chunk_stats<G, true>(sv, valid, scratch, m_c, e, l_c);
 #pragma unroll
         for (int h = 0; h < G; ++h) {
             sc[h][tid] = e[h];  // only this thread reads or writes slot tid until the barrier below
             if (tid == 0) {
-                const float qa = scratch[h][0] + scratch[h][2];
-                const float qb = scratch[h][1] + scratch[h][3];
                 ws_m[part + (size_t)h * ncmax] = m_c[h];
-                ws_l[part + (size_t)h * ncmax] = qa + qb;
+                ws_l[part + (size_t)h * ncmax] = l_c[h];
             }
         }
     }
@@ -328,7 +339,7 @@ __global__ __launch_bounds__(256) void softmax_kernel(const float* __restrict__ 
 {
     __shared__ float mc[kMaxChunksHook];
     __shared__ float lc[kMaxChunksHook];
-    __shared__ float scratch[4];
+    __shared__ float scratch[1][4];
     const int r = blockIdx.x, tid = threadIdx.x;
     int len = lens[r];
     len = len > Lmax ? Lmax : len;
@@ -345,12 +356,13 @@ __global__ __launch_bounds__(256) void softmax_kernel(const float* __restrict__ 
     for (int c = 0; c < nc; ++c) {
         const int j = c * kChunk + tid;
         const bool valid = j < len;
-        float m_c, e, l_c;
-        chunk_stats(valid ? sr[j] : 0.0f, valid, scratch, m_c, e, l_c);
-        if (valid) pr[j] = e;
+        const float sv[1] = {valid ? sr[j] : 0.0f};
+        float m_c[1], e[1], l_c[1];
+        chunk_stats<1, false>(sv, valid, scratch, m_c, e, l_c);
+        if (valid) pr[j] = e[0];
         if (tid == 0) {
-            mc[c] = m_c;
-            lc[c] = l_c;
+            mc[c] = m_c[0];
+            lc[c] = l_c[0];
         }
     }
     __syncthreads();

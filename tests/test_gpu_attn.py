@@ -221,3 +221,75 @@ def test_quantized_output_equals_quantizer_of_the_output(d, orc):
     assert np.array_equal(codes2.cpu().numpy(), po[slots])
     got_d2 = np.ascontiguousarray(scales2.cpu().numpy().reshape(Hq * 2, ldd)[:, :B].T)
     assert np.array_equal(got_d2.view(np.uint32), do[slots].view(np.uint32))
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,Lmax,path", [
+    (1, 32, 8, 1024, "one workgroup per query head, V through LDS"),
+    (6, 32, 8, 1024, "4 heads per workgroup, V through LDS"),
+    (20, 32, 8, 1024, "4 heads per workgroup, V from global memory"),
+    (3, 8, 8, 600, "1 head per KV head"),
+    (10, 16, 8, 512, "2 heads per workgroup"),
+    (9, 16, 2, 2048, "8 heads per workgroup"),
+])
+def test_chunk_statistics_bitwise_against_reference_softmax(d, orc, B, Hq, Hkv, Lmax, path):
+    """The attention kernel's own m_c and l_c, read out of the workspace, equal the reference statistics of
+    the same scores bit for bit (section 6.5, invariant 2: the reduction tree), ragged lengths included.
+    The scores are exact by construction: q and k hold small integers (every partial sum of a dot product
+    is an integer below 2^24, so the accumulation order cannot matter) and the scale is a power of two, so
+    the host computes the very fp32 scores the kernel does, with integer arithmetic.  The combined m and L
+    of the same rows are checked through det_softmax_f32, which runs the same per-chunk device routine."""
+    seed = ds.tensor_seed(3, 500) + 7 * B + Lmax
+    qi = ds.uniform_int(seed, (B, Hq, 128), -3, 3)
+    ki = ds.uniform_int(seed + 1, (B, Hkv, Lmax, 128), -3, 3)
+    q = ds.f32_to_bf16_bits(qi.astype(np.float32))
+    k = ds.f32_to_bf16_bits(ki.astype(np.float32))
+    v = ds.normal_bf16(seed + 2, (B, Hkv, Lmax, 128))
+    lens = ds.uniform_int(seed + 3, (B,), 1, Lmax)
+    lens[0] = Lmax
+    for i, special in enumerate([1, 255, 256, 257]):
+        if i + 1 < B:
+            lens[i + 1] = min(special, Lmax)
+    scale = 0.125
+    nc = (Lmax + 255) // 256
+    ws = torch.empty(d.det_attn_decode_workspace_bytes(B, Hq, 128, Lmax), dtype=torch.uint8, device=DEV)
+    ws.fill_(0xFF)
+    out = torch.empty((B, Hq, 128), dtype=torch.bfloat16, device=DEV)
+    step(f"chunk statistics bitwise: B={B} Hq={Hq} Hkv={Hkv} Lmax={Lmax} ({path})")
+    d.det_attn_decode(up_bf16(q), up_bf16(k), up_bf16(v), up(lens.astype(np.int32)), out, ws, scale)
+    torch.cuda.synchronize()
+    n = B * Hq * nc
+    wsf = ws.cpu().numpy().view(np.float32)
+    got_m = wsf[:n].reshape(B, Hq, nc)
+    got_l = wsf[n:2 * n].reshape(B, Hq, nc)
+    G = Hq // Hkv
+    # exact scores [B, Hq, Lmax]: integer dot products times 2^-3
+    s = np.empty((B, Hq, Lmax), dtype=np.float32)
+    for h in range(Hq):
+        s[:, h, :] = (np.einsum("bd,btd->bt", qi[:, h, :].astype(np.int64), ki[:, h // G, :, :].astype(np.int64))
+                      .astype(np.float32) * np.float32(scale))
+    # per chunk: a chunk alone is a one-chunk row, whose reference (m, L) are its (m_c, l_c)
+    rows = s.reshape(B * Hq * nc, 256) if Lmax % 256 == 0 else None
+    if rows is None:
+        pad = np.zeros((B, Hq, nc * 256), dtype=np.float32)
+        pad[:, :, :Lmax] = s
+        rows = pad.reshape(B * Hq * nc, 256)
+    clen = np.clip(lens[:, None, None] - 256 * np.arange(nc)[None, None, :], 0, 256)
+    clen = np.broadcast_to(clen, (B, Hq, nc)).reshape(-1).astype(np.int32)
+    _, ref_m, ref_l = orc.softmax_f32(rows, clen, want_p=False)
+    live = clen > 0
+    assert np.array_equal(got_m.reshape(-1)[live].view(np.uint32), ref_m[live].view(np.uint32)), "m_c"
+    assert np.array_equal(got_l.reshape(-1)[live].view(np.uint32), ref_l[live].view(np.uint32)), "l_c"
+    # chunks past the length are never written
+    assert (wsf[:2 * n].view(np.uint32).reshape(2, -1)[:, ~live] == 0xFFFFFFFF).all()
+    # combined m and L of the full rows
+    R = B * Hq
+    full = np.ascontiguousarray(s.reshape(R, Lmax))
+    flen = np.repeat(lens.astype(np.int32), Hq)
+    _, ref_M, ref_L = orc.softmax_f32(full, flen, want_p=False)
+    p = torch.zeros((R, Lmax), dtype=torch.float32, device=DEV)
+    m = torch.empty(R, dtype=torch.float32, device=DEV)
+    l = torch.empty(R, dtype=torch.float32, device=DEV)
+    d.det_softmax_f32(up(full), up(flen), p, m, l)
+    torch.cuda.synchronize()
+    assert np.array_equal(m.cpu().numpy().view(np.uint32), ref_M.view(np.uint32))
+    assert np.array_equal(l.cpu().numpy().view(np.uint32), ref_L.view(np.uint32))
