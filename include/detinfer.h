@@ -50,8 +50,18 @@ extern "C" {
  * Each output element has ONE fp32 accumulator that starts at +0 and takes K/32 matrix-core steps
  * in ascending order; step t adds the 32 products of a fixed set of k indices (k in
  * [64*(t/2), 64*(t/2)+64), see det_gemm_pack_b).  There is no split of K across workgroups or
- * waves, no atomics, and the kernel configuration (columns per workgroup, K staging) is a function
- * of (N, K) only: M decides how many 16-row blocks of the fixed tile hold data, nothing else.
+ * waves and there are no atomics.
+ *
+ * What depends on (N, K) only: the packing, the matrix-core instruction, the K staging and the order
+ * of the steps, i.e. everything that enters an element's arithmetic.  What det_gemm_bf16 (and the
+ * fused forms below) ALSO choose from M is the tile a launch cuts C into, i.e. which workgroup and wave
+ * computes an element: 256 rows x the packing's width by default; rows cut into shorter tiles when N
+ * alone gives fewer than 256 workgroups and M >= 17; 64-column tiles from M >= 96 (16-column packings)
+ * or M >= 192 (32-column packings); 128-column tiles when ceil(M/256) * N/128 >= 256.  The bytes of a
+ * row do not depend on that choice (every tile shape runs the same chain for an element; the tests
+ * compare every M in 1..256 with the M = 256 launch and with det_gemm_bf16_fixed_tile), but it IS a
+ * launch geometry keyed on the batch size, so it is named here and in det_fingerprint(), and
+ * det_gemm_bf16_fixed_tile below is the form without it.
  *
  *   A        [M, K] bf16, row stride lda elements (lda >= K, lda % 8 == 0)
  *   B_packed output of det_gemm_pack_b for the same (N, K)
@@ -61,6 +71,13 @@ extern "C" {
  */
 int det_gemm_bf16(const void *A, int lda, const void *B_packed, void *C, int ldc, int M, int N,
                   int K, int out_dtype, void *stream);
+
+/* det_gemm_bf16 with ONE tiling per (N, K) that never looks at M (section 6.5, invariant 1 read
+ * strictly: a fixed workgroup -> tile mapping whatever the batch): 256-row tiles of the packing's
+ * width, M only decides how many 16-row blocks of a tile hold data.  Same arguments, same bytes; slower
+ * from about a hundred rows on (the benchmark reports both). */
+int det_gemm_bf16_fixed_tile(const void *A, int lda, const void *B_packed, void *C, int ldc, int M, int N,
+                             int K, int out_dtype, void *stream);
 
 /* Bytes of the packed form of a [K, N] bf16 matrix (= 2*K*N). 0 if the shape is unsupported. */
 size_t det_gemm_packed_b_bytes(int N, int K);

@@ -29,6 +29,7 @@ _vp, _i, _f, _sz, _i64 = C.c_void_p, C.c_int, C.c_float, C.c_size_t, C.c_int64
 # name -> (restype, argtypes); mirrors include/detinfer.h one to one
 SIGNATURES = {
     "det_gemm_bf16": (_i, [_vp, _i, _vp, _vp, _i, _i, _i, _i, _i, _vp]),
+    "det_gemm_bf16_fixed_tile": (_i, [_vp, _i, _vp, _vp, _i, _i, _i, _i, _i, _vp]),
     "det_gemm_packed_b_bytes": (_sz, [_i, _i]),
     "det_gemm_pack_b": (_i, [_vp, _vp, _i, _i, _vp]),
     "det_gemm_bf16_residual": (_i, [_vp, _i, _vp, _vp, _i, _vp, _i, _i, _i, _i, _vp]),

@@ -11,7 +11,7 @@ import torch
 from ._lib import LayerCfg, LayerWeights, Sha256Ctx, lib
 
 __all__ = [
-    "DetError", "det_gemm_bf16", "det_gemm_packed_b_bytes", "det_gemm_pack_b", "det_gemm_bf16_residual",
+    "DetError", "det_gemm_bf16", "det_gemm_bf16_fixed_tile", "det_gemm_packed_b_bytes", "det_gemm_pack_b", "det_gemm_bf16_residual",
     "det_gemm_pack_gate_up", "det_gemm_swiglu_bf16", "pack_gate_up", "det_rmsnorm",
     "det_attn_decode_workspace_bytes", "det_attn_decode", "det_attn_decode_static", "det_attn_decode_rows", "det_decoder_layer_rows",
     "det_softmax_f32", "det_argmax", "det_sample", "det_rope",
@@ -276,7 +276,7 @@ def pack_weight(B_kn: torch.Tensor, stream=None) -> torch.Tensor:
 
 
 def det_gemm_bf16(A: torch.Tensor, B_packed: torch.Tensor, C_out: torch.Tensor, N: int, K: int,
-                  stream=None) -> None:
+                  stream=None, _entry: str = "det_gemm_bf16") -> None:
     """C_out[M, N] = A[M, K] @ B.  A and C_out may be row-strided views (stride(1) == 1)."""
     M = A.shape[0]
     if A.shape[1] != K or C_out.shape != (M, N) or A.stride(1) != 1 or C_out.stride(1) != 1:
@@ -291,8 +291,14 @@ def det_gemm_bf16(A: torch.Tensor, B_packed: torch.Tensor, C_out: torch.Tensor, 
         raise TypeError("C must be bf16 or fp32")
     lda = A.stride(0) if M > 1 else max(A.stride(0), K)
     ldc = C_out.stride(0) if M > 1 else max(C_out.stride(0), N)
-    _check("det_gemm_bf16", lib().det_gemm_bf16(_ptr(A, torch.bfloat16), lda, _contig(B_packed), _ptr(C_out),
-                                                 ldc, M, N, K, od, _stream(stream)))
+    _check(_entry, getattr(lib(), _entry)(_ptr(A, torch.bfloat16), lda, _contig(B_packed), _ptr(C_out),
+                                          ldc, M, N, K, od, _stream(stream)))
+
+
+def det_gemm_bf16_fixed_tile(A: torch.Tensor, B_packed: torch.Tensor, C_out: torch.Tensor, N: int, K: int,
+                             stream=None) -> None:
+    """det_gemm_bf16 with the one tiling per (N, K) that does not look at M; same bytes."""
+    det_gemm_bf16(A, B_packed, C_out, N, K, stream, _entry="det_gemm_bf16_fixed_tile")
 
 
 def det_gemm_pack_gate_up(B_kn: torch.Tensor, B_packed: torch.Tensor, stream=None) -> None:

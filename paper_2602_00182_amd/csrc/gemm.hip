@@ -557,9 +557,11 @@ static bool launch_gemm(const void* A, int lda, const void* Bp, void* C, int ldc
 }
 
 // Picks the kernel configuration (packing from N, tiling from N and M) and launches it.
+// fixed_tile: the one tiling per (N, K) that does not look at M: 256-row tiles of the packing's own width,
+// whatever the row count (det_gemm_bf16_fixed_tile).
 template <int EPI>
 static int gemm_dispatch(const void* A, int lda, const void* Bp, void* C, int ldc, const void* R, int ldr, int M,
-                         int N, int K, int f32, hipStream_t s)
+                         int N, int K, int f32, hipStream_t s, bool fixed_tile = false)
 {
     bool ok = true;  // false: the schedule would overrun the kernel's load counter (no supported shape does)
     const int cb = gemm_cols_per_block(N);
@@ -573,7 +575,8 @@ static int gemm_dispatch(const void* A, int lda, const void* Bp, void* C, int ld
     //
     // (1) Launches with enough rows that 128-column tiles of 256 rows still fill the chip (prefill): the
     //     widest tile moves the fewest bytes per flop, whatever the packing.
-    if (!small && cb < 8 && 8 % cb == 0 && N % 128 == 0 && (long long)((M + 255) / 256) * (N / 128) >= 256) {
+    if (!fixed_tile && !small && cb < 8 && 8 % cb == 0 && N % 128 == 0 &&
+        (long long)((M + 255) / 256) * (N / 128) >= 256) {
         if (cb == 1)
             ok = launch_gemm<8, kRingBig, EPI, 8, 4, 1>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s);
         else if (cb == 2)
@@ -588,7 +591,7 @@ static int gemm_dispatch(const void* A, int lda, const void* Bp, void* C, int ld
     int base_rows = 256;
     {
         const int fit = 256 / (N / (16 * cb));
-        if (!small && fit >= 2 && row_blocks >= 2) {
+        if (!fixed_tile && !small && fit >= 2 && row_blocks >= 2) {
             const int row_tiles = row_blocks < fit ? row_blocks : fit;
             const int rows = 16 * ((row_blocks + row_tiles - 1) / row_tiles);
             base_rows = rows < 256 ? rows : 256;
@@ -609,7 +612,7 @@ static int gemm_dispatch(const void* A, int lda, const void* Bp, void* C, int ld
     const long long base_cost =
         (long long)(base_live + 16 * cb) * rounds((long long)(N / (16 * cb)) * ((M + base_rows - 1) / base_rows));
     const bool sq_pays = 115 * sq_cost <= 100 * base_cost;
-    if (!small && N % 64 == 0 && sq_pays && ((cb == 1 && M >= 96) || (cb == 2 && M >= 192))) {
+    if (!fixed_tile && !small && N % 64 == 0 && sq_pays && ((cb == 1 && M >= 96) || (cb == 2 && M >= 192))) {
         const int rows = sq_rows;
         if (cb == 1)
             ok = launch_gemm<4, kRingBig, EPI, 8, 4, 1>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s, rows);
@@ -698,6 +701,17 @@ extern "C" int det_gemm_bf16(const void* A, int lda, const void* B_packed, void*
     if (ldc < N) return DET_EINVAL;
     return gemm_dispatch<kEpiStore>(A, lda, B_packed, C, ldc, nullptr, 0, M, N, K, out_dtype == DET_F32,
                                     static_cast<hipStream_t>(stream));
+}
+
+extern "C" int det_gemm_bf16_fixed_tile(const void* A, int lda, const void* B_packed, void* C, int ldc, int M, int N,
+                                        int K, int out_dtype, void* stream)
+{
+    if (out_dtype != DET_BF16 && out_dtype != DET_F32) return DET_EINVAL;
+    const int rc = gemm_args_ok(A, lda, B_packed, C, ldc, M, N, K);
+    if (rc != DET_OK) return rc;
+    if (ldc < N) return DET_EINVAL;
+    return gemm_dispatch<kEpiStore>(A, lda, B_packed, C, ldc, nullptr, 0, M, N, K, out_dtype == DET_F32,
+                                    static_cast<hipStream_t>(stream), true);
 }
 
 extern "C" int det_gemm_bf16_residual(const void* A, int lda, const void* B_packed, const void* R, int ldr,

@@ -392,6 +392,11 @@ def test_every_m_from_1_to_256_keeps_row_bytes(d, orc, K, N):
         d.det_qgemm_w4a8(cm, sm, Wq, Cq, N)
         if not torch.equal(C.view(torch.int16), full[:M].view(torch.int16)):
             bad.append(("bf16", M))
+        # the tiling that never looks at M gives the same bytes as the one keyed on M
+        C.fill_(float("nan"))
+        d.det_gemm_bf16_fixed_tile(X[:M], Wp, C, N, K)
+        if not torch.equal(C.view(torch.int16), full[:M].view(torch.int16)):
+            bad.append(("bf16 fixed tile", M))
         if not torch.equal(Cq.view(torch.int16), qfull[:M].view(torch.int16)):
             bad.append(("w4a8", M))
     assert not bad, bad[:10]
