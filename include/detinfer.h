@@ -125,7 +125,10 @@ int det_rmsnorm(const void *x, const void *w, void *y, int M, int H, float eps, 
  *   s_j = scale * (q . k_j), j < len, contraction on matrix cores with fp32 accumulation;
  *   chunk c = tokens [256c, min(256c+256, len)):  m_c = max s_j;  e_j = det_expf(s_j - m_c);
  *   l_c = tree-sum of e_j (same 256-leaf tree as RMSNorm, leaf = j - 256c);
- *   O_c[d] = sum_j e_j * v_jd in fp32 in a fixed order;
+ *   O_c[d] = sum_j e_j * v_jd on the matrix cores: e_j (fp32) is cut by truncation into three bf16 pieces
+ *            with e_j = hi + mid + lo exactly, so every product piece * v is exact in fp32; one fp32
+ *            accumulator per (head, d) from +0 takes the chunk's eight 32-token steps in ascending order,
+ *            each step the hi, then the mid, then the lo products (tokens at or past len add +0);
  *   combine in ascending c:  m = max m_c;  w_c = det_expf(m_c - m);  L = sum w_c*l_c;
  *   O[d] = sum w_c*O_c[d];  out[d] = bf16(O[d] / L).
  * The number of chunks depends only on that sequence's length.  Cache contents at or past len are
@@ -149,7 +152,10 @@ int det_attn_decode(const void *q, const void *kcache, const void *vcache, const
 /* The same operation on R rows that name their cache slot: row r reads slot slots[r] of caches
  * [S, Hkv, Lmax, D] with length seqlens[r].  Several rows may share a slot (the tokens of one prompt
  * at lengths 1..T: batch-invariant prefill, since each row is exactly the single-token operation).
- * 0 <= slots[r] < S is the caller's responsibility.  Workspace: det_attn_decode_workspace_bytes(R, ...). */
+ * 0 <= slots[r] < S is the caller's responsibility.  Workspace: det_attn_decode_workspace_bytes(R, ...).
+ * From sixteen rows on, eight consecutive rows go to one workgroup, and those of them that name the same
+ * slot share each 256-token chunk of K and V (causal prefill: one read of the prompt's cache per eight
+ * query tokens instead of one per token).  Which rows share a workgroup changes no row's arithmetic. */
 int det_attn_decode_rows(const void *q, const void *kcache, const void *vcache, const int32_t *seqlens,
                          const int32_t *slots, void *out, void *ws, size_t ws_bytes, int R, int Hq,
                          int Hkv, int D, int Lmax, float scale, void *stream);

@@ -14,10 +14,10 @@ void set_last_hip_error(int e) { g_last_hip_error = e; }
 extern "C" const char* det_fingerprint(void)
 {
     return "libdetinfer gfx950 hip-" DET_STR(HIP_VERSION_MAJOR) "." DET_STR(HIP_VERSION_MINOR) "." DET_STR(
-        HIP_VERSION_PATCH) " canon-1 gemm-16x16x32-k64"
+        HIP_VERSION_PATCH) " canon-2 gemm-16x16x32-k64"
         // launch geometry revision: which tile shapes and kernel forms the row count (GEMM), the batch
         // (attention) select.  They move no output byte, but a receipt pins them all the same.
-        " tiles-2(gemm:n128@256wg,rowcut,n64@m96/192;qgemm:sp@8rows;attn:split@128wg,vlds@512wg)";
+        " tiles-2(gemm:n128@256wg,rowcut,n64@m96/192;qgemm:sp@8rows;attn:split@128wg,rows8@16rows)";
 }
 
 extern "C" int det_last_hip_error(void) { return det::g_last_hip_error; }

@@ -6,6 +6,7 @@
 #include <math.h>
 
 #include <atomic>
+#include <type_traits>
 
 #include "internal.h"
 #include "stream.h"
@@ -14,57 +15,69 @@ namespace det {
 
 constexpr int kChunk = 256;
 constexpr int kD = 128;
+constexpr int kHalfTok = 128;  // tokens of the half chunk whose V^T sits in LDS at a time
 
-// Softmax statistics of one chunk for G independent rows at once (the G query heads of a KV group in the
-// attention kernel, G = 1 in the softmax entry point), one token per thread (leaf = threadIdx.x):
-//   m_c = max of the valid scores;  e = det_expf(s - m_c) for a valid token, 0 otherwise;
-//   l_c = the 256-leaf sum of e: inside a wavefront lane i takes lane i+off for off = 32, 16, .., 1, and
-//         the four wave sums q0..q3 combine as (q0+q2)+(q1+q3).
-// The G reductions are independent and share the barriers.  `scratch`: G x 4 floats of LDS; kScratchIdle
-// says that no thread can still be reading it from an earlier call (saves the leading barrier).
-// This is the only implementation of these statistics in the library: the attention kernel and
-// det_softmax_f32 both call it.
-template <int G, bool kScratchIdle>
-__device__ __forceinline__ void chunk_stats(const float (&s)[G], bool valid, float (*scratch)[4], float (&m_c)[G],
-                                            float (&e)[G], float (&l_c)[G])
+// The value lane i+OFF holds, for the lanes i that the stride-halving tree needs at that level (i < OFF; what
+// the other lanes receive is unspecified and never reaches lane 0).  Strides below 16 stay inside a row of
+// sixteen lanes and are a modifier of the consuming instruction (row shift left: lane i reads lane i+OFF);
+// 16 and 32 cross rows and go through the LDS crossbar.
+template <int OFF>
+__device__ __forceinline__ float lane_plus(float v)
 {
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-    float sv[G], red[G];
+    const int x = __builtin_bit_cast(int, v);
+    if constexpr (OFF >= 16) {
+        const int lane = (int)(threadIdx.x & (kWave - 1));
+        return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(((lane + OFF) & (kWave - 1)) << 2, x));
+    } else {
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, x, 0x100 + OFF, 0xF, 0xF, true));
+    }
+}
+
+// Softmax statistics of one 256-token chunk of one row, computed by ONE wavefront: lane l holds the scores
+// of tokens l, l+64, l+128 and l+192 of the chunk (s[k], valid[k] for token 64k + l).
+//   m_c = max of the valid scores (-inf if there is none);
+//   e   = det_expf(s - m_c) for a valid token, 0 otherwise;
+//   l_c = the 256-leaf sum of e: inside each group of 64 tokens lane i takes lane i+off for off = 32, 16,
+//         .., 1, and the four group sums q0..q3 combine as (q0+q2)+(q1+q3).
+// m_c is returned in every lane, l_c is meaningful in lane 0 only.  No LDS, no barrier: the waves of a
+// workgroup run it independently on different rows.  This is the only implementation of these statistics
+// in the library: the attention kernel and det_softmax_f32 both call it.
+__device__ __forceinline__ void chunk_stats(const float (&s)[4], const bool (&valid)[4], float& m_c, float (&e)[4],
+                                            float& l_c)
+{
+    float sv[4];
 #pragma unroll
-    for (int h = 0; h < G; ++h) {
-        sv[h] = valid ? s[h] : -INFINITY;
-        red[h] = sv[h];
+    for (int k = 0; k < 4; ++k) sv[k] = valid[k] ? s[k] : -INFINITY;
+    float m = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));  // max is exact: any order
+    m = fmaxf(m, lane_plus<32>(m));
+    m = fmaxf(m, lane_plus<16>(m));
+    m = fmaxf(m, lane_plus<8>(m));
+    m = fmaxf(m, lane_plus<4>(m));
+    m = fmaxf(m, lane_plus<2>(m));
+    m = fmaxf(m, lane_plus<1>(m));
+    m = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, m)));  // lane 0 holds the maximum
+    m_c = m;
+    float red[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        e[k] = valid[k] ? det_expf(sv[k] - m) : 0.0f;
+        red[k] = e[k];
     }
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1)
+    for (int k = 0; k < 4; ++k) red[k] = red[k] + lane_plus<32>(red[k]);
 #pragma unroll
-        for (int h = 0; h < G; ++h) red[h] = fmaxf(red[h], __shfl_xor(red[h], off, kWave));
-    if constexpr (!kScratchIdle) __syncthreads();
-    if (lane == 0)
+    for (int k = 0; k < 4; ++k) red[k] = red[k] + lane_plus<16>(red[k]);
 #pragma unroll
-        for (int h = 0; h < G; ++h) scratch[h][wave] = red[h];
-    __syncthreads();
+    for (int k = 0; k < 4; ++k) red[k] = red[k] + lane_plus<8>(red[k]);
 #pragma unroll
-    for (int h = 0; h < G; ++h) {
-        m_c[h] = fmaxf(fmaxf(scratch[h][0], scratch[h][1]), fmaxf(scratch[h][2], scratch[h][3]));
-        e[h] = valid ? det_expf(sv[h] - m_c[h]) : 0.0f;
-        red[h] = e[h];
-    }
+    for (int k = 0; k < 4; ++k) red[k] = red[k] + lane_plus<4>(red[k]);
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1)
+    for (int k = 0; k < 4; ++k) red[k] = red[k] + lane_plus<2>(red[k]);
 #pragma unroll
-        for (int h = 0; h < G; ++h) red[h] = red[h] + __shfl_down(red[h], off, kWave);
-    __syncthreads();  // the maxima in scratch have been read
-    if (lane == 0)
-#pragma unroll
-        for (int h = 0; h < G; ++h) scratch[h][wave] = red[h];
-    __syncthreads();
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-        const float qa = scratch[h][0] + scratch[h][2];
-        const float qb = scratch[h][1] + scratch[h][3];
-        l_c[h] = qa + qb;
-    }
+    for (int k = 0; k < 4; ++k) red[k] = red[k] + lane_plus<1>(red[k]);
+    const float qa = red[0] + red[2];
+    const float qb = red[1] + red[3];
+    l_c = qa + qb;
 }
 
 // Combination of chunk statistics in ascending chunk order:
@@ -78,158 +91,283 @@ __device__ __forceinline__ float combine_max(const float* mc, int nc)
 
 // ------------------------------------------------------------------ attention, pass 1
 
-// Grid (chunk, kv head, sequence); 256 threads.  G = query heads per KV head.
-//   scores: wave w takes tokens 64w..64w+63 of the chunk as four 16-token blocks; the K rows are
-//           the row operand of v_mfma_f32_16x16x32_bf16 and the G query vectors (zero padded to
-//           16) its column operand; four steps cover the 128 head dimensions in ascending order
-//           (step i takes d = 32g + 8i + e for lane group g).
-//   stats : chunk_stats per head, token = thread.
-//   PV    : lane (p = lane/16, dg = lane%16) of wave w owns d = 8dg..8dg+7 and tokens
-//           64w + 4it + p, it = 0..15, folded in ascending it with fma from +0; the four p are
-//           summed as (p0+p2)+(p1+p3), then the four waves as (w0+w2)+(w1+w3).
-template <int G, bool VLDS>
-__global__ __launch_bounds__(256) void attn_chunk_kernel(const uint16_t* __restrict__ q,
-                                                         const uint16_t* __restrict__ kcache,
-                                                         const uint16_t* __restrict__ vcache,
-                                                         const int32_t* __restrict__ seqlens,
-                                                         const int32_t* __restrict__ slots,
-                                                         float* __restrict__ ws_m, float* __restrict__ ws_l,
-                                                         float* __restrict__ ws_o, int Hq, int Hkv, int Lmax,
-                                                         int ncmax, float scale, int len_offset)
+// One workgroup: one 256-token chunk of one cache slot's K/V, for up to RT query rows (tokens) times G
+// query heads that share the KV head ("pairs").  Decode launches it with RT = 1 (every row has a cache slot
+// of its own); the rows form with RT = 8 lets the rows of one prompt share each chunk of K and V (causal
+// prefill: row i of a prompt has length p + i).  Grid (chunk, head group, row tile); 256 threads.
+//
+// The arithmetic of one (row, head, chunk) is the same whatever else sits in the workgroup:
+//   scores: wave w takes tokens 64w..64w+63 of the chunk as four 16-token blocks; the K rows are the row
+//           operand of v_mfma_f32_16x16x32_bf16 and sixteen pairs' query vectors its column operand; four
+//           steps cover the 128 head dimensions in ascending order (step i takes d = 32g + 8i + e for lane
+//           group g), one accumulator chain per (token, pair), then one multiply by the scale.
+//   stats : chunk_stats, one wave per pair, a token valid iff it lies below that row's length.
+//   PV    : on the matrix cores as well.  e_j (fp32, >= 0) is cut into three bf16 pieces by truncation,
+//           e = hi + mid + lo exactly, so every product piece * v is exact in fp32; one accumulator chain
+//           per (pair, d) runs over the chunk's eight 32-token steps in ascending order, each step adding
+//           the hi, then the mid, then the lo products (V^T is the row operand, the pieces the column
+//           operand).  Tokens at or past the row's length have e = 0 and add +0.
+// Rows of a tile that name different slots are handled one slot after the other (same arithmetic, no
+// sharing).  V rows at or past the longest length in the workgroup are never read (zeros instead), K rows
+// likewise; what the cache holds there cannot reach an output.
+
+// Index (in uint4 = eight tokens of one head dimension) into the transposed V half tile: 128 rows (d) of 16
+// pieces (128 tokens), the pieces of a row rotated by d + d/8 so that both the transposing writes (rows 8
+// apart, same piece) and the operand reads (sixteen consecutive rows, same piece) spread over the banks.
+__device__ __forceinline__ int vt_index(int d, int piece) { return d * 16 + ((piece + d + (d >> 3)) & 15); }
+// Index (in floats) of token tok in pair p's score row: the row's 16-byte pieces are rotated by p, so that
+// sixteen pairs reading or writing the same tokens hit different banks.
+__device__ __forceinline__ int sc_index(int p, int tok)
 {
-    __shared__ float sc[G][kChunk];       // scores, then e_j
-    __shared__ float po[4][G][kD];        // per-wave partial outputs
-    __shared__ float scratch[G][4];
-    __shared__ uint4 vbuf[VLDS ? 4 : 1][VLDS ? 16 : 1][64];  // the chunk's V rows: wave, block of 4 tokens, lane
+    return p * kChunk + ((((tok >> 2) + p) & 63) << 2) + (tok & 3);
+}
 
-    // blockIdx.y names a group of G consecutive query heads; its KV head is the one those heads share.  A
-    // launch with G = heads per KV head has one group per KV head; a launch with G = 1 on a model with
-    // more gives every query head a workgroup of its own (same arithmetic per head, more workgroups).
-    const int c = blockIdx.x, hgrp = blockIdx.y, b = blockIdx.z;
+template <int I>
+__device__ __forceinline__ uint32_t u4_word(const uint4& v)
+{
+    return I == 0 ? v.x : (I == 1 ? v.y : (I == 2 ? v.z : v.w));
+}
+
+template <int G, int RT>
+__global__ __launch_bounds__(256, RT == 1 ? 4 : 2) void attn_tile_kernel(const uint16_t* __restrict__ q,
+                                                        const uint16_t* __restrict__ kcache,
+                                                        const uint16_t* __restrict__ vcache,
+                                                        const int32_t* __restrict__ seqlens,
+                                                        const int32_t* __restrict__ slots,
+                                                        float* __restrict__ ws_m, float* __restrict__ ws_l,
+                                                        float* __restrict__ ws_o, int R, int Hq, int Hkv, int Lmax,
+                                                        int ncmax, float scale, int len_offset)
+{
+    constexpr int NP = G * RT;             // pairs (row, head) of the workgroup
+    constexpr int CBK = (NP + 15) / 16;    // blocks of sixteen pairs
+    constexpr int DPW = 2 * CBK;           // (pair block, 16-wide d block) units of one wave in PV: 8*CBK/4
+    static_assert((G & (G - 1)) == 0 && CBK <= 4, "pair layout");
+    __shared__ __align__(16) float sc[NP * kChunk];  // scores, then e_j
+    __shared__ uint4 vt[128 * 16];                   // V^T of half a chunk: [d][token], 32 KB
+    const int c = blockIdx.x, hgrp = blockIdx.y, tile = blockIdx.z;
     const int kvh = (hgrp * G) / (Hq / Hkv);
-    int len = seqlens[b] + len_offset;
-    len = len > Lmax ? Lmax : len;
     const int t0 = c * kChunk;
-    if (t0 >= len) return;  // uniform over the workgroup
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 4, lr = lane & 15;
-    const int slot = slots ? slots[b] : b;  // which cache slot this row reads
-    const size_t kv_base = ((size_t)slot * Hkv + kvh) * (size_t)Lmax * kD;
-    const uint16_t* kp = kcache + kv_base;
-    const uint16_t* vp = vcache + kv_base;
 
-    // VLDS (launches with few workgroups, where latency and not bandwidth sets the time): the chunk's
-    // V rows go straight into LDS (64 KB, LDS-DMA) before anything else, so that they travel while the
-    // scores are computed.  Wave w loads what it will use itself: block `it` holds tokens 64w + 4it ..
-    // +3, lane (g, lr) its 16 bytes d = 8lr..8lr+7 of token 4it + g -- the lane that reads it back.
-    // Tokens past the length load nothing.  Large launches read V from global memory in the PV loop:
-    // with 12 KB of LDS many workgroups share a compute unit and their phases overlap.
-    if constexpr (VLDS) {
-        const int wu = __builtin_amdgcn_readfirstlane(wave);  // the load takes wave-uniform base addresses
-        const char* vsrc = reinterpret_cast<const char*>(vp + (size_t)(t0 + 64 * wu) * kD);
-        const uint32_t vdst = (uint32_t)(uintptr_t)(lds_char_t*)&vbuf[0][0][0] + (uint32_t)wu * 16384u;
-#pragma unroll
-        for (int it = 0; it < 16; ++it)
-            if (t0 + 64 * wave + 4 * it + g < len) dma_block(vsrc + it * 1024, (uint32_t)lane * 16u, vdst + it * 1024);
-    }
-
-    // query fragments: head lr (< G) of this KV group, d = 32g + 8i + e
-    uint4 qf[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) qf[i] = make_uint4(0, 0, 0, 0);
-    if (lr < G) {
-        const uint4* qp = reinterpret_cast<const uint4*>(q + ((size_t)b * Hq + (size_t)hgrp * G + lr) * kD + 32 * g);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) qf[i] = qp[i];
-    }
-
-#pragma unroll
-    for (int tb = 0; tb < 4; ++tb) {
-        const int tok = t0 + 64 * wave + 16 * tb + lr;
-        uint4 kf[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) kf[i] = make_uint4(0, 0, 0, 0);
-        if (tok < len) {
-            const uint4* kr = reinterpret_cast<const uint4*>(kp + (size_t)tok * kD + 32 * g);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) kf[i] = kr[i];
+    // the tile's rows: length (0: no such row) and slot; a row is active if it has tokens in this chunk
+    __shared__ int len[RT], slot[RT];
+    if (tid < RT) {
+        const int r = tile * RT + tid;
+        int l = 0, sl = -1;
+        if (r < R) {
+            l = seqlens[r] + len_offset;
+            l = l > Lmax ? Lmax : l;
+            sl = slots ? slots[r] : r;
         }
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[i]),
-                                                          __builtin_bit_cast(bf16x8, qf[i]), acc, 0, 0, 0);
-        // lane holds S[token = 16tb + 4g + v][head = lr]
-        if (lr < G) {
-#pragma unroll
-            for (int v = 0; v < 4; ++v) sc[lr][64 * wave + 16 * tb + 4 * g + v] = acc[v] * scale;
-        }
+        len[tid] = l;
+        slot[tid] = sl;
     }
     __syncthreads();
+    bool any = false;
+#pragma unroll
+    for (int ri = 0; ri < RT; ++ri) any = any || len[ri] > t0;
+    if (!any) return;  // uniform over the workgroup
 
-    const bool valid = t0 + tid < len;
-    const size_t part = ((size_t)b * Hq + (size_t)hgrp * G) * ncmax + c;  // + h*ncmax
-    {
-        float sv[G], m_c[G], e[G], l_c[G];
+    uint32_t done = 0;
+    bool first_group = true;
+#pragma unroll 1
+    for (int first = 0; first < RT; ++first) {
+        if (((done >> first) & 1u) || len[first] <= t0) continue;
+        const int group_slot = slot[first];
+        uint32_t mask = 0;
+        int maxlen = 0;
 #pragma unroll
-        for (int h = 0; h < G; ++h) sv[h] = sc[h][tid];
-        chunk_stats<G, true>(sv, valid, scratch, m_c, e, l_c);
-#pragma unroll
-        for (int h = 0; h < G; ++h) {
-            sc[h][tid] = e[h];  // only this thread reads or writes slot tid until the barrier below
-            if (tid == 0) {
-                ws_m[part + (size_t)h * ncmax] = m_c[h];
-                ws_l[part + (size_t)h * ncmax] = l_c[h];
+        for (int ri = 0; ri < RT; ++ri) {
+            const int l = len[ri];
+            if (l > t0 && slot[ri] == group_slot) {
+                mask |= 1u << ri;
+                maxlen = l > maxlen ? l : maxlen;
             }
         }
-    }
-    __syncthreads();
+        done |= mask;
+        if (!first_group) __syncthreads();  // the previous group's LDS contents are no longer read
+        first_group = false;
 
-    float o[G][8];
+        const size_t kv_base = ((size_t)group_slot * Hkv + kvh) * (size_t)Lmax * kD;
+        const uint16_t* kp = kcache + kv_base;
+        const uint16_t* vp = vcache + kv_base;
+
+        // ---- V: half a chunk at a time through registers into the transposed LDS tile.  A thread owns the
+        // 8 x 8 block (tokens 8*oc .. +7 of the half) x (d = 8*o .. +7): eight 16-byte loads, one per token.
+        const int o = lane & 15, oc = 4 * wave + (lane >> 4);
+        uint4 vr[8];
+        auto load_v = [&](int hf) {
 #pragma unroll
-    for (int h = 0; h < G; ++h)
+            for (int j = 0; j < 8; ++j) {
+                const int tok = t0 + kHalfTok * hf + 8 * oc + j;
+                vr[j] = make_uint4(0, 0, 0, 0);
+                if (tok < maxlen) vr[j] = *reinterpret_cast<const uint4*>(vp + (size_t)tok * kD + 8 * o);
+            }
+        };
+        auto store_vt = [&]() {
+            auto row = [&](auto e_tag) {
+                constexpr int E = decltype(e_tag)::value;
+                uint32_t w[4];
 #pragma unroll
-        for (int d = 0; d < 8; ++d) o[h][d] = 0.0f;
-    if constexpr (VLDS) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's V rows have landed
-#pragma unroll 4
-    for (int it = 0; it < 16; ++it) {
-        const int tl = 64 * wave + 4 * it + g;
-        if (t0 + tl < len) {
-            uint4 vv;
-            if constexpr (VLDS)
-                vv = vbuf[wave][it][lane];
-            else
-                vv = *reinterpret_cast<const uint4*>(vp + (size_t)(t0 + tl) * kD + 8 * lr);
-            const uint32_t pw[4] = {vv.x, vv.y, vv.z, vv.w};
-            float vf[8];
+                for (int jj = 0; jj < 4; ++jj) {
+                    const uint32_t a = u4_word<E / 2>(vr[2 * jj]), b = u4_word<E / 2>(vr[2 * jj + 1]);
+                    w[jj] = (E & 1) ? ((a >> 16) | (b & 0xFFFF0000u)) : ((a & 0xFFFFu) | (b << 16));
+                }
+                vt[vt_index(8 * o + E, oc)] = make_uint4(w[0], w[1], w[2], w[3]);
+            };
+            row(std::integral_constant<int, 0>{});
+            row(std::integral_constant<int, 1>{});
+            row(std::integral_constant<int, 2>{});
+            row(std::integral_constant<int, 3>{});
+            row(std::integral_constant<int, 4>{});
+            row(std::integral_constant<int, 5>{});
+            row(std::integral_constant<int, 6>{});
+            row(std::integral_constant<int, 7>{});
+        };
+        load_v(0);  // travels while the scores are computed
+
+        // ---- scores
+        {
+            uint4 qf[CBK][4];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                vf[2 * k] = bf16lo_to_f32(pw[k]);
-                vf[2 * k + 1] = bf16hi_to_f32(pw[k]);
+            for (int cb = 0; cb < CBK; ++cb) {
+                const int p = 16 * cb + lr;
+                const int ri = p / G, h = p % G;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) qf[cb][i] = make_uint4(0, 0, 0, 0);
+                if (p < NP && ((mask >> ri) & 1u)) {
+                    const uint4* qp = reinterpret_cast<const uint4*>(
+                        q + ((size_t)(tile * RT + ri) * Hq + (size_t)hgrp * G + h) * kD + 32 * g);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) qf[cb][i] = qp[i];
+                }
             }
 #pragma unroll
-            for (int h = 0; h < G; ++h) {
-                const float e = sc[h][tl];
+            for (int tb = 0; tb < 4; ++tb) {
+                const int tok = t0 + 64 * wave + 16 * tb + lr;
+                uint4 kf[4];
 #pragma unroll
-                for (int d = 0; d < 8; ++d) o[h][d] = __builtin_fmaf(e, vf[d], o[h][d]);
+                for (int i = 0; i < 4; ++i) kf[i] = make_uint4(0, 0, 0, 0);
+                if (tok < maxlen) {
+                    const uint4* kr = reinterpret_cast<const uint4*>(kp + (size_t)tok * kD + 32 * g);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) kf[i] = kr[i];
+                }
+#pragma unroll
+                for (int cb = 0; cb < CBK; ++cb) {
+                    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[i]),
+                                                                      __builtin_bit_cast(bf16x8, qf[cb][i]), acc, 0, 0, 0);
+                    // lane holds S[token = 16tb + 4g + v][pair = 16cb + lr]
+                    const int p = 16 * cb + lr;
+                    if (p < NP)
+                        *reinterpret_cast<float4*>(&sc[sc_index(p, 64 * wave + 16 * tb + 4 * g)]) =
+                            make_float4(acc[0] * scale, acc[1] * scale, acc[2] * scale, acc[3] * scale);
+                }
             }
         }
-    }
+        store_vt();  // first half of V; nobody reads vt before the barriers below
+        load_v(1);   // second half travels during the statistics and the first half of PV
+        __syncthreads();
+
+        // ---- statistics: wave w takes pairs w, w+4, ..; no barrier inside
 #pragma unroll
-    for (int h = 0; h < G; ++h)
+        for (int pi = 0; pi < (NP + 3) / 4; ++pi) {
+            const int p = 4 * pi + wave;
+            if (p < NP) {  // uniform over the wave
+                const int ri = p / G;
+                const bool in_group = (mask >> ri) & 1u;
+                const int l = len[ri];
+                float sv[4], e[4], m_c, l_c;
+                bool vd[4];
 #pragma unroll
-        for (int d = 0; d < 8; ++d) {
-            float v = o[h][d];
-            v = v + __shfl_down(v, 32, kWave);
-            v = v + __shfl_down(v, 16, kWave);
-            if (g == 0) po[wave][h][8 * lr + d] = v;
+                for (int k = 0; k < 4; ++k) {
+                    vd[k] = in_group && t0 + 64 * k + lane < l;
+                    sv[k] = sc[sc_index(p, 64 * k + lane)];
+                }
+                chunk_stats(sv, vd, m_c, e, l_c);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) sc[sc_index(p, 64 * k + lane)] = e[k];
+                if (lane == 0 && in_group) {
+                    const size_t part = ((size_t)(tile * RT + ri) * Hq + (size_t)hgrp * G + p % G) * ncmax + c;
+                    ws_m[part] = m_c;
+                    ws_l[part] = l_c;
+                }
+            }
         }
-    __syncthreads();
-    for (int i = tid; i < G * kD; i += 256) {
-        const int h = i / kD, d = i % kD;
-        const float a = po[0][h][d] + po[2][h][d];
-        const float bb = po[1][h][d] + po[3][h][d];
-        ws_o[(part + (size_t)h * ncmax) * kD + d] = a + bb;
+        __syncthreads();
+
+        // ---- PV.  Wave w owns pair block pb and the 16-wide d blocks db0 .. db0+DPW-1.
+        const int pb = CBK == 1 ? 0 : (CBK == 2 ? wave >> 1 : wave);
+        const int db0 = CBK == 1 ? 2 * wave : (CBK == 2 ? 4 * (wave & 1) : 0);
+        const int pp = 16 * pb + lr;  // this lane's pair as the column of the operand and of the output
+        f32x4 acc[DPW];
+#pragma unroll
+        for (int u = 0; u < DPW; ++u) acc[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+        auto pv_half = [&](int hf) {
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4) {
+                const int tk = kHalfTok * hf + 32 * s4 + 8 * g;  // this lane's eight tokens of the step
+                float ev[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) ev[k] = 0.0f;
+                if (pp < NP) {
+                    const float4 a = *reinterpret_cast<const float4*>(&sc[sc_index(pp, tk)]);
+                    const float4 b = *reinterpret_cast<const float4*>(&sc[sc_index(pp, tk + 4)]);
+                    ev[0] = a.x, ev[1] = a.y, ev[2] = a.z, ev[3] = a.w;
+                    ev[4] = b.x, ev[5] = b.y, ev[6] = b.z, ev[7] = b.w;
+                }
+                uint32_t hi[8], mid[8], lo[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    hi[k] = __float_as_uint(ev[k]) & 0xFFFF0000u;
+                    const float r1 = ev[k] - __uint_as_float(hi[k]);
+                    mid[k] = __float_as_uint(r1) & 0xFFFF0000u;
+                    lo[k] = __float_as_uint(r1 - __uint_as_float(mid[k]));  // at most 8 significant bits: exact in bf16
+                }
+                auto pack = [](const uint32_t (&x)[8]) {
+                    return __builtin_bit_cast(bf16x8, make_uint4((x[0] >> 16) | (x[1] & 0xFFFF0000u), (x[2] >> 16) | (x[3] & 0xFFFF0000u),
+                                                                 (x[4] >> 16) | (x[5] & 0xFFFF0000u), (x[6] >> 16) | (x[7] & 0xFFFF0000u)));
+                };
+                const bf16x8 phi = pack(hi), pmid = pack(mid), plo = pack(lo);
+#pragma unroll
+                for (int u = 0; u < DPW; ++u) {
+                    const bf16x8 vf = __builtin_bit_cast(bf16x8, vt[vt_index(16 * (db0 + u) + lr, 4 * s4 + g)]);
+                    acc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, phi, acc[u], 0, 0, 0);
+                    acc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pmid, acc[u], 0, 0, 0);
+                    acc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, plo, acc[u], 0, 0, 0);
+                }
+            }
+        };
+        pv_half(0);
+        __syncthreads();  // every wave is done with the first half of V^T
+        store_vt();
+        __syncthreads();
+        pv_half(1);
+
+        // lane holds O[d = 16*(db0+u) + 4g + v][pair pp]
+        bool mine = false;
+        int my_row = 0;
+#pragma unroll
+        for (int ri = 0; ri < RT; ++ri)
+            if (pp < NP && pp / G == ri && ((mask >> ri) & 1u)) {
+                mine = true;
+                my_row = tile * RT + ri;
+            }
+        if (mine) {
+            const size_t part = ((size_t)my_row * Hq + (size_t)hgrp * G + pp % G) * ncmax + c;
+            float* op = ws_o + part * kD + 4 * g;
+#pragma unroll
+            for (int u = 0; u < DPW; ++u) {
+                float2* dst = reinterpret_cast<float2*>(op + 16 * (db0 + u));  // 8-byte stores: ws_o is only that aligned
+                dst[0] = make_float2(acc[u][0], acc[u][1]);
+                dst[1] = make_float2(acc[u][2], acc[u][3]);
+            }
+        }
     }
 }
 
@@ -331,7 +469,8 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const int32_t* __rest
 
 constexpr int kMaxChunksHook = 1024;
 
-// One workgroup per row, chunks in ascending order; p holds e_j until the final rescale.
+// One workgroup per row; wave w computes the statistics of chunks w, w+4, .. (chunk_stats), then the chunks
+// are combined in ascending order; p holds e_j until the final rescale.
 __global__ __launch_bounds__(256) void softmax_kernel(const float* __restrict__ s,
                                                       const int32_t* __restrict__ lens,
                                                       float* __restrict__ p, float* __restrict__ m_out,
@@ -339,8 +478,7 @@ __global__ __launch_bounds__(256) void softmax_kernel(const float* __restrict__ 
 {
     __shared__ float mc[kMaxChunksHook];
     __shared__ float lc[kMaxChunksHook];
-    __shared__ float scratch[1][4];
-    const int r = blockIdx.x, tid = threadIdx.x;
+    const int r = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int len = lens[r];
     len = len > Lmax ? Lmax : len;
     if (len <= 0) {
@@ -353,19 +491,25 @@ __global__ __launch_bounds__(256) void softmax_kernel(const float* __restrict__ 
     const float* sr = s + (size_t)r * Lmax;
     float* pr = p + (size_t)r * Lmax;
     const int nc = (len + kChunk - 1) / kChunk;
-    for (int c = 0; c < nc; ++c) {
-        const int j = c * kChunk + tid;
-        const bool valid = j < len;
-        const float sv[1] = {valid ? sr[j] : 0.0f};
-        float m_c[1], e[1], l_c[1];
-        chunk_stats<1, false>(sv, valid, scratch, m_c, e, l_c);
-        if (valid) pr[j] = e[0];
-        if (tid == 0) {
-            mc[c] = m_c[0];
-            lc[c] = l_c[0];
+    for (int c = wave; c < nc; c += 4) {
+        float sv[4], e[4], m_c, l_c;
+        bool vd[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int j = c * kChunk + 64 * k + lane;
+            vd[k] = j < len;
+            sv[k] = vd[k] ? sr[j] : 0.0f;
+        }
+        chunk_stats(sv, vd, m_c, e, l_c);
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (vd[k]) pr[c * kChunk + 64 * k + lane] = e[k];
+        if (lane == 0) {
+            mc[c] = m_c;
+            lc[c] = l_c;
         }
     }
-    __syncthreads();
+    __syncthreads();  // also orders this workgroup's writes of e_j before the reads below
     const float m = combine_max(mc, nc);
     float L = 0.0f;
     for (int c = 0; c < nc; ++c) {
@@ -452,24 +596,26 @@ int det::attn_decode_impl(const void* q, const void* kcache, const void* vcache,
     float* ws_m = static_cast<float*>(ws);
     float* ws_l = ws_m + n;
     float* ws_o = ws_l + n;
-    // Launches of a few dozen workgroups (one sequence, short context) are all latency: every query head
-    // then gets a workgroup of its own, which divides the statistics and the PV fold of a workgroup by G.
-    const bool split_heads = G > 1 && (size_t)ncmax * Hkv * B <= 128;
-    const dim3 grid(ncmax, split_heads ? Hq : Hkv, B);
+    // Launch geometry (which workgroup computes a (row, head, chunk); never its arithmetic):
+    //   * rows that name their slots (prefill: consecutive rows of a prompt share a slot) go eight to a
+    //     workgroup from sixteen rows on, so that they share each chunk of K and V;
+    //   * launches of a few dozen workgroups (one sequence, short context) are all latency: every query
+    //     head then gets a workgroup of its own, which divides a workgroup's statistics and PV work by G.
+    const bool tiled = slots != nullptr && B >= 16;
+    const int RT = tiled ? 8 : 1;
+    const bool split_heads = !tiled && G > 1 && (size_t)ncmax * Hkv * B <= 128;
+    const dim3 grid(ncmax, split_heads ? Hq : Hkv, (B + RT - 1) / RT);
     const uint16_t* qq = static_cast<const uint16_t*>(q);
     const uint16_t* kk = static_cast<const uint16_t*>(kcache);
     const uint16_t* vv = static_cast<const uint16_t*>(vcache);
-    // Which of the two data paths for V is a matter of time only: the arithmetic and its order are the
-    // same, so a row's bytes do not depend on it.  At most two workgroups per compute unit: latency bound.
-    const bool vlds = (size_t)grid.x * grid.y * grid.z <= 512;
-#define DET_LAUNCH_ATTN(GG)                                                                                      \
-    do {                                                                                                         \
-        if (vlds)                                                                                                \
-            hipLaunchKernelGGL((attn_chunk_kernel<GG, true>), grid, dim3(256), 0, s, qq, kk, vv, seqlens, slots, \
-                               ws_m, ws_l, ws_o, Hq, Hkv, Lmax, ncmax, scale, len_offset);                      \
-        else                                                                                                     \
-            hipLaunchKernelGGL((attn_chunk_kernel<GG, false>), grid, dim3(256), 0, s, qq, kk, vv, seqlens, slots,\
-                               ws_m, ws_l, ws_o, Hq, Hkv, Lmax, ncmax, scale, len_offset);                      \
+#define DET_LAUNCH_ATTN(GG)                                                                                       \
+    do {                                                                                                          \
+        if (tiled)                                                                                                \
+            hipLaunchKernelGGL((attn_tile_kernel<GG, 8>), grid, dim3(256), 0, s, qq, kk, vv, seqlens, slots, ws_m, \
+                               ws_l, ws_o, B, Hq, Hkv, Lmax, ncmax, scale, len_offset);                          \
+        else                                                                                                      \
+            hipLaunchKernelGGL((attn_tile_kernel<GG, 1>), grid, dim3(256), 0, s, qq, kk, vv, seqlens, slots, ws_m, \
+                               ws_l, ws_o, B, Hq, Hkv, Lmax, ncmax, scale, len_offset);                          \
     } while (0)
     switch (split_heads ? 1 : G) {
         case 1: DET_LAUNCH_ATTN(1); break;

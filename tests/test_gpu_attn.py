@@ -187,8 +187,11 @@ def test_rows_variant_slots(d, orc):
         q1 = np.repeat(qr[r:r + 1], S, axis=0)
         one = run_attn(d, q1, k, v, np.full(S, r + 1, dtype=np.int32))
         assert np.array_equal(got[r], one[3])
-    ref, refabs = orc.attn_decode_f64(qr[250:251], k[3:4], v[3:4], [251], SCALE)
-    assert within_bound(bits_to_f64(got[250:251]), ref, refabs).all()
+    # rows of the shared-chunk path against the fp64 definition: the first tiles, the tile that straddles
+    # the chunk boundary at 256 tokens, and the last tile
+    for r in list(range(0, 17)) + [250, 254, 255, 256, 257, 263, 264, 296, 299]:
+        ref, refabs = orc.attn_decode_f64(qr[r:r + 1], k[3:4], v[3:4], [r + 1], SCALE)
+        assert within_bound(bits_to_f64(got[r:r + 1]), ref, refabs).all(), r
 
 
 def test_quantized_output_equals_quantizer_of_the_output(d, orc):
