@@ -59,6 +59,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain device-to-device copy of known size (for scaling rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE readings) and exit")
+    ap.add_argument("--probe", default=None, metavar="SPEC",
+                    help="run a few launches of ONE operation and exit (the program that rocprofv3 counter "
+                         "passes run): gemm:K:N:M, gemm_fixed:K:N:M, qgemm:K:N:M, attn:B:L, prefill:S:T, layer:B")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -85,6 +88,10 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes_read": nbytes, "calibrate_copy_bytes_written": nbytes,
                           "launches": 5}))
+        return
+
+    if args.probe:
+        probe(torch, det, ds, dev, args.probe)
         return
 
     # ------------------------------------------------------------------ resident inputs
@@ -249,6 +256,72 @@ def main():
         result["library_gemm"] = library_gemm(torch, ds, dev, sweep_cold)
         result["token_selection"] = selection_numbers(torch, det, ds, dev)
     print(json.dumps(result))
+
+
+def probe(torch, det, ds, dev, spec):
+    """A few launches of one operation at one size, for counter passes of rocprofv3 (every launch of the
+    named kernel in the run is the same work, so per-dispatch counters can be averaged)."""
+    kind, *nums = spec.split(":")
+    nums = [int(x) for x in nums]
+    scale = float(np.float32(1.0 / math.sqrt(128.0)))
+    reps = 12
+    if kind in ("gemm", "gemm_fixed", "qgemm"):
+        K, N, M = nums
+        X = ds.normal_bf16_torch(ds.tensor_seed(2, 7) + K, (M, K), 1.0, 0.0, dev)
+        C = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+        Ws = [ds.normal_bf16_torch(ds.tensor_seed(2, 10 * si), (K, N), 0.02, 0.0, dev) for si in range(3)]
+        if kind == "qgemm":
+            Wp = [det.quant_pack_weight(w) for w in Ws]
+            codes, scales = det.quant_activations(X)
+            for i in range(reps):
+                det.det_qgemm_w4a8(codes, scales, Wp[i % 3], C, N)
+        else:
+            Wp = [det.pack_weight(w) for w in Ws]
+            fn = det.det_gemm_bf16 if kind == "gemm" else det.det_gemm_bf16_fixed_tile
+            for i in range(reps):
+                fn(X, Wp[i % 3], C, N, K)
+    elif kind in ("attn", "prefill"):
+        Hq, Hkv, D = 32, 8, 128
+        if kind == "attn":
+            B, L = nums
+            S, R = B, B
+            lens = torch.full((B,), L, dtype=torch.int32, device=dev)
+            slots = None
+        else:
+            S, T = nums
+            L, R = ((T + 255) // 256) * 256, S * T
+            lens = (torch.arange(R, device=dev, dtype=torch.int32) % T + 1).contiguous()
+            slots = (torch.arange(R, device=dev, dtype=torch.int32) // T).contiguous()
+        q = ds.normal_bf16_torch(ds.tensor_seed(3, 10), (R, Hq, D), 1.0, 0.0, dev)
+        k = ds.normal_bf16_torch(ds.tensor_seed(3, 11), (S, Hkv, L, D), 1.0, 0.0, dev)
+        v = ds.normal_bf16_torch(ds.tensor_seed(3, 12), (S, Hkv, L, D), 1.0, 0.0, dev)
+        ws = torch.empty(det.det_attn_decode_workspace_bytes(R, Hq, D, L), dtype=torch.uint8, device=dev)
+        out = torch.empty((R, Hq, D), dtype=torch.bfloat16, device=dev)
+        for _ in range(reps):
+            if slots is None:
+                det.det_attn_decode(q, k, v, lens, out, ws, scale)
+            else:
+                det.det_attn_decode_rows(q, k, v, lens, slots, out, ws, scale)
+    elif kind == "layer":
+        (B,) = nums
+        H, Hq, Hkv, D, F, Lmax = 4096, 32, 8, 128, 14336, 2048
+        g = lambda i, shape, std=0.02, mean=0.0: ds.normal_bf16_torch(ds.tensor_seed(4, i), shape, std, mean, dev)
+        w = det.layer_weights(g(0, (H,), 0.0, 1.0), det.pack_weight(g(1, (H, (Hq + 2 * Hkv) * D))),
+                              det.pack_weight(g(2, (Hq * D, H))), g(3, (H,), 0.0, 1.0),
+                              det.pack_gate_up(g(4, (H, 2 * F))), det.pack_weight(g(5, (F, H))))
+        cfg = det.layer_cfg(H, Hq, Hkv, D, F, Lmax, 1e-5, scale)
+        cos_t, sin_t = ds.rope_tables(Lmax, D, 5.0e5)
+        cos_d, sin_d = torch.from_numpy(cos_t).to(dev), torch.from_numpy(sin_t).to(dev)
+        x = g(50, (B, H), 1.0)
+        kc, vc = g(70, (B, Hkv, Lmax, D), 1.0), g(80, (B, Hkv, Lmax, D), 1.0)
+        pos = torch.full((B,), Lmax - 1, dtype=torch.int32, device=dev)
+        ws = torch.empty(det.det_decoder_layer_workspace_bytes(cfg, B), dtype=torch.uint8, device=dev)
+        for _ in range(reps):
+            det.det_decoder_layer(w, cfg, x, kc, vc, pos, cos_d, sin_d, ws)
+    else:
+        raise SystemExit(f"bench.py: unknown probe {spec!r}")
+    torch.cuda.synchronize()
+    print(json.dumps({"probe": spec, "launches": reps}))
 
 
 def measured_peaks(torch, dev, roofline):

@@ -17,22 +17,6 @@ constexpr int kChunk = 256;
 constexpr int kD = 128;
 constexpr int kHalfTok = 128;  // tokens of the half chunk whose V^T sits in LDS at a time
 
-// The value lane i+OFF holds, for the lanes i that the stride-halving tree needs at that level (i < OFF; what
-// the other lanes receive is unspecified and never reaches lane 0).  Strides below 16 stay inside a row of
-// sixteen lanes and are a modifier of the consuming instruction (row shift left: lane i reads lane i+OFF);
-// 16 and 32 cross rows and go through the LDS crossbar.
-template <int OFF>
-__device__ __forceinline__ float lane_plus(float v)
-{
-    const int x = __builtin_bit_cast(int, v);
-    if constexpr (OFF >= 16) {
-        const int lane = (int)(threadIdx.x & (kWave - 1));
-        return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(((lane + OFF) & (kWave - 1)) << 2, x));
-    } else {
-        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, x, 0x100 + OFF, 0xF, 0xF, true));
-    }
-}
-
 // Softmax statistics of one 256-token chunk of one row, computed by ONE wavefront: lane l holds the scores
 // of tokens l, l+64, l+128 and l+192 of the chunk (s[k], valid[k] for token 64k + l).
 //   m_c = max of the valid scores (-inf if there is none);

@@ -66,12 +66,33 @@ __device__ __forceinline__ float det_expf(float x)
 
 // ---------------------------------------------------------------- canonical reductions
 
-// Stride-halving sum inside one wavefront: for off = 32,16,..,1 lane i takes lane i+off.  Lane 0
-// ends with the canonical sum of the 64 leaves; other lanes hold partial sums of no further use.
+// The value lane i+OFF holds, for the lanes i that the stride-halving tree needs at that level (i < OFF; what
+// the other lanes receive is unspecified and never reaches lane 0).  Strides below 16 stay inside a row of
+// sixteen lanes and are a modifier of the consuming instruction (row shift left: lane i reads lane i+OFF);
+// 16 and 32 cross rows and go through the LDS crossbar.
+template <int OFF>
+__device__ __forceinline__ float lane_plus(float v)
+{
+    const int x = __builtin_bit_cast(int, v);
+    if constexpr (OFF >= 16) {
+        const int lane = (int)(threadIdx.x & (kWave - 1));
+        return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(((lane + OFF) & (kWave - 1)) << 2, x));
+    } else {
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, x, 0x100 + OFF, 0xF, 0xF, true));
+    }
+}
+
+// Sum of the 64 values of one wavefront as a balanced tree of fixed shape: level by level for the strides
+// 32, 16, 8, 4, 2, 1, lane i adds the partial sum of lane i+stride to its own.  Lane 0 ends with the sum
+// ((..(v0+v32)+(v16+v48)..)); other lanes hold values of no further use.
 __device__ __forceinline__ float wave_tree_sum(float v)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = v + __shfl_down(v, off, kWave);
+    v = v + lane_plus<32>(v);
+    v = v + lane_plus<16>(v);
+    v = v + lane_plus<8>(v);
+    v = v + lane_plus<4>(v);
+    v = v + lane_plus<2>(v);
+    v = v + lane_plus<1>(v);
     return v;
 }
 

@@ -1,5 +1,5 @@
-// RMSNorm and greedy argmax: one 256-thread workgroup per row, canonical tree reductions (the
-// paper's section 6.5, invariant 2, with the shuffle loop written for a 64-wide wavefront).
+// RMSNorm and greedy argmax: one 256-thread workgroup per row; the sums use the balanced 256-leaf tree of
+// fixed shape that the paper's section 6.5 (invariant 2) asks for, laid over four 64-wide wavefronts.
 #include "common.h"
 
 namespace det {
