@@ -108,13 +108,36 @@ __device__ __forceinline__ void tie(T& v)
 {
     asm volatile("" : "+v"(v));
 }
-// Operands of one step: weight blocks 2 KB apart from waddr, activation tiles NW*2 KB apart from aaddr.
-template <int NW, class Frags, int... J, int... Q>
-__device__ __forceinline__ void read_frags(Frags& fr, uint32_t waddr, uint32_t aaddr, std::integer_sequence<int, J...>,
-                                           std::integer_sequence<int, Q...>)
+// Operands of one step: weight blocks 2 KB apart from waddr + WOFF (a constant of the instruction),
+// activation tiles NW*2 KB apart from aaddr.
+template <int NW, int WOFF, class Frags, int... J, int... Q>
+__device__ __forceinline__ void read_frags_at(Frags& fr, uint32_t waddr, uint32_t aaddr, std::integer_sequence<int, J...>,
+                                              std::integer_sequence<int, Q...>)
 {
-    ((fr.wf[J] = lds_read_b128<J * 2048>(waddr)), ...);
+    ((fr.wf[J] = lds_read_b128<WOFF + J * 2048>(waddr)), ...);
     ((fr.xf[Q] = lds_read_b128<Q * NW * 2048>(aaddr)), ...);
+}
+template <int NW, class Frags, int... J, int... Q>
+__device__ __forceinline__ void read_frags(Frags& fr, uint32_t waddr, uint32_t aaddr, std::integer_sequence<int, J...> w,
+                                           std::integer_sequence<int, Q...> x)
+{
+    read_frags_at<NW, 0>(fr, waddr, aaddr, w, x);
+}
+template <int... I, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F&& f)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+// f(integral_constant<int, 0>), .., f(integral_constant<int, N-1>): a loop whose index is a constant in the body
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
+// Steps the operand reads of a small tile run ahead of the matrix core (see the kernel), by operand reads a step
+__host__ __device__ constexpr int gemm_steps_ahead(int reads)
+{
+    return 15 / reads >= 7 ? 7 : (15 / reads >= 5 ? 5 : (15 / reads >= 3 ? 3 : 1));
 }
 template <class Frags, int... J, int... Q>
 __device__ __forceinline__ void tie_frags(Frags& fr, std::integer_sequence<int, J...>, std::integer_sequence<int, Q...>)
@@ -146,6 +169,16 @@ static gemm_tile_plan make_tile_plan(int mrem, int cb, int ringb, int nw, int nl
     t.HB = (mrem + 7) >> 3;
     const int nb = 2 * cb + 2 * t.RB;
     t.SPC = (ringb / 3) / nb > 1 ? (ringb / 3) / nb : 1;
+    {
+        // Small tiles run their operand reads in groups of stages (see the kernel's small-tile pipeline): a
+        // chunk that is a whole number of groups takes the short loop.  Sized for the wave with the most row
+        // blocks; data movement only.
+        const int nrb0 = (t.RB + nw - 1) / nw;
+        if (cb * nrb0 < 6) {
+            const int gs = (gemm_steps_ahead(cb + nrb0) + 1) / 2;
+            if (t.SPC >= 2 * gs) t.SPC -= t.SPC % gs;  // never gives up more than a third of a chunk
+        }
+    }
     t.slot_blocks = t.SPC * nb;
     t.nslots = ringb / t.slot_blocks < 4 ? ringb / t.slot_blocks : 4;
     const int nstages = K >> 6;
@@ -379,6 +412,15 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
 #pragma unroll
                 for (int j = 0; j < CB; ++j)
                     acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fr.wf[j], fr.xf[r], acc[r][j], 0, 0, 0);
+            // The matrix-core instructions have no side effects the compiler must order, so it may sink them
+            // below the reads that follow, which reuse the registers of `fr`: it would then rename those
+            // registers and copy them around, and a copy of a register whose read is still in flight copies
+            // stale data.  Tying the accumulators here (an empty instruction that "uses" them) pins the
+            // instructions above it, in order, before every later read.
+#pragma unroll
+            for (int r = 0; r < NRB; ++r)
+#pragma unroll
+                for (int j = 0; j < CB; ++j) tie(acc[r][j]);
             __builtin_amdgcn_sched_barrier(0);
         };
         // all of this wave's LDS reads have returned, then the barrier that opens the next chunk
@@ -431,47 +473,96 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
             // run kAhead steps ahead, one pipeline per chunk (a chunk has many stages here).  The wait before a
             // step leaves the reads of the kAhead-1 steps after it in flight; the step's own look-ahead read is
             // issued after that wait, so at most kAhead*kReads <= 15 reads are ever outstanding and every wait
-            // names a count below the counter's no-wait value.  Reads past the chunk's last stage are
-            // redirected to the last stage: in bounds and never fed to the matrix core, which keeps the
-            // counts the same in every iteration.  Their registers are tied after the wait that ends the
-            // chunk like any other read's (see lds_read_b128).
+            // names a count below the counter's no-wait value.
             constexpr int kReads = CB + NRB;
-            constexpr int kAhead = 15 / kReads >= 7 ? 7 : (15 / kReads >= 5 ? 5 : (15 / kReads >= 3 ? 3 : 1));
+            constexpr int kAhead = gemm_steps_ahead(kReads);
             constexpr int DS = kAhead + 1;  // even, so that the parity of a step is static in the unrolled loop
+            constexpr int GS = DS / 2;      // stages of one unrolled group of DS steps
             static_assert(kAhead * kReads <= 15 && (kAhead - 1) * kReads <= 14, "LDS counter");
+            static_assert(2 * GS * 2 * CB * 1024 + CB * 2048 < 65536, "weight offsets fit the read instruction's offset field");
             using wseq = std::make_integer_sequence<int, CB>;
             using xseq = std::make_integer_sequence<int, NRB>;
             const uint32_t x0 = (uint32_t)a0_off * 16u, x1 = (uint32_t)a1_off * 16u;
+            const uint32_t a_stage = (uint32_t)nA * 1024u;  // activation tiles of one stage
             int slot_c = 0;
             for (int c = 0; c < nchunks; ++c) {
                 open_chunk();
                 const int s_cnt = chunk_stages(c);
                 const uint32_t wb = ring_addr + (uint32_t)(slot_c * slot_blocks) * 1024u + (uint32_t)lane * 16u;
                 const uint32_t xb = ring_addr + (uint32_t)(slot_c * slot_blocks + s_cnt * 2 * CB) * 1024u;
-                const int last = s_cnt - 1;
-                auto rd_step = [&](Frags& fr, int u, int odd) {  // step u = 2*stage + odd; odd is static at every call
-                    const int sl = min(u >> 1, last);
-                    read_frags<NW>(fr, wb + (uint32_t)(sl * 2 * CB + odd) * 1024u, xb + (uint32_t)(sl * nA) * 1024u + (odd ? x1 : x0),
-                                   wseq{}, xseq{});
-                };
                 Frags f[DS];
+                // (the division is by a constant; the host makes the chunks whole groups wherever it can)
+                const int ngroups = s_cnt / GS;
+                if (ngroups * GS == s_cnt) {
+                    // The chunk is a whole number of groups of DS steps.  Step k of group g consumes f[k] and
+                    // issues the read of the step kAhead later: for k = 0 the group's own last step, for
+                    // k >= 1 step k-1 of group g+1, which the last group does not have, so nothing is ever
+                    // read that is not used.  Addresses: the weight blocks of a group and of the group after
+                    // it sit at constant offsets from one running pointer; the activation tiles of a stage are
+                    // nA KB apart (a run-time value), one running pointer per stage of this and the next group.
+                    uint32_t wg = wb;
+                    uint32_t xs[2 * GS];
 #pragma unroll
-                for (int d = 0; d < DS - 1; ++d) rd_step(f[d], d, d & 1);
-                const int nsteps = 2 * s_cnt;
-                for (int u0 = 0; u0 < nsteps; u0 += DS) {
-#pragma unroll
-                    for (int k = 0; k < DS; ++k) {
-                        if (u0 + k < nsteps) {
+                    for (int sg = 0; sg < 2 * GS; ++sg) xs[sg] = xb + (uint32_t)sg * a_stage;
+                    static_for<DS - 1>([&](auto dc) {
+                        constexpr int d = decltype(dc)::value;
+                        read_frags_at<NW, ((d >> 1) * 2 * CB + (d & 1)) * 1024>(f[d], wg, xs[d >> 1] + ((d & 1) ? x1 : x0), wseq{}, xseq{});
+                    });
+                    for (int grp = 0; grp + 1 < ngroups; ++grp) {
+                        static_for<DS>([&](auto kc) {
+                            constexpr int k = decltype(kc)::value;
+                            constexpr int t = k == 0 ? DS - 1 : DS + k - 1;  // the step read now, counted from this group's step 0
                             wait_lds_reads<(kAhead - 1) * kReads>();
                             tie_frags(f[k], wseq{}, xseq{});
-                            rd_step(f[(k + DS - 1) % DS], u0 + k + DS - 1, (k + DS - 1) & 1);
+                            read_frags_at<NW, ((t >> 1) * 2 * CB + (t & 1)) * 1024>(f[t % DS], wg, xs[t >> 1] + ((t & 1) ? x1 : x0), wseq{}, xseq{});
                             mm(f[k]);
+                        });
+                        wg += (uint32_t)(GS * 2 * CB) * 1024u;
+#pragma unroll
+                        for (int sg = 0; sg < 2 * GS; ++sg) xs[sg] += (uint32_t)GS * a_stage;
+                    }
+                    static_for<DS>([&](auto kc) {  // the last group
+                        constexpr int k = decltype(kc)::value;
+                        if constexpr (k == 0) {
+                            wait_lds_reads<(kAhead - 1) * kReads>();
+                            tie_frags(f[0], wseq{}, xseq{});
+                            read_frags_at<NW, (((DS - 1) >> 1) * 2 * CB + 1) * 1024>(f[DS - 1], wg, xs[(DS - 1) >> 1] + x1, wseq{}, xseq{});
+                        } else {
+                            wait_lds_reads<(DS - 1 - k) * kReads>();
+                            tie_frags(f[k], wseq{}, xseq{});
+                        }
+                        mm(f[k]);
+                    });
+                } else {
+                    // Any other chunk (the last one of a K that is not a whole number of groups): the same
+                    // pipeline with every address computed per step.  Reads past the chunk's last stage are
+                    // redirected to the last stage: in bounds and never fed to the matrix core, which keeps
+                    // the counts the same in every iteration; their registers are tied after the wait that
+                    // ends the chunk like any other read's (see lds_read_b128).
+                    const int last = s_cnt - 1;
+                    auto rd_step = [&](Frags& fr, int u, int odd) {  // step u = 2*stage + odd; odd is static at every call
+                        const int sl = min(u >> 1, last);
+                        read_frags<NW>(fr, wb + (uint32_t)(sl * 2 * CB + odd) * 1024u, xb + (uint32_t)sl * a_stage + (odd ? x1 : x0),
+                                       wseq{}, xseq{});
+                    };
+#pragma unroll
+                    for (int d = 0; d < DS - 1; ++d) rd_step(f[d], d, d & 1);
+                    const int nsteps = 2 * s_cnt;
+                    for (int u0 = 0; u0 < nsteps; u0 += DS) {
+#pragma unroll
+                        for (int k = 0; k < DS; ++k) {
+                            if (u0 + k < nsteps) {
+                                wait_lds_reads<(kAhead - 1) * kReads>();
+                                tie_frags(f[k], wseq{}, xseq{});
+                                rd_step(f[(k + DS - 1) % DS], u0 + k + DS - 1, (k + DS - 1) & 1);
+                                mm(f[k]);
+                            }
                         }
                     }
-                }
-                wait_lds_reads<0>();
+                    wait_lds_reads<0>();
 #pragma unroll
-                for (int d = 0; d < DS; ++d) tie_frags(f[d], wseq{}, xseq{});
+                    for (int d = 0; d < DS; ++d) tie_frags(f[d], wseq{}, xseq{});
+                }
                 slot_c = slot_c + 1 == nslots ? 0 : slot_c + 1;
             }
         }
