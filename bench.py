@@ -482,8 +482,80 @@ def cpu_baseline(ds):
             flops += gemm_flops(M, N, K)
         reps += 1
     return {"value": round(flops / t / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
+            "cores_note": "threads of the oracle's parallel loops (OpenMP), as many as the host offers this process",
             "kind": "oracle", "sample": f"fp64 reference GEMM, the four shapes at M={M}, {reps} pass(es) "
-                                        f"({flops / 1e9:.0f} GFLOP in {t:.1f} s)", "cpu": _cpu_model()}
+                                        f"({flops / 1e9:.0f} GFLOP in {t:.1f} s)", "cpu": _cpu_model(),
+            "other_legs": cpu_baseline_other_legs(ds)}
+
+
+def cpu_baseline_other_legs(ds):
+    """The oracle timed on the other parts of the path, each a bounded sample (a few seconds): fp32 RMSNorm /
+    softmax / argmax, fp64 attention at one point of the attention grid, one Llama-shaped decoder layer at
+    B = 1, and one decode step of a small model (2 layers, H = 256)."""
+    import oracle
+    from oracle import model as omodel
+
+    legs = {}
+
+    def timed(fn, min_s=1.0, max_reps=50):
+        t, n = 0.0, 0
+        while t < min_s and n < max_reps:
+            t0 = time.perf_counter()
+            fn()
+            t += time.perf_counter() - t0
+            n += 1
+        return t / n, n
+
+    x = ds.normal_bf16(901, (256, 4096))
+    w = ds.normal_bf16(902, (4096,), 0.0, 1.0)
+    dt, n = timed(lambda: oracle.rmsnorm(x, w, 1e-5))
+    legs["rmsnorm_256x4096"] = {"us": round(dt * 1e6, 1), "rows_per_s": round(256 / dt, 1), "reps": n}
+    sc = (ds.bf16_bits_to_f32(ds.normal_bf16(903, (64, 4096))) * np.float32(3.0)).astype(np.float32)
+    lens = np.full(64, 4096, dtype=np.int32)
+    dt, n = timed(lambda: oracle.softmax_f32(sc, lens))
+    legs["softmax_64x4096"] = {"us": round(dt * 1e6, 1), "rows_per_s": round(64 / dt, 1), "reps": n}
+    lg = ds.bf16_bits_to_f32(ds.normal_bf16(904, (64, 32000))).astype(np.float32)
+    dt, n = timed(lambda: oracle.argmax_f32(lg))
+    legs["argmax_64x32000"] = {"us": round(dt * 1e6, 1), "rows_per_s": round(64 / dt, 1), "reps": n}
+
+    B, Hq, Hkv, D, L = 16, 32, 8, 128, 4096
+    q = ds.normal_bf16(905, (B, Hq, D))
+    k = ds.normal_bf16(906, (B, Hkv, L, D))
+    v = ds.normal_bf16(907, (B, Hkv, L, D))
+    scale = float(np.float32(1.0 / math.sqrt(128.0)))
+    dt, n = timed(lambda: oracle.attn_decode_f64(q, k, v, np.full(B, L, dtype=np.int32), scale), max_reps=5)
+    legs["attention_f64_B16_L4096"] = {"ms": round(dt * 1e3, 2), "kv_gb_per_s": round(B * Hkv * L * D * 4 / dt / 1e9, 2),
+                                        "reps": n}
+
+    H, F, Lmax = 4096, 14336, 2048
+    s = ds.tensor_seed(4, 0)
+    g = lambda i, shape, std=0.02, mean=0.0: ds.normal_bf16(s + i, shape, std, mean)
+    lw = dict(norm1=g(0, (H,), 0.0, 1.0), wqkv=g(1, (H, (Hq + 2 * Hkv) * D)), wo=g(2, (Hq * D, H)),
+              norm2=g(3, (H,), 0.0, 1.0), wgu=g(4, (H, 2 * F)), wdown=g(5, (F, H)))
+    cfg = dict(H=H, Hq=Hq, Hkv=Hkv, D=D, F=F, Lmax=Lmax, eps=1e-5, scale=scale)
+    cos_t, sin_t = ds.rope_tables(Lmax, D, 5.0e5)
+    x1 = ds.normal_bf16(s + 51, (1, H))
+    kc = ds.normal_bf16(s + 71, (1, Hkv, Lmax, D))
+    vc = ds.normal_bf16(s + 81, (1, Hkv, Lmax, D))
+    dt, n = timed(lambda: omodel.layer(x1, lw, kc, vc, [Lmax - 1], cos_t, sin_t, cfg), max_reps=3)
+    legs["decoder_layer_B1_ctx2048"] = {"ms": round(dt * 1e3, 1), "layer_tokens_per_s": round(1 / dt, 2), "reps": n}
+    del lw, kc, vc
+
+    H, Hq, Hkv, F, V, NL, Lm = 256, 2, 1, 512, 512, 2, 64
+    s = ds.tensor_seed(5, 700)
+    g = lambda i, shape, std=0.05, mean=0.0: ds.normal_bf16(s + i, shape, std, mean)
+    layers = [dict(norm1=g(10 * l, (H,), 0.0, 1.0), wqkv=g(10 * l + 1, (H, (Hq + 2 * Hkv) * D)), wo=g(10 * l + 2, (Hq * D, H)),
+                   norm2=g(10 * l + 3, (H,), 0.0, 1.0), wgu=g(10 * l + 4, (H, 2 * F)), wdown=g(10 * l + 5, (F, H)))
+              for l in range(1, NL + 1)]
+    weights = dict(embed=g(1, (V, H), 1.0), lm_head=g(2, (H, V)), final_norm=g(3, (H,), 0.0, 1.0), layers=layers)
+    cfg = dict(H=H, Hq=Hq, Hkv=Hkv, D=D, F=F, Lmax=Lm, eps=1e-5, scale=scale)
+    cos_t, sin_t = ds.rope_tables(Lm, D, 5.0e5)
+    kcs = [np.zeros((4, Hkv, Lm, D), dtype=np.uint16) for _ in range(NL)]
+    vcs = [np.zeros((4, Hkv, Lm, D), dtype=np.uint16) for _ in range(NL)]
+    toks = ds.uniform_int(s + 900, (4,), 0, V - 1)
+    dt, n = timed(lambda: omodel.model_step(weights, cfg, toks, np.full(4, 10, dtype=np.int32), kcs, vcs, cos_t, sin_t))
+    legs["small_model_step_B4_2layers_H256"] = {"ms": round(dt * 1e3, 2), "tokens_per_s": round(4 / dt, 1), "reps": n}
+    return legs
 
 
 def _cpu_model():
@@ -692,14 +764,16 @@ def decode_numbers(torch, det, ds, dev):
     for key, model in models:
         prefill_decode(model, toks_d[:4], lens_d[:4], 4, cos_d, sin_d)
         torch.cuda.synchronize()
-        dt = float("inf")
-        for _ in range(2):   # the better of two runs: the job is short enough for host jitter to show
+        runs = []
+        for _ in range(3):   # every run is reported: the job is short enough for host jitter to show
             t0 = time.perf_counter()
             gen, _ = prefill_decode(model, toks_d, lens_d, 128, cos_d, sin_d)
             torch.cuda.synchronize()
-            dt = min(dt, time.perf_counter() - t0)
+            runs.append(time.perf_counter() - t0)
+        dt = float(np.median(runs))
         out["job_64_prompts" + key[len("model_8_layer_step"):]] = {
             "prompts": 64, "prompt_tokens": int(lens.sum()), "new_tokens": 64 * 128, "seconds": round(dt, 4),
+            "seconds_each_run": [round(r, 4) for r in runs], "reported": "median of the runs",
             "generated_tokens_per_s": round(64 * 128 / dt, 1)}
     return out
 

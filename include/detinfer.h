@@ -20,6 +20,10 @@
  *   - Every call returns DET_OK or an error code below and launches nothing on error.  After
  *     DET_EHIP, det_last_hip_error() returns the hipError_t value seen by the calling thread.
  *   - Pointers must be 16-byte aligned (DET_EALIGN otherwise).
+ *   - The library keeps no state between calls, with three exceptions that never reach an output byte:
+ *     the per-thread last HIP error; the per-device address of the fixed scratch array of
+ *     det_attn_decode_static (looked up once); and det_sha256_force_portable(), a process-wide switch
+ *     for tests that selects between two implementations of the same hash.
  */
 #ifndef DETINFER_H
 #define DETINFER_H
@@ -261,7 +265,10 @@ typedef struct det_layer_weights {
 
 size_t det_decoder_layer_workspace_bytes(const det_layer_cfg *cfg /* host */, int B);
 
-/*   w, cfg      host structs holding device pointers / sizes
+/* One decoder layer as a pure function of (weights, x, caches, positions): section 6.1's contract (an
+ * honest re-execution reproduces the bytes) composed from the operations above, which is what lets a
+ * verifier re-run a single layer of a disputed step (section 6.1, layer-granular re-execution).
+ *   w, cfg      host structs holding device pointers / sizes
  *   x_inout     [B, H] bf16, updated in place
  *   kcache, vcache [B, Hkv, Lmax, D] bf16, row positions[b] of every KV head of sequence b written
  *   positions   [B] int32, 0 <= positions[b] < Lmax
