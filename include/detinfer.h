@@ -144,8 +144,10 @@ int det_rmsnorm(const void *x, const void *w, void *y, int M, int H, float eps, 
  *   ws       det_attn_decode_workspace_bytes(B, Hq, D, Lmax) bytes.  After the call it holds the chunk
  *            partials, fp32, nc = ceil(Lmax/256): m_c [B, Hq, nc], then l_c [B, Hq, nc], then the
  *            unnormalised chunk outputs o_c [B, Hq, nc, D]; entries of chunks at or past the sequence's
- *            length are not written.  (Tests read m_c and l_c there and compare them bit for bit with
- *            the reference statistics of the same scores.)
+ *            length are not written, and neither is the o_c of a sequence of at most 256 tokens: its
+ *            single chunk is finished by the first pass with the operations the combination would
+ *            apply to it (det_attn_decode_quant_q8 always takes the second pass).  (Tests read m_c and
+ *            l_c there and compare them bit for bit with the reference statistics of the same scores.)
  *   Shapes: D == 128, Hq % Hkv == 0, Hq/Hkv in {1, 2, 4, 8}.
  */
 size_t det_attn_decode_workspace_bytes(int B, int Hq, int D, int Lmax);

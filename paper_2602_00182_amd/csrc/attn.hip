@@ -112,15 +112,16 @@ __device__ __forceinline__ uint32_t u4_word(const uint4& v)
     return I == 0 ? v.x : (I == 1 ? v.y : (I == 2 ? v.z : v.w));
 }
 
-template <int G, int RT>
+template <int G, int RT, bool DIRECT>
 __global__ __launch_bounds__(256, RT == 1 ? 4 : 2) void attn_tile_kernel(const uint16_t* __restrict__ q,
                                                         const uint16_t* __restrict__ kcache,
                                                         const uint16_t* __restrict__ vcache,
                                                         const int32_t* __restrict__ seqlens,
                                                         const int32_t* __restrict__ slots,
                                                         float* __restrict__ ws_m, float* __restrict__ ws_l,
-                                                        float* __restrict__ ws_o, int R, int Hq, int Hkv, int Lmax,
-                                                        int ncmax, float scale, int len_offset)
+                                                        float* __restrict__ ws_o, uint16_t* __restrict__ out, int R,
+                                                        int Hq, int Hkv, int Lmax, int ncmax, float scale,
+                                                        int len_offset)
 {
     constexpr int NP = G * RT;             // pairs (row, head) of the workgroup
     constexpr int CBK = (NP + 15) / 16;    // blocks of sixteen pairs
@@ -128,6 +129,7 @@ __global__ __launch_bounds__(256, RT == 1 ? 4 : 2) void attn_tile_kernel(const u
     static_assert((G & (G - 1)) == 0 && CBK <= 4, "pair layout");
     __shared__ __align__(16) float sc[NP * kChunk];  // scores, then e_j
     __shared__ uint4 vt[128 * 16];                   // V^T of half a chunk: [d][token], 32 KB
+    __shared__ float mc_s[NP], lc_s[NP];             // the pairs' chunk statistics (DIRECT only)
     const int c = blockIdx.x, hgrp = blockIdx.y, tile = blockIdx.z;
     const int kvh = (hgrp * G) / (Hq / Hkv);
     const int t0 = c * kChunk;
@@ -149,6 +151,17 @@ __global__ __launch_bounds__(256, RT == 1 ? 4 : 2) void attn_tile_kernel(const u
         slot[tid] = sl;
     }
     __syncthreads();
+    if constexpr (DIRECT) {
+        // rows without any token get zeros, from the workgroups of chunk 0 (there is no second pass to do it)
+        if (c == 0) {
+#pragma unroll
+            for (int ri = 0; ri < RT; ++ri) {
+                const int r = tile * RT + ri;
+                if (r < R && len[ri] <= 0)
+                    for (int i = tid; i < G * kD; i += 256) out[((size_t)r * Hq + (size_t)hgrp * G) * kD + i] = 0;
+            }
+        }
+    }
     bool any = false;
 #pragma unroll
     for (int ri = 0; ri < RT; ++ri) any = any || len[ri] > t0;
@@ -280,6 +293,10 @@ __global__ __launch_bounds__(256, RT == 1 ? 4 : 2) void attn_tile_kernel(const u
                     const size_t part = ((size_t)(tile * RT + ri) * Hq + (size_t)hgrp * G + p % G) * ncmax + c;
                     ws_m[part] = m_c;
                     ws_l[part] = l_c;
+                    if constexpr (DIRECT) {
+                        mc_s[p] = m_c;
+                        lc_s[p] = l_c;
+                    }
                 }
             }
         }
@@ -335,14 +352,34 @@ __global__ __launch_bounds__(256, RT == 1 ? 4 : 2) void attn_tile_kernel(const u
 
         // lane holds O[d = 16*(db0+u) + 4g + v][pair pp]
         bool mine = false;
-        int my_row = 0;
+        int my_row = 0, my_len = 0;
 #pragma unroll
         for (int ri = 0; ri < RT; ++ri)
             if (pp < NP && pp / G == ri && ((mask >> ri) & 1u)) {
                 mine = true;
                 my_row = tile * RT + ri;
+                my_len = len[ri];
             }
-        if (mine) {
+        if (DIRECT && mine && my_len <= kChunk) {
+            // The row has this one chunk: what the second pass would compute from the single partial, computed
+            // here with the same operations (m = m_c; w = det_expf(m_c - m); L = 0 + w*l_c; O = 0 + w*O_c;
+            // out = bf16(O / L)), and the partial output is not written.
+            const float w = det_expf(mc_s[pp] - mc_s[pp]);
+            const float wl = w * lc_s[pp];
+            const float L = 0.0f + wl;
+            uint16_t* orow = out + ((size_t)my_row * Hq + (size_t)hgrp * G + pp % G) * kD + 4 * g;
+#pragma unroll
+            for (int u = 0; u < DPW; ++u) {
+                float y[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float wo = w * acc[u][v];
+                    const float O = 0.0f + wo;
+                    y[v] = O / L;
+                }
+                *reinterpret_cast<uint2*>(orow + 16 * (db0 + u)) = make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
+            }
+        } else if (mine) {
             const size_t part = ((size_t)my_row * Hq + (size_t)hgrp * G + pp % G) * ncmax + c;
             float* op = ws_o + part * kD + 4 * g;
 #pragma unroll
@@ -373,7 +410,7 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const int32_t* __rest
                                                            const float* __restrict__ ws_o,
                                                            void* __restrict__ out, int Hq, int Lmax,
                                                            int ncmax, int len_offset, float* __restrict__ scales,
-                                                           int ldd)
+                                                           int ldd, int first_pass_wrote_short_rows)
 {
     __shared__ float s_w[128];
     __shared__ float s_l[128];
@@ -400,6 +437,7 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const int32_t* __rest
             if ((d & 63) == 0) scales[(size_t)(2 * h + (d >> 6)) * ldd + b] = df;
         }
     };
+    if (first_pass_wrote_short_rows && len <= kChunk) return;  // rows of at most one chunk are complete (uniform)
     if (len <= 0) {  // uniform over the workgroup
         store(0);
         return;
@@ -592,14 +630,22 @@ int det::attn_decode_impl(const void* q, const void* kcache, const void* vcache,
     const uint16_t* qq = static_cast<const uint16_t*>(q);
     const uint16_t* kk = static_cast<const uint16_t*>(kcache);
     const uint16_t* vv = static_cast<const uint16_t*>(vcache);
-#define DET_LAUNCH_ATTN(GG)                                                                                       \
-    do {                                                                                                          \
-        if (tiled)                                                                                                \
-            hipLaunchKernelGGL((attn_tile_kernel<GG, 8>), grid, dim3(256), 0, s, qq, kk, vv, seqlens, slots, ws_m, \
-                               ws_l, ws_o, B, Hq, Hkv, Lmax, ncmax, scale, len_offset);                          \
-        else                                                                                                      \
-            hipLaunchKernelGGL((attn_tile_kernel<GG, 1>), grid, dim3(256), 0, s, qq, kk, vv, seqlens, slots, ws_m, \
-                               ws_l, ws_o, B, Hq, Hkv, Lmax, ncmax, scale, len_offset);                          \
+    // Without the quantizing second pass, the first pass itself finishes every row of at most one chunk.
+    const bool direct = qscales == nullptr;
+    uint16_t* out16 = static_cast<uint16_t*>(out);
+#define DET_LAUNCH_ATTN2(GG, RTV, DIR)                                                                              \
+    hipLaunchKernelGGL((attn_tile_kernel<GG, RTV, DIR>), grid, dim3(256), 0, s, qq, kk, vv, seqlens, slots, ws_m, ws_l, \
+                       ws_o, out16, B, Hq, Hkv, Lmax, ncmax, scale, len_offset)
+#define DET_LAUNCH_ATTN(GG)                                \
+    do {                                                   \
+        if (tiled && direct)                               \
+            DET_LAUNCH_ATTN2(GG, 8, true);                 \
+        else if (tiled)                                    \
+            DET_LAUNCH_ATTN2(GG, 8, false);                \
+        else if (direct)                                   \
+            DET_LAUNCH_ATTN2(GG, 1, true);                 \
+        else                                               \
+            DET_LAUNCH_ATTN2(GG, 1, false);                \
     } while (0)
     switch (split_heads ? 1 : G) {
         case 1: DET_LAUNCH_ATTN(1); break;
@@ -608,15 +654,16 @@ int det::attn_decode_impl(const void* q, const void* kcache, const void* vcache,
         default: DET_LAUNCH_ATTN(8); break;
     }
 #undef DET_LAUNCH_ATTN
+#undef DET_LAUNCH_ATTN2
     int rc = check_launch();
     if (rc != DET_OK) return rc;
     if (qscales) {
         if (!aligned16(qscales)) return DET_EALIGN;
         hipLaunchKernelGGL(attn_combine_kernel<true>, dim3(Hq, B), dim3(128), 0, s, seqlens, ws_m, ws_l, ws_o, out, Hq,
-                           Lmax, ncmax, len_offset, static_cast<float*>(qscales), (B + 3) & ~3);
-    } else {
+                           Lmax, ncmax, len_offset, static_cast<float*>(qscales), (B + 3) & ~3, 0);
+    } else if (ncmax > 1) {  // with one chunk at most, every row is already complete
         hipLaunchKernelGGL(attn_combine_kernel<false>, dim3(Hq, B), dim3(128), 0, s, seqlens, ws_m, ws_l, ws_o, out, Hq,
-                           Lmax, ncmax, len_offset, nullptr, 0);
+                           Lmax, ncmax, len_offset, nullptr, 0, 1);
     }
     return check_launch();
 }
