@@ -35,10 +35,17 @@ N_SETS = 3
 PEAK_MFMA_TFLOPS = 2500.0   # MI355X dense bf16
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 DOMINANT = (4096, 28672)    # the launch that moves most of the step's bytes (gemm_kernel<8,144,0,8,4,8>)
-# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a
-# plain copy kernel (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000): 238.78 MB read + 3.26 MB written, averaged
-# over the nine M of the sweep (summary under profiles/).
-DOMINANT_TRAFFIC_BYTES = 241.98e6
+def dominant_traffic_bytes():
+    """HBM bytes per launch of the dominant kernel as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    (scaled by a plain copy kernel of known size): read from the committed summary of those runs,
+    profiles/gemm_kernel_llama_sweep.md.  None if the summary is missing (the bench never guesses it)."""
+    import re
+    try:
+        text = open(os.path.join(ROOT, "profiles", "gemm_kernel_llama_sweep.md")).read()
+    except OSError:
+        return None
+    m = re.search(r"measured HBM traffic ([0-9.]+) MB per launch", text)
+    return float(m.group(1)) * 1e6 if m else None
 
 
 def gemm_flops(M, N, K):
@@ -224,7 +231,7 @@ def main():
     achieved = dom_bytes / dom_avg_ms / 1e6
     roofline = {"bound": "hbm", "kernel": "det::gemm_kernel<8,144,0,8,4,8> (K=4096, N=28672, M=1..256)",
                 "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": DOMINANT_TRAFFIC_BYTES,
+                "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": dominant_traffic_bytes(),
                 "avg_launch_us": round(dom_avg_ms * 1e3, 2), "bytes_per_launch": int(dom_bytes),
                 "per_shape": per_shape}
 
@@ -347,6 +354,16 @@ def measured_peaks(torch, dev, roofline):
 
     copy_ms = timed(lambda: b.copy_(a))
     read_ms = timed(lambda: f.sum())
+    # LDS fill rate of a compute unit for L2-resident data (the library's probe kernels): 256 workgroups, one per
+    # compute unit, all streaming the same 2 MB
+    import paper_2602_00182_amd as det
+    small = torch.ones(2 << 20, dtype=torch.uint8, device=dev)
+    sink = torch.zeros(4, dtype=torch.uint8, device=dev)
+    fill = {}
+    for path, name in ((0, "registers_then_lds_store"), (1, "lds_dma")):
+        iters = 2000
+        ms = timed(lambda: det.det_probe_lds_fill(small, path, 256, iters, sink), reps=3)
+        fill[name + "_bytes_per_clock_per_cu_at_2p4ghz"] = round(256 * iters * 32768 / ms / 1e6 / 256 / 2.4, 1)
     copy_gbs = 2 * n / copy_ms / 1e6
     read_gbs = n / read_ms / 1e6
     best = max(copy_gbs, read_gbs)
@@ -354,6 +371,7 @@ def measured_peaks(torch, dev, roofline):
     torch.cuda.empty_cache()
     return {"copy_1GiB_gbs": round(copy_gbs, 1), "read_1GiB_gbs": round(read_gbs, 1),
             "dominant_kernel_frac_of_measured": round(roofline["achieved"] / best, 4),
+            "lds_fill_l2_resident": fill,
             "note": "device-to-device copy counts read + written bytes; the read pass is torch's sum over fp32"}
 
 

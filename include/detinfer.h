@@ -413,6 +413,13 @@ int det_commit_sha256(const void *prompt, size_t prompt_bytes, const void *logit
  * CPU has SHA instructions (process-wide). */
 int det_sha256_force_portable(int on);
 
+/* Measurement aid (not part of the decode path): `workgroups` workgroups of 256 threads each stream the
+ * buffer src (src_bytes, at most 1 GiB, every workgroup the same bytes, so that they come from L2) into
+ * their LDS `iters` times 32 KB, path 0 through registers and LDS stores, path 1 with LDS-DMA loads.
+ * Moves workgroups * iters * 32768 bytes; the caller times it.  sink: 4 bytes, never written in practice. */
+int det_probe_lds_fill(const void *src, size_t src_bytes, int path, int workgroups, int iters, void *sink,
+                       void *stream);
+
 /* Build identification: target architecture, ROCm version the library was built with, and the
  * kernel-configuration revision (echoes the paper's `system_fingerprint` response field, section
  * 7.1).  Static storage; host pointer. */

@@ -52,6 +52,7 @@ SIGNATURES = {
                                _vp, _sz, _i, _vp]),
     "det_decoder_layer_rows": (_i, [C.POINTER(LayerWeights), C.POINTER(LayerCfg), _vp, _vp, _vp, _vp, _vp, _vp, _vp,
                                     _vp, _sz, _i, _vp]),
+    "det_probe_lds_fill": (_i, [_vp, _sz, _i, _i, _i, _vp, _vp]),
     "det_next_token": (_i, [_vp, _i, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _vp]),
     "det_decode_advance": (_i, [_vp, _vp, _i, _vp, _vp, _i, _vp]),
     "det_qgemm_packed_w_bytes": (_sz, [_i, _i]),

@@ -11,7 +11,7 @@ import torch
 from ._lib import LayerCfg, LayerWeights, Sha256Ctx, lib
 
 __all__ = [
-    "DetError", "det_gemm_bf16", "det_gemm_bf16_fixed_tile", "det_gemm_packed_b_bytes", "det_gemm_pack_b", "det_gemm_bf16_residual",
+    "DetError", "det_gemm_bf16", "det_gemm_bf16_fixed_tile", "det_probe_lds_fill", "det_gemm_packed_b_bytes", "det_gemm_pack_b", "det_gemm_bf16_residual",
     "det_gemm_pack_gate_up", "det_gemm_swiglu_bf16", "pack_gate_up", "det_rmsnorm",
     "det_attn_decode_workspace_bytes", "det_attn_decode", "det_attn_decode_static", "det_attn_decode_rows", "det_decoder_layer_rows",
     "det_softmax_f32", "det_argmax", "det_sample", "det_rope",
@@ -293,6 +293,12 @@ def det_gemm_bf16(A: torch.Tensor, B_packed: torch.Tensor, C_out: torch.Tensor, 
     ldc = C_out.stride(0) if M > 1 else max(C_out.stride(0), N)
     _check(_entry, getattr(lib(), _entry)(_ptr(A, torch.bfloat16), lda, _contig(B_packed), _ptr(C_out),
                                           ldc, M, N, K, od, _stream(stream)))
+
+
+def det_probe_lds_fill(src: torch.Tensor, path: int, workgroups: int, iters: int, sink: torch.Tensor, stream=None) -> None:
+    """Measurement aid: see the header.  src: any contiguous device tensor; sink: at least 4 bytes."""
+    _check("det_probe_lds_fill", lib().det_probe_lds_fill(_contig(src), src.numel() * src.element_size(), path,
+                                                           workgroups, iters, _contig(sink), _stream(stream)))
 
 
 def det_gemm_bf16_fixed_tile(A: torch.Tensor, B_packed: torch.Tensor, C_out: torch.Tensor, N: int, K: int,

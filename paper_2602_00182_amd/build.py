@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdetinfer.so")
-SOURCES = ["api.hip", "gemm.hip", "reduce.hip", "attn.hip", "elementwise.hip", "layer.hip", "sample.hip", "commit.hip", "qgemm.hip"]
+SOURCES = ["api.hip", "gemm.hip", "reduce.hip", "attn.hip", "elementwise.hip", "layer.hip", "sample.hip", "commit.hip", "qgemm.hip", "probe.hip"]
 
 # -ffp-contract=off: a fused multiply-add exists only where the source writes fmaf().
 # -packed-fp32-ops off: packed fp32 VALU forms are not used by this library.

@@ -5,12 +5,13 @@ has its own oracle test; this one checks the composition (section 6.6's loop as 
 6.1): which token feeds which step, positions, the cache rows a step reads, the last-row gather after
 prefill, the lm_head and the token selection.
 
-Bars.  Logits (fp32 from the GPU, fp64 reference): |err| <= 2^-8 |ref| + 2^-6 rms(ref row).  A logit is a
+Bars.  Logits (fp32 from the GPU, fp64 reference): |err| <= 2^-8 |ref| + 2^-9 rms(ref row).  A logit is a
 256-term product of the normalised final hidden row; the two sides' hidden rows differ only where one of
 the roundings on the way landed on the other side of a bf16 boundary (one ulp, 2^-7 relative, of one
-element), which moves a logit by about 2^-7 |xn_k w_kj| ~ 2^-11 rms(row); such flips accumulate over layers
-and, through the KV cache, over steps, so the bar leaves room for about a thousand of them; an indexing
-mistake (wrong position, row, token or weight orientation) moves logits by about rms(row) itself.  Tokens:
+element), which moves a logit by about 2^-7 |xn_k w_kj| ~ 2^-11 rms(row).  On this small model no such flip
+happens with the committed seeds (measured and printed: max err = 2^-20 rms, fp32 against fp64
+accumulation only); the bar leaves room for a handful of flips, while an indexing mistake (wrong position,
+row, token or weight orientation) moves logits by about rms(row) itself, five hundred times the bar.  Tokens:
 equal to the oracle's argmax wherever the oracle's top-2 margin exceeds twice that bar."""
 import math
 
@@ -74,7 +75,7 @@ def _oracle_run(weights_h, toks, lens, gen):
 def _check(ref_logits_bt, gpu_logits, gpu_token, what):
     """ref_logits_bt, gpu_logits: [V]; the bar of the module docstring."""
     rms = np.sqrt((ref_logits_bt ** 2).mean())
-    bar = 2.0 ** -8 * np.abs(ref_logits_bt) + 2.0 ** -6 * rms
+    bar = 2.0 ** -8 * np.abs(ref_logits_bt) + 2.0 ** -9 * rms
     err = np.abs(gpu_logits.astype(np.float64) - ref_logits_bt)
     assert (err <= bar).all(), (what, (err / bar).max())
     order = np.argsort(-ref_logits_bt, kind="stable")
@@ -82,6 +83,7 @@ def _check(ref_logits_bt, gpu_logits, gpu_token, what):
     decided = margin > 2 * bar.max()
     if decided:
         assert gpu_token == order[0], (what, gpu_token, order[0])
+    _check.worst_rel_rms = max(getattr(_check, "worst_rel_rms", 0.0), float((err / rms).max()))
     return (err / bar).max(), bool(decided)
 
 
@@ -104,7 +106,7 @@ def test_decode_loop_against_oracle_model(model, weights_h):
             t = int(l) - 1 + j
             r, dec = _check(ref[t, b], kept[t][b].cpu().numpy(), gen[b, j], f"greedy b={b} step={t}")
             worst, decided = max(worst, r), decided + dec
-    print(f"[measured] decode loop vs oracle model: max err/bar = {worst:.3f}, "
+    print(f"[measured] decode loop vs oracle model: max err/bar = {worst:.5f}, max err/rms(row) = 2^{math.log2(max(_check.worst_rel_rms, 1e-30)):.2f}, "
           f"tokens decided by margin: {decided} of {len(lens) * N_NEW}", flush=True)
     assert decided >= len(lens) * N_NEW // 2
     step("tiny model: one-pass prefill + decode")
