@@ -577,13 +577,28 @@ def cpu_baseline_other_legs(ds):
 
 
 def _cpu_model():
+    """Model string of the host CPU; virtual machines often report only the family name, so the family /
+    model / stepping numbers and the number of logical CPUs this process may use are appended."""
+    name, fam, model, step = "unknown", None, None, None
     try:
         for line in open("/proc/cpuinfo"):
-            if line.startswith("model name"):
-                return line.split(":", 1)[1].strip()
+            key, _, val = line.partition(":")
+            key, val = key.strip(), val.strip()
+            if key == "model name" and name == "unknown":
+                name = val
+            elif key == "cpu family" and fam is None:
+                fam = val
+            elif key == "model" and model is None:
+                model = val
+            elif key == "stepping" and step is None:
+                step = val
     except OSError:
         pass
-    return "unknown"
+    try:
+        ncpu = len(os.sched_getaffinity(0))
+    except AttributeError:
+        ncpu = os.cpu_count()
+    return f"{name} (family {fam}, model {model}, stepping {step}; {ncpu} logical CPUs available to this process)"
 
 
 def bit_identical(torch, det, weights, X):
