@@ -313,7 +313,7 @@ def probe(torch, det, ds, dev, spec):
         (B,) = nums
         H, Hq, Hkv, D, F, Lmax = 4096, 32, 8, 128, 14336, 2048
         g = lambda i, shape, std=0.02, mean=0.0: ds.normal_bf16_torch(ds.tensor_seed(4, i), shape, std, mean, dev)
-        w = det.layer_weights(g(0, (H,), 0.0, 1.0), det.pack_weight(g(1, (H, (Hq + 2 * Hkv) * D))),
+        w = det.layer_weights(g(0, (H,), 0.0, 1.0), det.pack_qkv(g(1, (H, (Hq + 2 * Hkv) * D)), Hq, Hkv, D),
                               det.pack_weight(g(2, (Hq * D, H))), g(3, (H,), 0.0, 1.0),
                               det.pack_gate_up(g(4, (H, 2 * F))), det.pack_weight(g(5, (F, H))))
         cfg = det.layer_cfg(H, Hq, Hkv, D, F, Lmax, 1e-5, scale)
@@ -706,7 +706,7 @@ def decode_numbers(torch, det, ds, dev):
     scale = float(np.float32(1.0 / math.sqrt(128.0)))
     s = ds.tensor_seed(4, 0)
     g = lambda i, shape, std=0.02, mean=0.0: ds.normal_bf16_torch(s + i, shape, std, mean, dev)
-    packed = [g(0, (H,), 0.0, 1.0), det.pack_weight(g(1, (H, (Hq + 2 * Hkv) * D))), det.pack_weight(g(2, (Hq * D, H))),
+    packed = [g(0, (H,), 0.0, 1.0), det.pack_qkv(g(1, (H, (Hq + 2 * Hkv) * D)), Hq, Hkv, D), det.pack_weight(g(2, (Hq * D, H))),
               g(3, (H,), 0.0, 1.0), det.pack_gate_up(g(4, (H, 2 * F))), det.pack_weight(g(5, (F, H)))]
     struct = det.layer_weights(*packed)
     # the same layer with 4-bit weights and 8-bit activations (det_qdecoder_layer)

@@ -100,12 +100,26 @@ int det_gemm_pack_b(const void *B_kn, void *B_packed, int N, int K, void *stream
  *   F up columns, with gate_j and up_j made neighbours, for det_gemm_swiglu_bf16.  F % 8 == 0.
  * det_gemm_swiglu_bf16: Y[M, F] = det_swiglu( g, u ) with [g | u] = det_gemm_bf16(A, [Wgate | Wup])
  *   rounded to bf16 first.  B_gate_up is the output of det_gemm_pack_gate_up; ldy >= F, ldy % 4 == 0.
+ * det_gemm_pack_qkv: packs a [K, (Hq+2Hkv) D] bf16 matrix whose columns are Hq query heads, Hkv key
+ *   heads and Hkv value heads of D = 128 columns each, with the columns d and d + D/2 of every head
+ *   (a rotation pair of det_rope) made neighbours, for det_gemm_qkv_rope_append.
+ * det_gemm_qkv_rope_append: the layer's fused projection.  With qkv = det_gemm_bf16(A, Wqkv) (bf16),
+ *   row i at position p = positions[i] (clamped to 0..Lmax-1) and cache slot s = slots[i] (slots NULL:
+ *   s = i): qbuf[i] = det_rope(query heads of qkv[i], p); kcache[s][:, p, :] = det_rope(key heads, p);
+ *   vcache[s][:, p, :] = value heads.  Exactly the bytes of those three steps; qkv itself is never
+ *   stored.  qbuf [M, Hq, D] bf16; caches [S, Hkv, Lmax, D] bf16; rope_cos/sin [Lmax, D/2] fp32,
+ *   16-byte aligned; no two rows of one call may name the same (slot, position).  D must be 128.
  */
 int det_gemm_bf16_residual(const void *A, int lda, const void *B_packed, const void *R, int ldr,
                            void *C, int ldc, int M, int N, int K, void *stream);
 int det_gemm_pack_gate_up(const void *B_kn, void *B_packed, int F, int K, void *stream);
 int det_gemm_swiglu_bf16(const void *A, int lda, const void *B_gate_up, void *Y, int ldy, int M,
                          int F, int K, void *stream);
+int det_gemm_pack_qkv(const void *B_kn, void *B_packed, int Hq, int Hkv, int D, int K, void *stream);
+int det_gemm_qkv_rope_append(const void *A, int lda, const void *B_qkv, void *qbuf, void *kcache,
+                             void *vcache, const int32_t *positions, const int32_t *slots,
+                             const float *rope_cos, const float *rope_sin, int M, int Hq, int Hkv,
+                             int D, int Lmax, int K, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
  * RMSNorm (section 6.5, invariant 2: canonical tree reduction; tree of Fig. "kernel_tree").
@@ -258,7 +272,8 @@ typedef struct det_layer_cfg {
 
 typedef struct det_layer_weights {
     const void *w_norm1; /* [H] bf16 */
-    const void *wqkv;    /* packed [K=H, N=(Hq+2Hkv)D]; columns: q heads, k heads, v heads */
+    const void *wqkv;    /* [K=H, N=(Hq+2Hkv)D] (columns: q heads, k heads, v heads) packed by
+                          * det_gemm_pack_qkv */
     const void *wo;      /* packed [K=Hq*D, N=H] */
     const void *w_norm2; /* [H] bf16 */
     const void *wgu;     /* [K=H, N=2F] (columns: gate, up) packed by det_gemm_pack_gate_up */

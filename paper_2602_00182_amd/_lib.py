@@ -35,6 +35,8 @@ SIGNATURES = {
     "det_gemm_bf16_residual": (_i, [_vp, _i, _vp, _vp, _i, _vp, _i, _i, _i, _i, _vp]),
     "det_gemm_pack_gate_up": (_i, [_vp, _vp, _i, _i, _vp]),
     "det_gemm_swiglu_bf16": (_i, [_vp, _i, _vp, _vp, _i, _i, _i, _i, _vp]),
+    "det_gemm_pack_qkv": (_i, [_vp, _vp, _i, _i, _i, _i, _vp]),
+    "det_gemm_qkv_rope_append": (_i, [_vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp]),
     "det_rmsnorm": (_i, [_vp, _vp, _vp, _i, _i, _f, _vp]),
     "det_attn_decode_workspace_bytes": (_sz, [_i, _i, _i, _i]),
     "det_attn_decode": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _sz, _i, _i, _i, _i, _i, _f, _vp]),

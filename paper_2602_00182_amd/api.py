@@ -12,7 +12,8 @@ from ._lib import LayerCfg, LayerWeights, Sha256Ctx, lib
 
 __all__ = [
     "DetError", "det_gemm_bf16", "det_gemm_bf16_fixed_tile", "det_probe_lds_fill", "det_gemm_packed_b_bytes", "det_gemm_pack_b", "det_gemm_bf16_residual",
-    "det_gemm_pack_gate_up", "det_gemm_swiglu_bf16", "pack_gate_up", "det_rmsnorm",
+    "det_gemm_pack_gate_up", "det_gemm_swiglu_bf16", "pack_gate_up", "det_gemm_pack_qkv", "pack_qkv",
+    "det_gemm_qkv_rope_append", "det_rmsnorm",
     "det_attn_decode_workspace_bytes", "det_attn_decode", "det_attn_decode_static", "det_attn_decode_rows", "det_decoder_layer_rows",
     "det_softmax_f32", "det_argmax", "det_sample", "det_rope",
     "det_swiglu", "det_residual_add", "det_embed_gather", "det_decoder_layer_workspace_bytes",
@@ -323,6 +324,45 @@ def pack_gate_up(B_kn: torch.Tensor, stream=None) -> torch.Tensor:
     out = torch.empty(N2 * K, dtype=torch.bfloat16, device=B_kn.device)
     det_gemm_pack_gate_up(B_kn, out, stream)
     return out
+
+
+def det_gemm_pack_qkv(B_kn: torch.Tensor, B_packed: torch.Tensor, Hq: int, Hkv: int, D: int = 128, stream=None) -> None:
+    K, N = B_kn.shape
+    if N != (Hq + 2 * Hkv) * D or B_packed.numel() * B_packed.element_size() < 2 * N * K:
+        raise ValueError("bad fused query/key/value weight")
+    _check("det_gemm_pack_qkv", lib().det_gemm_pack_qkv(_contig(B_kn, torch.bfloat16), _contig(B_packed), Hq, Hkv, D, K,
+                                                         _stream(stream)))
+
+
+def pack_qkv(B_kn: torch.Tensor, Hq: int, Hkv: int, D: int = 128, stream=None) -> torch.Tensor:
+    """Allocates and fills the packed form of a [K, (Hq+2Hkv)D] weight for det_gemm_qkv_rope_append (the
+    form det_decoder_layer takes as wqkv)."""
+    K, N = B_kn.shape
+    if det_gemm_packed_b_bytes(N, K) == 0:
+        raise DetError("det_gemm_packed_b_bytes", 2)
+    out = torch.empty(N * K, dtype=torch.bfloat16, device=B_kn.device)
+    det_gemm_pack_qkv(B_kn, out, Hq, Hkv, D, stream)
+    return out
+
+
+def det_gemm_qkv_rope_append(A, B_qkv, qbuf, kcache, vcache, positions, slots, rope_cos, rope_sin, stream=None) -> None:
+    """The layer's fused projection: A [M, K] times the weight of pack_qkv, query heads rotated into qbuf
+    [M, Hq, D], key heads rotated and value heads copied into caches [S, Hkv, Lmax, D] at (slot, position).
+    slots None: row i uses slot i."""
+    M, K = A.shape
+    _, Hq, D = qbuf.shape
+    _, Hkv, Lmax, _ = kcache.shape
+    if qbuf.shape[0] != M or vcache.shape != kcache.shape or A.stride(1) != 1 or positions.numel() != M:
+        raise ValueError("bad fused projection operands")
+    if slots is not None and slots.numel() != M:
+        raise ValueError("bad slots")
+    if rope_cos.shape != (Lmax, D // 2) or rope_sin.shape != (Lmax, D // 2):
+        raise ValueError("bad rope tables")
+    _check("det_gemm_qkv_rope_append", lib().det_gemm_qkv_rope_append(
+        _ptr(A, torch.bfloat16), _ld(A, K), _contig(B_qkv), _contig(qbuf, torch.bfloat16),
+        _contig(kcache, torch.bfloat16), _contig(vcache, torch.bfloat16), _contig(positions, torch.int32),
+        None if slots is None else _contig(slots, torch.int32), _contig(rope_cos, torch.float32),
+        _contig(rope_sin, torch.float32), M, Hq, Hkv, D, Lmax, K, _stream(stream)))
 
 
 def _ld(t: torch.Tensor, cols: int) -> int:

@@ -131,6 +131,62 @@ constexpr int kEpiStore = 0, kEpiResidual = 1, kEpiSwiglu = 2;
 // kEpiSwigluQuant (quantized GEMM with 128-column tiles only): the SwiGLU epilogue's bf16 values written as
 // their 8-bit block quantization; a tile row holds exactly one block of 64 outputs.
 constexpr int kEpiSwigluQuant = 3;
+// kEpiRopeAppend (bf16 GEMM of the fused query/key/value projection): the weight columns of every
+// 128-wide head are packed so that a rotation pair (d, d + 64) sits in adjacent columns 2d, 2d + 1;
+// a lane's four columns are two pairs, which it rotates at the row's position and writes straight
+// to where the layer wants them: query heads to qbuf, key heads (rotated) and value heads (as they
+// are) to the row's cache slot at that position.  The bytes of the plain GEMM followed by the
+// rotation and the append; C is not written.
+constexpr int kEpiRopeAppend = 4;
+
+struct gemm_rope_args {
+    const int32_t* pos = nullptr;    // [M] position of each row (clamped to 0..Lmax-1)
+    const int32_t* slots = nullptr;  // [M] cache slot of each row, or null: row b uses slot b
+    const float* cos_t = nullptr;    // [Lmax, 64]
+    const float* sin_t = nullptr;
+    uint16_t* qbuf = nullptr;    // [M, Hq, 128]
+    uint16_t* kcache = nullptr;  // [S, Hkv, Lmax, 128]
+    uint16_t* vcache = nullptr;
+    int Hq = 0, Hkv = 0, Lmax = 0;
+};
+
+// Rotate-half pair (i, i + D/2):
+//   y_lo = bf16( fma(-x_hi, sin, x_lo*cos) ),  y_hi = bf16( fma(x_lo, sin, x_hi*cos) )
+__device__ __forceinline__ void rope_pair(uint16_t xlo, uint16_t xhi, float c, float s, uint16_t& ylo,
+                                          uint16_t& yhi)
+{
+    const float lo = bf16_to_f32(xlo), hi = bf16_to_f32(xhi);
+    const float a = lo * c;
+    const float b = hi * c;
+    ylo = f32_to_bf16_rne(__builtin_fmaf(-hi, s, a));
+    yhi = f32_to_bf16_rne(__builtin_fmaf(lo, s, b));
+}
+
+// kEpiRopeAppend for one lane: packed columns n..n+3 of head n / 128 are the pairs i0 = (n % 128) / 2
+// and i0 + 1; p and slot are the row's (clamped) position and cache slot.
+__device__ __forceinline__ void gemm_epilogue_rope_append(const float (&v)[4], const gemm_rope_args& ra, size_t row,
+                                                          int p, int slot, int n)
+{
+    constexpr int D = 128, half = 64;
+    const int head = n >> 7, i0 = (n & (D - 1)) >> 1;
+    uint16_t x[4], lo0, hi0, lo1, hi1;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) x[e] = f32_to_bf16_rne(v[e]);
+    uint16_t* dst;
+    if (head < ra.Hq + ra.Hkv) {
+        const float2 c = *reinterpret_cast<const float2*>(ra.cos_t + (size_t)p * half + i0);
+        const float2 s = *reinterpret_cast<const float2*>(ra.sin_t + (size_t)p * half + i0);
+        rope_pair(x[0], x[1], c.x, s.x, lo0, hi0);
+        rope_pair(x[2], x[3], c.y, s.y, lo1, hi1);
+        dst = head < ra.Hq ? ra.qbuf + (row * ra.Hq + head) * D
+                           : ra.kcache + (((size_t)slot * ra.Hkv + (head - ra.Hq)) * ra.Lmax + p) * D;
+    } else {
+        lo0 = x[0], hi0 = x[1], lo1 = x[2], hi1 = x[3];
+        dst = ra.vcache + (((size_t)slot * ra.Hkv + (head - ra.Hq - ra.Hkv)) * ra.Lmax + p) * D;
+    }
+    *reinterpret_cast<uint32_t*>(dst + i0) = lo0 | ((uint32_t)lo1 << 16);
+    *reinterpret_cast<uint32_t*>(dst + half + i0) = hi0 | ((uint32_t)hi1 << 16);
+}
 
 __device__ __forceinline__ float silu_mul(float gate, float up)
 {

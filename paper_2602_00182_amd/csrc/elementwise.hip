@@ -5,18 +5,6 @@
 
 namespace det {
 
-// Rotate-half pair (i, i + D/2):
-//   y_lo = bf16( fma(-x_hi, sin, x_lo*cos) ),  y_hi = bf16( fma(x_lo, sin, x_hi*cos) )
-__device__ __forceinline__ void rope_pair(uint16_t xlo, uint16_t xhi, float c, float s, uint16_t& ylo,
-                                          uint16_t& yhi)
-{
-    const float lo = bf16_to_f32(xlo), hi = bf16_to_f32(xhi);
-    const float a = lo * c;
-    const float b = hi * c;
-    ylo = f32_to_bf16_rne(__builtin_fmaf(-hi, s, a));
-    yhi = f32_to_bf16_rne(__builtin_fmaf(lo, s, b));
-}
-
 // Grid (row); x, y: [R, nh, D] with row strides.
 __global__ __launch_bounds__(256) void rope_kernel(const uint16_t* __restrict__ x, int ldx,
                                                    uint16_t* __restrict__ y, int ldy,

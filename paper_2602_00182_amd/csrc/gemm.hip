@@ -206,7 +206,8 @@ template <int CB, int RINGB, int EPI, int NW, int NL, int PCB>
 __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __restrict__ A, int lda,
                                                           const uint4* __restrict__ Bp, void* C, int ldc,
                                                           const uint16_t* R, int ldr, int K, int out_f32,
-                                                          gemm_tile_plan plan_full, gemm_tile_plan plan_tail)
+                                                          gemm_tile_plan plan_full, gemm_tile_plan plan_tail,
+                                                          gemm_rope_args ra)
 {
     static_assert(RINGB >= 4 * (CB + 16), "the ring must hold two stages of the largest tile");
     static_assert(NL >= 1, "a tile of NW row blocks or more needs waves that only load");
@@ -574,12 +575,21 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
             const int rowl = 16 * (wave + NW * r) + lr;
             if (rowl < mrem) {
                 const size_t row = (size_t)(m0 + rowl);
+                int p = 0, slot = 0;
+                if constexpr (EPI == kEpiRopeAppend) {
+                    p = ra.pos[row];
+                    p = p < 0 ? 0 : (p >= ra.Lmax ? ra.Lmax - 1 : p);
+                    slot = ra.slots ? ra.slots[row] : (int)row;
+                }
 #pragma unroll
                 for (int j = 0; j < CB; ++j) {
                     const int n = n0 + 16 * j + 4 * g;
                     const f32x4 a4 = acc[r][j];
                     const float v[4] = {a4[0], a4[1], a4[2], a4[3]};
-                    gemm_epilogue_store<EPI>(v, C, ldc, R, ldr, row, n, out_f32);
+                    if constexpr (EPI == kEpiRopeAppend)
+                        gemm_epilogue_rope_append(v, ra, row, p, slot, n);
+                    else
+                        gemm_epilogue_store<EPI>(v, C, ldc, R, ldr, row, n, out_f32);
                 }
             }
         }
@@ -601,9 +611,11 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
 
 // One thread per 16 bytes of the packed matrix: gathers 8 K-consecutive elements of one column.
 // gate_up_f > 0: packed column 2j is logical column j (gate) and 2j+1 is gate_up_f + j (up).
+// rope_d > 0: within every head of rope_d columns, packed columns 2i and 2i+1 are the head's logical
+// columns i and i + rope_d/2 (a rotation pair).
 __global__ __launch_bounds__(256) void gemm_pack_kernel(const uint16_t* __restrict__ Bkn,
                                                         uint4* __restrict__ Bp, int N, int K, int cb,
-                                                        int gate_up_f)
+                                                        int gate_up_f, int rope_d)
 {
     const size_t total = (size_t)N * K / 8;
     const int stage_u4 = cb * 2 * 64;
@@ -619,6 +631,10 @@ __global__ __launch_bounds__(256) void gemm_pack_kernel(const uint16_t* __restri
         const int lane = f & 63;
         int n = tile * 16 * cb + 16 * j + (lane & 15);
         if (gate_up_f > 0) n = (n & 1) ? gate_up_f + (n >> 1) : (n >> 1);
+        if (rope_d > 0) {
+            const int r = n % rope_d;
+            n = n - r + (r >> 1) + ((r & 1) ? rope_d >> 1 : 0);
+        }
         const int k0 = 64 * st + 32 * i + 8 * (lane >> 4);
         uint16_t e[8];
 #pragma unroll
@@ -633,8 +649,9 @@ __global__ __launch_bounds__(256) void gemm_pack_kernel(const uint16_t* __restri
 }
 
 template <int CB, int RINGB, int EPI, int NW, int NL, int PCB = CB>
-static bool launch_gemm(const void* A, int lda, const void* Bp, void* C, int ldc, const void* R, int ldr, int M,
-                        int N, int K, int out_f32, hipStream_t s, int tile_rows = 256)
+static bool launch_gemm(const void* A, int lda, const void* Bp, void* C, int ldc, const void* R, int ldr,
+                        const gemm_rope_args& ra, int M, int N, int K, int out_f32, hipStream_t s,
+                        int tile_rows = 256)
 {
     // tile_rows: a multiple of 16 in 16..256 (the kernel handles 1..16 row blocks of 16 rows)
     dim3 grid(N / (16 * CB), (M + tile_rows - 1) / tile_rows);
@@ -643,7 +660,7 @@ static bool launch_gemm(const void* A, int lda, const void* Bp, void* C, int ldc
     if (!plan_fits_load_counter(full, CB) || !plan_fits_load_counter(tail, CB)) return false;
     hipLaunchKernelGGL((gemm_kernel<CB, RINGB, EPI, NW, NL, PCB>), grid, dim3(64 * (NW + NL)), 0, s,
                        static_cast<const uint16_t*>(A), lda, static_cast<const uint4*>(Bp), C, ldc,
-                       static_cast<const uint16_t*>(R), ldr, K, out_f32, full, tail);
+                       static_cast<const uint16_t*>(R), ldr, K, out_f32, full, tail, ra);
     return true;
 }
 
@@ -652,7 +669,8 @@ static bool launch_gemm(const void* A, int lda, const void* Bp, void* C, int ldc
 // whatever the row count (det_gemm_bf16_fixed_tile).
 template <int EPI>
 static int gemm_dispatch(const void* A, int lda, const void* Bp, void* C, int ldc, const void* R, int ldr, int M,
-                         int N, int K, int f32, hipStream_t s, bool fixed_tile = false)
+                         int N, int K, int f32, hipStream_t s, bool fixed_tile = false,
+                         const gemm_rope_args& ra = gemm_rope_args{})
 {
     bool ok = true;  // false: the schedule would overrun the kernel's load counter (no supported shape does)
     const int cb = gemm_cols_per_block(N);
@@ -669,11 +687,11 @@ static int gemm_dispatch(const void* A, int lda, const void* Bp, void* C, int ld
     if (!fixed_tile && !small && cb < 8 && 8 % cb == 0 && N % 128 == 0 &&
         (long long)((M + 255) / 256) * (N / 128) >= 256) {
         if (cb == 1)
-            ok = launch_gemm<8, kRingBig, EPI, 8, 4, 1>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s);
+            ok = launch_gemm<8, kRingBig, EPI, 8, 4, 1>(A, lda, Bp, C, ldc, R, ldr, ra, M, N, K, f32, s);
         else if (cb == 2)
-            ok = launch_gemm<8, kRingBig, EPI, 8, 4, 2>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s);
+            ok = launch_gemm<8, kRingBig, EPI, 8, 4, 2>(A, lda, Bp, C, ldc, R, ldr, ra, M, N, K, f32, s);
         else
-            ok = launch_gemm<8, kRingBig, EPI, 8, 4, 4>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s);
+            ok = launch_gemm<8, kRingBig, EPI, 8, 4, 4>(A, lda, Bp, C, ldc, R, ldr, ra, M, N, K, f32, s);
         return ok ? check_launch() : DET_ESHAPE;
     }
     // (2) Matrices too narrow to give every compute unit a column tile (N / (16 cb) < 256): the rows are
@@ -706,20 +724,20 @@ static int gemm_dispatch(const void* A, int lda, const void* Bp, void* C, int ld
     if (!fixed_tile && !small && N % 64 == 0 && sq_pays && ((cb == 1 && M >= 96) || (cb == 2 && M >= 192))) {
         const int rows = sq_rows;
         if (cb == 1)
-            ok = launch_gemm<4, kRingBig, EPI, 8, 4, 1>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s, rows);
+            ok = launch_gemm<4, kRingBig, EPI, 8, 4, 1>(A, lda, Bp, C, ldc, R, ldr, ra, M, N, K, f32, s, rows);
         else
-            ok = launch_gemm<4, kRingBig, EPI, 8, 4, 2>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s, rows);
+            ok = launch_gemm<4, kRingBig, EPI, 8, 4, 2>(A, lda, Bp, C, ldc, R, ldr, ra, M, N, K, f32, s, rows);
         return ok ? check_launch() : DET_ESHAPE;
     }
 #define DET_GEMM_CASE(CBV)                                                                                  \
     case CBV:                                                                                               \
         if constexpr (CBV <= 3) {                                                                           \
             if (small) {                                                                                    \
-                ok = launch_gemm<CBV, gemm_small_ring_blocks(CBV), EPI, gemm_waves(CBV), gemm_loader_waves(CBV, true)>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s); \
+                ok = launch_gemm<CBV, gemm_small_ring_blocks(CBV), EPI, gemm_waves(CBV), gemm_loader_waves(CBV, true)>(A, lda, Bp, C, ldc, R, ldr, ra, M, N, K, f32, s); \
                 break;                                                                                      \
             }                                                                                               \
         }                                                                                                   \
-        ok = launch_gemm<CBV, kRingBig, EPI, gemm_waves(CBV), gemm_loader_waves(CBV, false)>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s, base_rows);            \
+        ok = launch_gemm<CBV, kRingBig, EPI, gemm_waves(CBV), gemm_loader_waves(CBV, false)>(A, lda, Bp, C, ldc, R, ldr, ra, M, N, K, f32, s, base_rows);            \
         break;
     switch (cb) {
         DET_GEMM_CASE(1)
@@ -730,7 +748,7 @@ static int gemm_dispatch(const void* A, int lda, const void* Bp, void* C, int ld
         DET_GEMM_CASE(6)
         DET_GEMM_CASE(7)
         default:
-            ok = launch_gemm<8, kRingBig, EPI, gemm_waves(8), gemm_loader_waves(8, false)>(A, lda, Bp, C, ldc, R, ldr, M, N, K, f32, s, base_rows);
+            ok = launch_gemm<8, kRingBig, EPI, gemm_waves(8), gemm_loader_waves(8, false)>(A, lda, Bp, C, ldc, R, ldr, ra, M, N, K, f32, s, base_rows);
             break;
     }
 #undef DET_GEMM_CASE
@@ -749,7 +767,7 @@ extern "C" size_t det_gemm_packed_b_bytes(int N, int K)
     return (size_t)2 * N * K;
 }
 
-static int pack_impl(const void* B_kn, void* B_packed, int N, int K, int gate_up_f, void* stream)
+static int pack_impl(const void* B_kn, void* B_packed, int N, int K, int gate_up_f, void* stream, int rope_d = 0)
 {
     if (!B_kn || !B_packed) return DET_EINVAL;
     if (!gemm_shape_ok(N, K)) return DET_ESHAPE;
@@ -758,7 +776,7 @@ static int pack_impl(const void* B_kn, void* B_packed, int N, int K, int gate_up
     const int blocks = (int)((total + 255) / 256 < 65536 ? (total + 255) / 256 : 65536);
     hipLaunchKernelGGL(gemm_pack_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<const uint16_t*>(B_kn), static_cast<uint4*>(B_packed), N, K,
-                       gemm_cols_per_block(N), gate_up_f);
+                       gemm_cols_per_block(N), gate_up_f, rope_d);
     return check_launch();
 }
 
@@ -771,6 +789,12 @@ extern "C" int det_gemm_pack_gate_up(const void* B_kn, void* B_packed, int F, in
 {
     if (F < 1 || F % 8 != 0) return DET_ESHAPE;
     return pack_impl(B_kn, B_packed, 2 * F, K, F, stream);
+}
+
+extern "C" int det_gemm_pack_qkv(const void* B_kn, void* B_packed, int Hq, int Hkv, int D, int K, void* stream)
+{
+    if (Hq < 1 || Hkv < 1 || D != 128) return DET_ESHAPE;
+    return pack_impl(B_kn, B_packed, (Hq + 2 * Hkv) * D, K, 0, stream, D);
 }
 
 static int gemm_args_ok(const void* A, int lda, const void* Bp, const void* C, int ldc, int M, int N, int K)
@@ -825,4 +849,28 @@ extern "C" int det_gemm_swiglu_bf16(const void* A, int lda, const void* B_gate_u
     if (ldy < F) return DET_EINVAL;
     return gemm_dispatch<kEpiSwiglu>(A, lda, B_gate_up, Y, ldy, nullptr, 0, M, 2 * F, K, 0,
                                      static_cast<hipStream_t>(stream));
+}
+
+extern "C" int det_gemm_qkv_rope_append(const void* A, int lda, const void* B_qkv, void* qbuf, void* kcache,
+                                        void* vcache, const int32_t* positions, const int32_t* slots,
+                                        const float* rope_cos, const float* rope_sin, int M, int Hq, int Hkv, int D,
+                                        int Lmax, int K, void* stream)
+{
+    if (Hq < 1 || Hkv < 1 || D != 128 || Lmax < 1) return DET_ESHAPE;
+    const int N = (Hq + 2 * Hkv) * D;
+    const int rc = gemm_args_ok(A, lda, B_qkv, qbuf, 4, M, N, K);
+    if (rc != DET_OK) return rc;
+    if (!kcache || !vcache || !positions || !rope_cos || !rope_sin) return DET_EINVAL;
+    if (!aligned16(kcache) || !aligned16(vcache) || !aligned16(rope_cos) || !aligned16(rope_sin)) return DET_EALIGN;
+    gemm_rope_args ra;
+    ra.pos = positions;
+    ra.slots = slots;
+    ra.cos_t = rope_cos;
+    ra.sin_t = rope_sin;
+    ra.qbuf = static_cast<uint16_t*>(qbuf);
+    ra.kcache = static_cast<uint16_t*>(kcache);
+    ra.vcache = static_cast<uint16_t*>(vcache);
+    ra.Hq = Hq, ra.Hkv = Hkv, ra.Lmax = Lmax;
+    return gemm_dispatch<kEpiRopeAppend>(A, lda, B_qkv, qbuf, 4, nullptr, 0, M, N, K, 0,
+                                         static_cast<hipStream_t>(stream), false, ra);
 }

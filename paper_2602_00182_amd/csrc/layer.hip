@@ -7,21 +7,19 @@ namespace det {
 static size_t up256(size_t n) { return (n + 255) & ~(size_t)255; }
 
 struct LayerWs {
-    size_t h, qkv, qbuf, att, mm, attn, attn_bytes, total;
+    size_t h, qbuf, att, mm, attn, attn_bytes, total;
 };
 
 static LayerWs layer_ws(const det_layer_cfg& c, int B)
 {
     LayerWs w{};
     size_t off = 0;
-    const size_t nqkv = (size_t)(c.Hq + 2 * c.Hkv) * c.D;
     auto take = [&](size_t bytes) {
         const size_t o = off;
         off += up256(bytes);
         return o;
     };
     w.h = take(2 * (size_t)B * c.H);
-    w.qkv = take(2 * (size_t)B * nqkv);
     w.qbuf = take(2 * (size_t)B * c.Hq * c.D);
     w.att = take(2 * (size_t)B * c.Hq * c.D);
     w.mm = take(2 * (size_t)B * c.F);
@@ -93,12 +91,10 @@ static int decoder_layer_impl(const det_layer_weights* w, const det_layer_cfg* c
     if (ws_bytes < l.total) return DET_EWORKSPACE;
     char* base = static_cast<char*>(ws);
     void* h = base + l.h;
-    void* qkv = base + l.qkv;
     void* qbuf = base + l.qbuf;
     void* att = base + l.att;
     void* mm = base + l.mm;
     void* aws = base + l.attn;
-    const int nqkv = (c.Hq + 2 * c.Hkv) * c.D;
     const int nq = c.Hq * c.D;
     hipStream_t s = static_cast<hipStream_t>(stream);
     int rc;
@@ -108,9 +104,8 @@ static int decoder_layer_impl(const det_layer_weights* w, const det_layer_cfg* c
         if (rc != DET_OK) return rc; \
     } while (0)
     DET_TRY(det_rmsnorm(x_inout, w->w_norm1, h, B, c.H, c.eps, stream));
-    DET_TRY(det_gemm_bf16(h, c.H, w->wqkv, qkv, nqkv, B, nqkv, c.H, DET_BF16, stream));
-    DET_TRY(rope_append(qkv, qbuf, kcache, vcache, positions, slots, rope_cos, rope_sin, B, c.Hq, c.Hkv, c.D, c.Lmax,
-                        s));
+    DET_TRY(det_gemm_qkv_rope_append(h, c.H, w->wqkv, qbuf, kcache, vcache, positions, slots, rope_cos, rope_sin, B,
+                                     c.Hq, c.Hkv, c.D, c.Lmax, c.H, stream));
     DET_TRY(attn_decode_impl(qbuf, kcache, vcache, positions, slots, 1, att, aws, l.attn_bytes, B, c.Hq, c.Hkv, c.D,
                              c.Lmax, c.scale, s));
     DET_TRY(det_gemm_bf16_residual(att, nq, w->wo, x_inout, c.H, x_inout, c.H, B, c.H, nq, stream));

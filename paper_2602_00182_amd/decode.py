@@ -52,7 +52,8 @@ class DecodeModel:
         self.lm_head = pack(weights["lm_head"])
         self.layers = []
         for lw in weights["layers"]:
-            packed = dict(norm1=lw["norm1"].contiguous(), wqkv=pack(lw["wqkv"]),
+            wqkv = pack(lw["wqkv"]) if quantized else api.pack_qkv(lw["wqkv"], cfg.Hq, cfg.Hkv, cfg.D)
+            packed = dict(norm1=lw["norm1"].contiguous(), wqkv=wqkv,
                           wo=pack(lw["wo"]), norm2=lw["norm2"].contiguous(),
                           wgu=pack_gu(lw["wgu"]), wdown=pack(lw["wdown"]))
             struct = api.layer_weights(packed["norm1"], packed["wqkv"], packed["wo"], packed["norm2"],

@@ -329,6 +329,53 @@ def test_fused_swiglu_epilogue_equals_unfused_bytes(d, orc, M, K, F):
     assert np.array_equal(down_bf16(fused), orc.swiglu(np.ascontiguousarray(guh[:, :F]), np.ascontiguousarray(guh[:, F:])))
 
 
+@pytest.mark.parametrize("M,Hq,Hkv,K,Lmax,use_slots", [(1, 32, 8, 4096, 64, False), (7, 4, 2, 256, 40, True),
+                                                       (33, 8, 2, 1024, 96, True), (300, 32, 8, 4096, 320, False),
+                                                       (1300, 32, 8, 512, 700, True), (130, 2, 1, 512, 130, True)])
+def test_fused_rope_append_epilogue_equals_unfused_bytes(d, M, Hq, Hkv, K, Lmax, use_slots):
+    """det_gemm_qkv_rope_append on the pair-interleaved packing = det_gemm_bf16 on the plain packing, then
+    det_rope on the query and key heads and a copy of the key and value heads into the caches, byte for
+    byte; every other cache row keeps its bytes."""
+    D = 128
+    N = (Hq + 2 * Hkv) * D
+    A = up_bf16(ds.normal_bf16(720 + M, (M, K)))
+    W = up_bf16(ds.normal_bf16(721 + Hq, (K, N), 0.05))
+    cos_h, sin_h = ds.rope_tables(Lmax, D, 5.0e5)
+    cos_t, sin_t = torch.from_numpy(cos_h).to(DEV), torch.from_numpy(sin_h).to(DEV)
+    rng = np.random.default_rng(722 + M)
+    if use_slots:  # a few slots, several rows each, distinct (slot, position) pairs, out-of-range positions clamped
+        S = max(2, (M + Lmax - 1) // Lmax + 1)
+        cells = rng.permutation(S * Lmax)[:M]
+        slots_h, pos_h = (cells // Lmax).astype(np.int32), (cells % Lmax).astype(np.int32)
+    else:
+        S = M
+        slots_h, pos_h = np.arange(M, dtype=np.int32), rng.integers(0, Lmax, M).astype(np.int32)
+        pos_h[0] = Lmax + 5  # clamped to Lmax - 1
+    pos = torch.from_numpy(pos_h).to(DEV)
+    slots = torch.from_numpy(slots_h).to(DEV) if use_slots else None
+    kc0 = up_bf16(ds.normal_bf16(723, (S, Hkv, Lmax, D)))
+    vc0 = up_bf16(ds.normal_bf16(724, (S, Hkv, Lmax, D)))
+    step(f"gemm rope/append epilogue M={M} Hq={Hq} Hkv={Hkv} K={K}")
+    qkv = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+    d.det_gemm_bf16(A, d.pack_weight(W), qkv, N, K)
+    qk = qkv[:, :(Hq + Hkv) * D].contiguous().view(M, Hq + Hkv, D)
+    qk_rot = torch.empty_like(qk)
+    d.det_rope(qk, qk_rot, pos, cos_t, sin_t)
+    torch.cuda.synchronize()
+    pc = torch.from_numpy(np.clip(pos_h, 0, Lmax - 1).astype(np.int64)).to(DEV)
+    sl = torch.from_numpy(slots_h.astype(np.int64)).to(DEV)
+    k_ref, v_ref = kc0.clone(), vc0.clone()
+    k_ref[sl, :, pc, :] = qk_rot[:, Hq:, :]
+    v_ref[sl, :, pc, :] = qkv[:, (Hq + Hkv) * D:].view(M, Hkv, D)
+    qbuf = torch.zeros((M, Hq, D), dtype=torch.bfloat16, device=DEV)
+    kc, vc = kc0.clone(), vc0.clone()
+    d.det_gemm_qkv_rope_append(A, d.pack_qkv(W, Hq, Hkv, D), qbuf, kc, vc, pos, slots, cos_t, sin_t)
+    torch.cuda.synchronize()
+    assert torch.equal(qbuf.view(torch.int16), qk_rot[:, :Hq, :].contiguous().view(torch.int16))
+    assert torch.equal(kc.view(torch.int16), k_ref.view(torch.int16))
+    assert torch.equal(vc.view(torch.int16), v_ref.view(torch.int16))
+
+
 def test_seeded_shape_sweep_both_gemms(d, orc):
     """Thirty seeded (M, N, K) drawn across every tiling rule (narrow and wide packings, row-cut, 64- and
     128-column tiles, several row tiles, ragged M): a sample of each product within the fp64 bound, one

@@ -19,7 +19,7 @@ def test_decoder_layer_graph_replays_match_eager():
     H, Hq, Hkv, D, F, Lmax, B = 1024, 8, 2, 128, 2816, 512, 5
     scale = float(np.float32(1.0 / math.sqrt(D)))
     g = lambda i, shape, std=0.03, mean=0.0: ds.normal_bf16_torch(9000 + i, shape, std, mean, DEV)
-    tensors = [g(0, (H,), 0.1, 1.0), d.pack_weight(g(1, (H, (Hq + 2 * Hkv) * D))), d.pack_weight(g(2, (Hq * D, H))),
+    tensors = [g(0, (H,), 0.1, 1.0), d.pack_qkv(g(1, (H, (Hq + 2 * Hkv) * D)), Hq, Hkv, D), d.pack_weight(g(2, (Hq * D, H))),
                g(3, (H,), 0.1, 1.0), d.pack_gate_up(g(4, (H, 2 * F))), d.pack_weight(g(5, (F, H)))]
     w = d.layer_weights(*tensors)
     cfg = d.layer_cfg(H, Hq, Hkv, D, F, Lmax, 1e-5, scale)

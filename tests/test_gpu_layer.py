@@ -35,7 +35,8 @@ def layer(d):
         wgu=ds.normal_bf16_torch(s + 4, (H, 2 * F), 0.02, 0.0, DEV),
         wdown=ds.normal_bf16_torch(s + 5, (F, H), 0.02, 0.0, DEV),
     )
-    packed = {k: ((d.pack_gate_up(v) if k == "wgu" else d.pack_weight(v)) if v.dim() == 2 else v)
+    packed = {k: ((d.pack_gate_up(v) if k == "wgu" else d.pack_qkv(v, Hq, Hkv, D) if k == "wqkv" else d.pack_weight(v))
+                  if v.dim() == 2 else v)
               for k, v in logical.items()}
     struct = d.layer_weights(packed["norm1"], packed["wqkv"], packed["wo"], packed["norm2"], packed["wgu"],
                              packed["wdown"])

@@ -83,7 +83,7 @@ def test_decoder_layer_repeats_streams_and_background_load(d):
     H, Hq, Hkv, D, F, Lmax = 4096, 32, 8, 128, 14336, 2048
     s = ds.tensor_seed(4, 0)
     g = lambda i, shape, std=0.02, mean=0.0: ds.normal_bf16_torch(s + i, shape, std, mean, DEV)
-    packed = [g(0, (H,), 0.0, 1.0), d.pack_weight(g(1, (H, (Hq + 2 * Hkv) * D))), d.pack_weight(g(2, (Hq * D, H))),
+    packed = [g(0, (H,), 0.0, 1.0), d.pack_qkv(g(1, (H, (Hq + 2 * Hkv) * D)), Hq, Hkv, D), d.pack_weight(g(2, (Hq * D, H))),
               g(3, (H,), 0.0, 1.0), d.pack_gate_up(g(4, (H, 2 * F))), d.pack_weight(g(5, (F, H)))]
     struct = d.layer_weights(*packed)
     cfg = d.layer_cfg(H, Hq, Hkv, D, F, Lmax, 1e-5, SCALE)
