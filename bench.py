@@ -34,7 +34,7 @@ MS = [1, 2, 4, 8, 16, 32, 64, 128, 256]
 N_SETS = 3
 PEAK_MFMA_TFLOPS = 2500.0   # MI355X dense bf16
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
-DOMINANT = (4096, 28672)    # the launch that moves most of the step's bytes (gemm_kernel<8,144,0,8,4,8>)
+DOMINANT = (4096, 28672)    # the launch that moves most of the step's bytes (gemm_kernel<8,144,0,8,4,8,false>)
 def dominant_traffic_bytes():
     """HBM bytes per launch of the dominant kernel as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
     (scaled by a plain copy kernel of known size): read from the committed summary of those runs,
@@ -229,7 +229,7 @@ def main():
     dom_bytes = float(np.mean([gemm_bytes(M, DOMINANT[1], DOMINANT[0]) for M in MS]))
     dom_avg_ms = float(np.mean(dom_ms))
     achieved = dom_bytes / dom_avg_ms / 1e6
-    roofline = {"bound": "hbm", "kernel": "det::gemm_kernel<8,144,0,8,4,8> (K=4096, N=28672, M=1..256)",
+    roofline = {"bound": "hbm", "kernel": "det::gemm_kernel<8,144,0,8,4,8,false> (K=4096, N=28672, M=1..256)",
                 "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": dominant_traffic_bytes(),
                 "avg_launch_us": round(dom_avg_ms * 1e3, 2), "bytes_per_launch": int(dom_bytes),

@@ -13,7 +13,7 @@ from ._lib import LayerCfg, LayerWeights, Sha256Ctx, lib
 __all__ = [
     "DetError", "det_gemm_bf16", "det_gemm_bf16_fixed_tile", "det_probe_lds_fill", "det_gemm_packed_b_bytes", "det_gemm_pack_b", "det_gemm_bf16_residual",
     "det_gemm_pack_gate_up", "det_gemm_swiglu_bf16", "pack_gate_up", "det_gemm_pack_qkv", "pack_qkv",
-    "det_gemm_qkv_rope_append", "det_rmsnorm",
+    "det_gemm_qkv_rope_append", "det_rmsnorm_gemm_qkv_rope_append", "det_rmsnorm_gemm_swiglu_bf16", "det_rmsnorm",
     "det_attn_decode_workspace_bytes", "det_attn_decode", "det_attn_decode_static", "det_attn_decode_rows", "det_decoder_layer_rows",
     "det_softmax_f32", "det_argmax", "det_sample", "det_rope",
     "det_swiglu", "det_residual_add", "det_embed_gather", "det_decoder_layer_workspace_bytes",
@@ -363,6 +363,36 @@ def det_gemm_qkv_rope_append(A, B_qkv, qbuf, kcache, vcache, positions, slots, r
         _contig(kcache, torch.bfloat16), _contig(vcache, torch.bfloat16), _contig(positions, torch.int32),
         None if slots is None else _contig(slots, torch.int32), _contig(rope_cos, torch.float32),
         _contig(rope_sin, torch.float32), M, Hq, Hkv, D, Lmax, K, _stream(stream)))
+
+
+def det_rmsnorm_gemm_qkv_rope_append(x, w_norm, eps: float, B_qkv, h, qbuf, kcache, vcache, positions, slots, rope_cos,
+                                     rope_sin, stream=None) -> None:
+    """det_gemm_qkv_rope_append of det_rmsnorm(x, w_norm, eps); h [M, K] bf16 is scratch."""
+    M, K = x.shape
+    _, Hq, D = qbuf.shape
+    _, Hkv, Lmax, _ = kcache.shape
+    if qbuf.shape[0] != M or vcache.shape != kcache.shape or x.stride(1) != 1 or positions.numel() != M:
+        raise ValueError("bad fused projection operands")
+    if w_norm.shape != (K,) or h.shape != (M, K) or (slots is not None and slots.numel() != M):
+        raise ValueError("bad norm operands")
+    if rope_cos.shape != (Lmax, D // 2) or rope_sin.shape != (Lmax, D // 2):
+        raise ValueError("bad rope tables")
+    _check("det_rmsnorm_gemm_qkv_rope_append", lib().det_rmsnorm_gemm_qkv_rope_append(
+        _ptr(x, torch.bfloat16), _ld(x, K), _contig(w_norm, torch.bfloat16), eps, _contig(B_qkv),
+        _contig(h, torch.bfloat16), _contig(qbuf, torch.bfloat16), _contig(kcache, torch.bfloat16),
+        _contig(vcache, torch.bfloat16), _contig(positions, torch.int32),
+        None if slots is None else _contig(slots, torch.int32), _contig(rope_cos, torch.float32),
+        _contig(rope_sin, torch.float32), M, Hq, Hkv, D, Lmax, K, _stream(stream)))
+
+
+def det_rmsnorm_gemm_swiglu_bf16(x, w_norm, eps: float, B_gate_up, h, Y, F: int, stream=None) -> None:
+    """det_gemm_swiglu_bf16 of det_rmsnorm(x, w_norm, eps); h [M, K] bf16 is scratch."""
+    M, K = x.shape
+    if Y.shape != (M, F) or x.stride(1) != 1 or Y.stride(1) != 1 or w_norm.shape != (K,) or h.shape != (M, K):
+        raise ValueError("bad operand shapes")
+    _check("det_rmsnorm_gemm_swiglu_bf16", lib().det_rmsnorm_gemm_swiglu_bf16(
+        _ptr(x, torch.bfloat16), _ld(x, K), _contig(w_norm, torch.bfloat16), eps, _contig(B_gate_up),
+        _contig(h, torch.bfloat16), _ptr(Y, torch.bfloat16), _ld(Y, F), M, F, K, _stream(stream)))
 
 
 def _ld(t: torch.Tensor, cols: int) -> int:

@@ -17,7 +17,7 @@ extern "C" const char* det_fingerprint(void)
         HIP_VERSION_PATCH) " canon-2 gemm-16x16x32-k64"
         // launch geometry revision: which tile shapes and kernel forms the row count (GEMM), the batch
         // (attention) select.  They move no output byte, but a receipt pins them all the same.
-        " tiles-2(gemm:n128@256wg,rowcut,n64@m96/192;qgemm:sp@8rows;attn:split@128wg,rows8@16rows)";
+        " tiles-3(gemm:n128@256wg,rowcut,n64@m96/192,norm-in-kernel@4rows;qgemm:sp@8rows;attn:split@128wg,rows8@16rows)";
 }
 
 extern "C" int det_last_hip_error(void) { return det::g_last_hip_error; }

@@ -122,6 +122,40 @@ __device__ __forceinline__ float block_max(float v, float* scratch)
     return fmaxf(fmaxf(scratch[0], scratch[1]), fmaxf(scratch[2], scratch[3]));
 }
 
+// RMSNorm arithmetic shared by the kernel of its own and by the GEMM that normalizes its rows itself:
+// the sum of squares of one 8-element vector folded into acc in ascending element order, and
+// y = bf16((x*r)*w) of one vector.
+__device__ __forceinline__ float rms_fold(const uint4& x, float acc)
+{
+    const uint32_t p[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const float lo = bf16lo_to_f32(p[k]);
+        const float hi = bf16hi_to_f32(p[k]);
+        acc = __builtin_fmaf(lo, lo, acc);
+        acc = __builtin_fmaf(hi, hi, acc);
+    }
+    return acc;
+}
+__device__ __forceinline__ float rms_scale(float ss, int H, float eps)
+{
+    const float mean = ss / (float)H;
+    return 1.0f / __builtin_sqrtf(mean + eps);
+}
+__device__ __forceinline__ uint4 rms_apply(const uint4& x, const uint4& w, float r)
+{
+    const uint32_t p[4] = {x.x, x.y, x.z, x.w};
+    const uint32_t q[4] = {w.x, w.y, w.z, w.w};
+    uint32_t o[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const float lo = (bf16lo_to_f32(p[k]) * r) * bf16lo_to_f32(q[k]);
+        const float hi = (bf16hi_to_f32(p[k]) * r) * bf16hi_to_f32(q[k]);
+        o[k] = pack_bf16x2(lo, hi);
+    }
+    return make_uint4(o[0], o[1], o[2], o[3]);
+}
+
 // Epilogues.  kEpiStore: C = bf16(acc) or fp32 acc.  kEpiResidual: C = bf16(fp32(bf16(acc)) + fp32(R)),
 // the bytes of the plain GEMM followed by the residual add.  kEpiSwiglu: the weight columns are packed
 // gate_j, up_j interleaved, and Y[j] = bf16( silu(bf16(acc_gate_j)) * bf16(acc_up_j) ), the bytes of the

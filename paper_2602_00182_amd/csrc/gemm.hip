@@ -161,13 +161,17 @@ struct gemm_tile_plan {
     uint32_t inv_nload, inv_hb;  // floor(2^20/d)+1: n/d = (n * inv) >> 20, exact for the small n used here
 };
 
-static gemm_tile_plan make_tile_plan(int mrem, int cb, int ringb, int nw, int nl, int K)
+// a_res: the activations do not travel through the ring (the kernel that normalizes its rows itself keeps them
+// resident in the first K/64 blocks of its LDS): a stage is its weight blocks only, the ring is what is left,
+// and only the NL waves that never compute load.
+static gemm_tile_plan make_tile_plan(int mrem, int cb, int ringb, int nw, int nl, int K, bool a_res = false)
 {
     gemm_tile_plan t;
     t.mrem = mrem;
     t.RB = (mrem + 15) >> 4;
     t.HB = (mrem + 7) >> 3;
-    const int nb = 2 * cb + 2 * t.RB;
+    if (a_res) ringb -= K >> 6;
+    const int nb = 2 * cb + (a_res ? 0 : 2 * t.RB);
     t.SPC = (ringb / 3) / nb > 1 ? (ringb / 3) / nb : 1;
     {
         // Small tiles run their operand reads in groups of stages (see the kernel's small-tile pipeline): a
@@ -184,7 +188,7 @@ static gemm_tile_plan make_tile_plan(int mrem, int cb, int ringb, int nw, int nl
     const int nstages = K >> 6;
     t.nchunks = (nstages + t.SPC - 1) / t.SPC;
     t.last_cnt = nstages - (t.nchunks - 1) * t.SPC;
-    t.nload = nw + nl - (t.RB < nw ? t.RB : nw);
+    t.nload = a_res ? nl : nw + nl - (t.RB < nw ? t.RB : nw);
     t.inv_nload = (1u << 20) / (uint32_t)t.nload + 1u;
     t.inv_hb = (1u << 20) / (uint32_t)t.HB + 1u;
     return t;
@@ -196,19 +200,27 @@ static gemm_tile_plan make_tile_plan(int mrem, int cb, int ringb, int nw, int nl
 static bool plan_fits_load_counter(const gemm_tile_plan& t, int cb)
 {
     const int per_chunk = (t.SPC * 2 * cb + t.nload - 1) / t.nload + t.SPC * ((t.HB + t.nload - 1) / t.nload) + 1;
-    return (t.nslots - 1) * per_chunk <= 62;
+    return t.nslots >= 2 && (t.nslots - 1) * per_chunk <= 62;
 }
 
 // PCB: column blocks per slab of the packed weights.  PCB == CB: the workgroup's weights are one slab.
 // PCB < CB (tall launches of narrow matrices, see gemm_dispatch): the workgroup owns CB/PCB adjacent
 // slabs of a matrix packed for narrower tiles, and its rows are a tile of plan_full.mrem rows.
-template <int CB, int RINGB, int EPI, int NW, int NL, int PCB>
+//
+// NORM: the rows of A are raw activations and the operand is their RMSNorm with the weight vector R and
+// epsilon eps (the bytes det_rmsnorm would write, computed by the same routines in the same order).  Only for
+// tiles of at most 4 rows and K <= 4096: the waves 0 .. NW-1 normalize the rows (256 threads a row, as the
+// RMSNorm kernel has them) straight into LDS, where they stay for the whole K range in the first K/64
+// blocks, one 8-row half block a stage; the ring behind them carries weights only, loaded by the NL waves
+// that never compute, which start streaming before the rows are read.
+template <int CB, int RINGB, int EPI, int NW, int NL, int PCB, bool NORM>
 __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __restrict__ A, int lda,
                                                           const uint4* __restrict__ Bp, void* C, int ldc,
                                                           const uint16_t* R, int ldr, int K, int out_f32,
                                                           gemm_tile_plan plan_full, gemm_tile_plan plan_tail,
-                                                          gemm_rope_args ra)
+                                                          gemm_rope_args ra, float eps)
 {
+    static_assert(!NORM || (PCB == CB && NW % 4 == 0), "the normalizing form: one slab, whole teams of four waves");
     static_assert(RINGB >= 4 * (CB + 16), "the ring must hold two stages of the largest tile");
     static_assert(NL >= 1, "a tile of NW row blocks or more needs waves that only load");
     static_assert(CB % PCB == 0 && (PCB == CB || ((CB & (CB - 1)) == 0 && (PCB & (PCB - 1)) == 0)), "slab split by shifts");
@@ -231,7 +243,8 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
     const int P = nslots - 1;      // chunks in flight
     const int nstages = K >> 6;
     const int nchunks = tp.nchunks;
-    const uint32_t ring_addr = (uint32_t)(uintptr_t)(lds_char_t*)ring;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_char_t*)ring;
+    const uint32_t ring_addr = lds_base + (NORM ? (uint32_t)nstages * 1024u : 0u);  // behind the resident activations
     auto chunk_stages = [&](int c) { return c < nchunks - 1 ? SPC : (c == nchunks - 1 ? tp.last_cnt : 0); };
 
     // Roles.  Row block rb belongs to wave rb % NW (waves 0 .. NW-1); a wave with a row block only
@@ -244,6 +257,71 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
     // and everyone is done reading chunk c-1.
     const int ncomp = min(RB, NW);
     const int nrb = wave < ncomp ? (int)((unsigned)(RB - wave + NW - 1) / (unsigned)NW) : 0;
+
+    // NORM: waves 0 .. NW-1 normalize the tile's rows into LDS.  A team of four waves is the 256 threads of
+    // the RMSNorm kernel: thread t of the team owns the vectors t, t + 256 of a row, the wave sums go
+    // through LDS and are combined as (q0+q2)+(q1+q3).  Team i takes the rows i, i + NW/4, ...  All loads are
+    // issued before the first sum so that the rows cost one round trip.  Two barriers in here: the loads are
+    // issued, and the hand-over of the wave sums; the rows themselves are published by the barrier that opens
+    // chunk 0.
+    __shared__ float norm_part[NORM ? 32 : 1];
+    auto normalize_rows = [&]() {
+        constexpr int NT = NW / 4;   // teams
+        constexpr int RPT = 4 / NT;  // rows a team can own (the tile has at most four)
+        const int team = wave >> 2, vt = tid & 255, nvec = K >> 3;
+        const uint4* wn4 = reinterpret_cast<const uint4*>(R);
+        uint4 wv[2], xv[RPT][2];
+        float part[RPT];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            if (vt + 256 * i < nvec) wv[i] = wn4[vt + 256 * i];
+#pragma unroll
+        for (int q = 0; q < RPT; ++q) {
+            const int row = team + NT * q;
+            if (row < mrem) {
+                const uint4* xr = reinterpret_cast<const uint4*>(A + (size_t)(m0 + row) * lda);
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+                    if (vt + 256 * i < nvec) xv[q][i] = xr[vt + 256 * i];
+            }
+        }
+        // The rows' loads are in the memory pipe: only now may the loading waves start the weight stream.  The pipe
+        // returns loads in issue order, and a row load queued behind the first chunks of weights would wait
+        // for all of them.
+        asm volatile("s_barrier" ::: "memory");
+#pragma unroll
+        for (int q = 0; q < RPT; ++q) {
+            const int row = team + NT * q;
+            part[q] = 0.0f;
+            if (row < mrem) {
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+                    if (vt + 256 * i < nvec) part[q] = rms_fold(xv[q][i], part[q]);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < RPT; ++q) {
+            const float w = wave_tree_sum(part[q]);
+            if (lane == 0) norm_part[(team + NT * q) * 4 + (wave & 3)] = w;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+#pragma unroll
+        for (int q = 0; q < RPT; ++q) {
+            const int row = team + NT * q;
+            if (row < mrem) {
+                const float* s4 = norm_part + row * 4;
+                const float a = s4[0] + s4[2];
+                const float b = s4[1] + s4[3];
+                const float r = rms_scale(a + b, K, eps);
+                const int z = ((row >> 1) & 3) << 1;  // the swizzle of the activation tiles (see above)
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const int v = vt + 256 * i;
+                    if (v < nvec) ring[(v >> 3) * 64 + row * 8 + ((v & 7) ^ z)] = rms_apply(xv[q][i], wv[i], r);
+                }
+            }
+        }
+    };
 
     // LDS layout of a chunk of s_cnt stages inside its slot: first the s_cnt*2*CB weight blocks in
     // the order they lie in the packed matrix (stage, column block, step), then s_cnt*RB activation
@@ -258,9 +336,16 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
     // matrix-core step (same piece of rows 0..15) over all sixteen 16-byte bank groups.
 
     if (nrb == 0) {
+        if constexpr (NORM) {
+            if (wave < NW) {  // normalizes, then only keeps the barrier count
+                normalize_rows();
+                for (int c = 0; c < nchunks; ++c) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                return;
+            }
+        }
         // ---------------------------------------------------------------- loading wave
-        const int nload = tp.nload;  // = NW + NL - ncomp
-        const int lrank = wave - ncomp;
+        const int nload = tp.nload;  // = NW + NL - ncomp (NORM: NL)
+        const int lrank = NORM ? wave - NW : wave - ncomp;
         // first slab of this workgroup (a slab holds nstages stages of 2*PCB blocks)
         const char* wbytes = reinterpret_cast<const char*>(Bp + (size_t)blockIdx.x * (CB / PCB) * nstages * (2 * PCB * 64));
         const char* abytes = reinterpret_cast<const char*>(A + (size_t)m0 * lda);
@@ -284,7 +369,7 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
         const int nw_stage = strided(2 * CB);
         auto loads_for = [&](int s_cnt) {
             return (PCB == CB ? strided(s_cnt * 2 * CB) : s_cnt * nw_stage) +
-                   (stage_split ? s_cnt * strided(HB) : strided(s_cnt * HB));
+                   (NORM ? 0 : (stage_split ? s_cnt * strided(HB) : strided(s_cnt * HB)));
         };
         // every chunk but the last has SPC stages, so two values cover all chunks
         const int loads_full = loads_for(SPC);
@@ -314,6 +399,7 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
                             slot_addr + (uint32_t)u * 1024u, (uint32_t)(2 * CB) * 1024u, s_cnt);
                 }
             }
+            if constexpr (NORM) return;  // the activations are resident
             // Half block hb of stage sl comes from abytes + hb*half_bytes + 128*(s0+sl) and goes to block
             // 2*RB*sl + hb of the tile area; both are walked with running addresses.
             if (stage_split && (nload & 1) == 0) {  // all of this wave's half blocks have the parity of its rank
@@ -367,7 +453,9 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
             }
         };
 
+        if constexpr (NORM) asm volatile("s_barrier" ::: "memory");  // the rows' loads are issued (see normalize_rows)
         for (int c = 0; c < P; ++c) load_chunk(c, c);
+        if constexpr (NORM) asm volatile("s_barrier" ::: "memory");  // the hand-over of the wave sums in normalize_rows
         const int younger_steady = (P - 1) * loads_full;  // while chunks c+1 .. c+P-1 are all full ones
         int slot_c = 0;    // slot of chunk c
         int slot_new = P;  // slot of chunk c+P (the slot chunk c-1 used: nslots = P+1)
@@ -426,6 +514,7 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
         };
         // all of this wave's LDS reads have returned, then the barrier that opens the next chunk
         auto open_chunk = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+        if constexpr (NORM) normalize_rows();
 
         if constexpr (CB * NRB >= 6) {
             // One two-deep pipeline over the whole K range: the operands of a step are read while the step
@@ -441,7 +530,8 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
             int s_cnt = chunk_stages(0);
             open_chunk();
             uint32_t wa = ring_addr + (uint32_t)lane * 16u;                 // weight block 0 of the stage, this lane
-            uint32_t xa = ring_addr + (uint32_t)(s_cnt * 2 * CB) * 1024u;   // activation tiles of the stage
+            uint32_t xa = NORM ? lds_base : ring_addr + (uint32_t)(s_cnt * 2 * CB) * 1024u;  // activation tiles of the stage
+            const uint32_t a_step = NORM ? 1024u : (uint32_t)nA * 1024u;
             const uint32_t x0 = (uint32_t)a0_off * 16u, x1 = (uint32_t)a1_off * 16u;
             read_frags<NW>(f0, wa, xa + x0, wseq{}, xseq{});
             for (int c = 0; c < nchunks; ++c) {
@@ -455,14 +545,14 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
                     tie_frags(f1, wseq{}, xseq{});
                     if (sl + 1 < s_cnt) {
                         wa += (uint32_t)(2 * CB) * 1024u;
-                        xa += (uint32_t)nA * 1024u;
+                        xa += a_step;
                         read_frags<NW>(f0, wa, xa + x0, wseq{}, xseq{});
                     } else if (c + 1 < nchunks) {
                         open_chunk();
                         slot_c = slot_c + 1 == nslots ? 0 : slot_c + 1;
                         next_cnt = chunk_stages(c + 1);
                         wa = ring_addr + (uint32_t)(slot_c * slot_blocks) * 1024u + (uint32_t)lane * 16u;
-                        xa = ring_addr + (uint32_t)(slot_c * slot_blocks + next_cnt * 2 * CB) * 1024u;
+                        xa = NORM ? xa + 1024u : ring_addr + (uint32_t)(slot_c * slot_blocks + next_cnt * 2 * CB) * 1024u;
                         read_frags<NW>(f0, wa, xa + x0, wseq{}, xseq{});
                     }
                     mm(f1);
@@ -484,13 +574,14 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
             using wseq = std::make_integer_sequence<int, CB>;
             using xseq = std::make_integer_sequence<int, NRB>;
             const uint32_t x0 = (uint32_t)a0_off * 16u, x1 = (uint32_t)a1_off * 16u;
-            const uint32_t a_stage = (uint32_t)nA * 1024u;  // activation tiles of one stage
+            const uint32_t a_stage = NORM ? 1024u : (uint32_t)nA * 1024u;  // activation tiles of one stage
             int slot_c = 0;
             for (int c = 0; c < nchunks; ++c) {
                 open_chunk();
                 const int s_cnt = chunk_stages(c);
                 const uint32_t wb = ring_addr + (uint32_t)(slot_c * slot_blocks) * 1024u + (uint32_t)lane * 16u;
-                const uint32_t xb = ring_addr + (uint32_t)(slot_c * slot_blocks + s_cnt * 2 * CB) * 1024u;
+                const uint32_t xb = NORM ? lds_base + (uint32_t)(c * SPC) * 1024u
+                                         : ring_addr + (uint32_t)(slot_c * slot_blocks + s_cnt * 2 * CB) * 1024u;
                 Frags f[DS];
                 // (the division is by a constant; the host makes the chunks whole groups wherever it can)
                 const int ngroups = s_cnt / GS;
@@ -594,7 +685,9 @@ __global__ __launch_bounds__(64 * (NW + NL)) void gemm_kernel(const uint16_t* __
             }
         }
     };
-    if constexpr (NW == 8) {
+    if constexpr (NORM) {
+        run(std::integral_constant<int, 1>{});
+    } else if constexpr (NW == 8) {
         if (nrb == 1)
             run(std::integral_constant<int, 1>{});
         else
@@ -648,21 +741,53 @@ __global__ __launch_bounds__(256) void gemm_pack_kernel(const uint16_t* __restri
     }
 }
 
-template <int CB, int RINGB, int EPI, int NW, int NL, int PCB = CB>
+// Up to four rows: each workgroup repeats the normalization of every row, which is off the critical path only
+// while it is shorter than the wait for the first weights (measured on the layer: 4 us gained at one row, 3 at
+// two, 1 at four, 3 lost at eight).
+constexpr int kNormRows = 4;
+template <int CB, int RINGB, int EPI, int NW, int NL, int PCB = CB, bool NORM = false>
 static bool launch_gemm(const void* A, int lda, const void* Bp, void* C, int ldc, const void* R, int ldr,
                         const gemm_rope_args& ra, int M, int N, int K, int out_f32, hipStream_t s,
-                        int tile_rows = 256)
+                        int tile_rows = 256, float eps = 0.0f)
 {
     // tile_rows: a multiple of 16 in 16..256 (the kernel handles 1..16 row blocks of 16 rows)
     dim3 grid(N / (16 * CB), (M + tile_rows - 1) / tile_rows);
-    const gemm_tile_plan full = make_tile_plan(tile_rows, CB, RINGB, NW, NL, K);
-    const gemm_tile_plan tail = make_tile_plan(M - tile_rows * ((M - 1) / tile_rows), CB, RINGB, NW, NL, K);
+    if (NORM && (M > kNormRows || grid.y != 1 || (K >> 6) + 4 * CB > RINGB)) return false;
+    const gemm_tile_plan tail = make_tile_plan(M - tile_rows * ((M - 1) / tile_rows), CB, RINGB, NW, NL, K, NORM);
+    const gemm_tile_plan full = NORM ? tail : make_tile_plan(tile_rows, CB, RINGB, NW, NL, K);  // NORM: the one tile is the tail
     if (!plan_fits_load_counter(full, CB) || !plan_fits_load_counter(tail, CB)) return false;
-    hipLaunchKernelGGL((gemm_kernel<CB, RINGB, EPI, NW, NL, PCB>), grid, dim3(64 * (NW + NL)), 0, s,
+    hipLaunchKernelGGL((gemm_kernel<CB, RINGB, EPI, NW, NL, PCB, NORM>), grid, dim3(64 * (NW + NL)), 0, s,
                        static_cast<const uint16_t*>(A), lda, static_cast<const uint4*>(Bp), C, ldc,
-                       static_cast<const uint16_t*>(R), ldr, K, out_f32, full, tail, ra);
+                       static_cast<const uint16_t*>(R), ldr, K, out_f32, full, tail, ra, eps);
     return true;
 }
+
+// The launch that normalizes its rows itself (see the kernel): M <= 4, K <= 4096, R = the norm's weight vector.
+template <int EPI>
+static int gemm_dispatch_norm(const void* X, int ldx, const void* wn, float eps, const void* Bp, void* C, int ldc, int M,
+                              int N, int K, hipStream_t s, const gemm_rope_args& ra)
+{
+    bool ok = true;
+    switch (gemm_cols_per_block(N)) {
+#define DET_GEMM_NORM_CASE(CBV)                                                                                        \
+    case CBV:                                                                                                          \
+        ok = launch_gemm<CBV, kRingBig, EPI, gemm_waves(CBV), gemm_loader_waves(CBV, false), CBV, true>(               \
+            X, ldx, Bp, C, ldc, wn, 0, ra, M, N, K, 0, s, 256, eps);                                                   \
+        break;
+        DET_GEMM_NORM_CASE(1)
+        DET_GEMM_NORM_CASE(2)
+        DET_GEMM_NORM_CASE(3)
+        DET_GEMM_NORM_CASE(4)
+        DET_GEMM_NORM_CASE(5)
+        DET_GEMM_NORM_CASE(6)
+        DET_GEMM_NORM_CASE(7)
+        default:
+            DET_GEMM_NORM_CASE(8)
+#undef DET_GEMM_NORM_CASE
+    }
+    return ok ? check_launch() : DET_ESHAPE;
+}
+static bool gemm_norm_fusable(int M, int K) { return M <= kNormRows && K <= 4096; }
 
 // Picks the kernel configuration (packing from N, tiling from N and M) and launches it.
 // fixed_tile: the one tiling per (N, K) that does not look at M: 256-row tiles of the packing's own width,
@@ -873,4 +998,57 @@ extern "C" int det_gemm_qkv_rope_append(const void* A, int lda, const void* B_qk
     ra.Hq = Hq, ra.Hkv = Hkv, ra.Lmax = Lmax;
     return gemm_dispatch<kEpiRopeAppend>(A, lda, B_qkv, qbuf, 4, nullptr, 0, M, N, K, 0,
                                          static_cast<hipStream_t>(stream), false, ra);
+}
+
+extern "C" int det_rmsnorm_gemm_qkv_rope_append(const void* x, int ldx, const void* w_norm, float eps, const void* B_qkv,
+                                                void* h, void* qbuf, void* kcache, void* vcache,
+                                                const int32_t* positions, const int32_t* slots, const float* rope_cos,
+                                                const float* rope_sin, int M, int Hq, int Hkv, int D, int Lmax, int K,
+                                                void* stream)
+{
+    if (!x || !w_norm || !h) return DET_EINVAL;
+    if (!aligned16(w_norm) || !aligned16(h)) return DET_EALIGN;
+    if (!gemm_norm_fusable(M, K)) {
+        if (ldx != K) return DET_EINVAL;  // det_rmsnorm takes contiguous rows
+        const int rc = det_rmsnorm(x, w_norm, h, M, K, eps, stream);
+        if (rc != DET_OK) return rc;
+        return det_gemm_qkv_rope_append(h, K, B_qkv, qbuf, kcache, vcache, positions, slots, rope_cos, rope_sin, M, Hq,
+                                        Hkv, D, Lmax, K, stream);
+    }
+    if (Hq < 1 || Hkv < 1 || D != 128 || Lmax < 1) return DET_ESHAPE;
+    const int N = (Hq + 2 * Hkv) * D;
+    const int rc = gemm_args_ok(x, ldx, B_qkv, qbuf, 4, M, N, K);
+    if (rc != DET_OK) return rc;
+    if (!kcache || !vcache || !positions || !rope_cos || !rope_sin) return DET_EINVAL;
+    if (!aligned16(kcache) || !aligned16(vcache) || !aligned16(rope_cos) || !aligned16(rope_sin)) return DET_EALIGN;
+    gemm_rope_args ra;
+    ra.pos = positions;
+    ra.slots = slots;
+    ra.cos_t = rope_cos;
+    ra.sin_t = rope_sin;
+    ra.qbuf = static_cast<uint16_t*>(qbuf);
+    ra.kcache = static_cast<uint16_t*>(kcache);
+    ra.vcache = static_cast<uint16_t*>(vcache);
+    ra.Hq = Hq, ra.Hkv = Hkv, ra.Lmax = Lmax;
+    return gemm_dispatch_norm<kEpiRopeAppend>(x, ldx, w_norm, eps, B_qkv, qbuf, 4, M, N, K,
+                                              static_cast<hipStream_t>(stream), ra);
+}
+
+extern "C" int det_rmsnorm_gemm_swiglu_bf16(const void* x, int ldx, const void* w_norm, float eps, const void* B_gate_up,
+                                            void* h, void* Y, int ldy, int M, int F, int K, void* stream)
+{
+    if (!x || !w_norm || !h) return DET_EINVAL;
+    if (!aligned16(w_norm) || !aligned16(h)) return DET_EALIGN;
+    if (!gemm_norm_fusable(M, K)) {
+        if (ldx != K) return DET_EINVAL;
+        const int rc = det_rmsnorm(x, w_norm, h, M, K, eps, stream);
+        if (rc != DET_OK) return rc;
+        return det_gemm_swiglu_bf16(h, K, B_gate_up, Y, ldy, M, F, K, stream);
+    }
+    if (F < 1 || F % 8 != 0) return DET_ESHAPE;
+    const int rc = gemm_args_ok(x, ldx, B_gate_up, Y, ldy, M, 2 * F, K);
+    if (rc != DET_OK) return rc;
+    if (ldy < F) return DET_EINVAL;
+    return gemm_dispatch_norm<kEpiSwiglu>(x, ldx, w_norm, eps, B_gate_up, Y, ldy, M, 2 * F, K,
+                                          static_cast<hipStream_t>(stream), gemm_rope_args{});
 }

@@ -103,14 +103,13 @@ static int decoder_layer_impl(const det_layer_weights* w, const det_layer_cfg* c
         rc = (call);                 \
         if (rc != DET_OK) return rc; \
     } while (0)
-    DET_TRY(det_rmsnorm(x_inout, w->w_norm1, h, B, c.H, c.eps, stream));
-    DET_TRY(det_gemm_qkv_rope_append(h, c.H, w->wqkv, qbuf, kcache, vcache, positions, slots, rope_cos, rope_sin, B,
-                                     c.Hq, c.Hkv, c.D, c.Lmax, c.H, stream));
+    DET_TRY(det_rmsnorm_gemm_qkv_rope_append(x_inout, c.H, w->w_norm1, c.eps, w->wqkv, h, qbuf, kcache, vcache,
+                                             positions, slots, rope_cos, rope_sin, B, c.Hq, c.Hkv, c.D, c.Lmax, c.H,
+                                             stream));
     DET_TRY(attn_decode_impl(qbuf, kcache, vcache, positions, slots, 1, att, aws, l.attn_bytes, B, c.Hq, c.Hkv, c.D,
                              c.Lmax, c.scale, s));
     DET_TRY(det_gemm_bf16_residual(att, nq, w->wo, x_inout, c.H, x_inout, c.H, B, c.H, nq, stream));
-    DET_TRY(det_rmsnorm(x_inout, w->w_norm2, h, B, c.H, c.eps, stream));
-    DET_TRY(det_gemm_swiglu_bf16(h, c.H, w->wgu, mm, c.F, B, c.F, c.H, stream));
+    DET_TRY(det_rmsnorm_gemm_swiglu_bf16(x_inout, c.H, w->w_norm2, c.eps, w->wgu, h, mm, c.F, B, c.F, c.H, stream));
     DET_TRY(det_gemm_bf16_residual(mm, c.F, w->wdown, x_inout, c.H, x_inout, c.H, B, c.H, c.F, stream));
 #undef DET_TRY
     return DET_OK;

@@ -36,34 +36,19 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint4* __restrict__ 
         const int v = threadIdx.x + i * 256;
         if (v < nvec) {
             xv[i] = xr[v];
-            const uint32_t p[4] = {xv[i].x, xv[i].y, xv[i].z, xv[i].w};
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const float lo = bf16lo_to_f32(p[k]);
-                const float hi = bf16hi_to_f32(p[k]);
-                acc = __builtin_fmaf(lo, lo, acc);
-                acc = __builtin_fmaf(hi, hi, acc);
-            }
+            acc = rms_fold(xv[i], acc);
         }
     }
     const float ss = block_tree_sum(acc, scratch);
-    const float mean = ss / (float)H;
-    const float r = 1.0f / __builtin_sqrtf(mean + eps);
+    const float r = rms_scale(ss, H, eps);
 #pragma unroll
     for (int i = 0; i < kMaxVecPerThread; ++i) {
         const int v = threadIdx.x + i * 256;
         if (v < nvec) {
-            const uint32_t p[4] = {xv[i].x, xv[i].y, xv[i].z, xv[i].w};
-            const uint32_t q[4] = {wv[i].x, wv[i].y, wv[i].z, wv[i].w};
-            uint32_t o[4];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const float lo = (bf16lo_to_f32(p[k]) * r) * bf16lo_to_f32(q[k]);
-                const float hi = (bf16hi_to_f32(p[k]) * r) * bf16hi_to_f32(q[k]);
-                o[k] = pack_bf16x2(lo, hi);
-            }
+            const uint4 yv = rms_apply(xv[i], wv[i], r);
+            const uint32_t o[4] = {yv.x, yv.y, yv.z, yv.w};
             if constexpr (!QUANT) {
-                yr[v] = make_uint4(o[0], o[1], o[2], o[3]);
+                yr[v] = yv;
             } else {
                 float a[8];
                 float amax = 0.0f;

@@ -376,6 +376,43 @@ def test_fused_rope_append_epilogue_equals_unfused_bytes(d, M, Hq, Hkv, K, Lmax,
     assert torch.equal(vc.view(torch.int16), v_ref.view(torch.int16))
 
 
+@pytest.mark.parametrize("K,Hq,Hkv,F", [(4096, 32, 8, 14336), (2048, 16, 4, 5632), (1024, 4, 2, 2048), (256, 2, 1, 8000),
+                                        (4096, 8, 8, 24000), (3072, 24, 8, 8192)])
+def test_gemm_that_normalizes_its_rows_equals_rmsnorm_then_gemm(d, K, Hq, Hkv, F):
+    """det_rmsnorm_gemm_qkv_rope_append / det_rmsnorm_gemm_swiglu_bf16 = det_rmsnorm, then the GEMM, byte for
+    byte, for every M in 1..6 (1..4: the workgroups normalize the rows themselves; 5, 6: two launches)."""
+    D, Lmax = 128, 48
+    N = (Hq + 2 * Hkv) * D
+    Wq = d.pack_qkv(up_bf16(ds.normal_bf16(731 + K, (K, N), 0.05)), Hq, Hkv, D)
+    Wg = d.pack_gate_up(up_bf16(ds.normal_bf16(732 + F, (K, 2 * F), 0.05)))
+    wn = up_bf16(ds.normal_bf16(733 + K, (K,), 0.3, 1.0))
+    cos_h, sin_h = ds.rope_tables(Lmax, D, 5.0e5)
+    cos_t, sin_t = torch.from_numpy(cos_h).to(DEV), torch.from_numpy(sin_h).to(DEV)
+    eps = 1e-5
+    for M in range(1, 7):
+        step(f"norm-fused gemm K={K} N={N} F={F} M={M}")
+        lda = K + 64 if M % 2 == 0 else K  # strided rows on the fused path
+        xbuf = up_bf16(ds.normal_bf16(734 + M, (M, lda), 1.5, 0.25))
+        x = xbuf[:, :K] if M < 5 else xbuf[:, :K].contiguous()
+        pos = torch.from_numpy(np.random.default_rng(735 + M).permutation(Lmax)[:M].astype(np.int32)).to(DEV)
+        h = torch.empty((M, K), dtype=torch.bfloat16, device=DEV)
+        d.det_rmsnorm(x.contiguous(), wn, h, eps)
+        q_ref = torch.zeros((M, Hq, D), dtype=torch.bfloat16, device=DEV)
+        kc_ref = up_bf16(ds.normal_bf16(736, (M, Hkv, Lmax, D)))
+        vc_ref = up_bf16(ds.normal_bf16(737, (M, Hkv, Lmax, D)))
+        kc, vc, q = kc_ref.clone(), vc_ref.clone(), torch.zeros_like(q_ref)
+        d.det_gemm_qkv_rope_append(h, Wq, q_ref, kc_ref, vc_ref, pos, None, cos_t, sin_t)
+        y_ref = torch.empty((M, F), dtype=torch.bfloat16, device=DEV)
+        d.det_gemm_swiglu_bf16(h, Wg, y_ref, F, K)
+        h2 = torch.zeros_like(h)
+        d.det_rmsnorm_gemm_qkv_rope_append(x, wn, eps, Wq, h2, q, kc, vc, pos, None, cos_t, sin_t)
+        y = torch.empty_like(y_ref)
+        d.det_rmsnorm_gemm_swiglu_bf16(x, wn, eps, Wg, h2, y, F)
+        torch.cuda.synchronize()
+        for got, want in ((q, q_ref), (kc, kc_ref), (vc, vc_ref), (y, y_ref)):
+            assert torch.equal(got.view(torch.int16), want.view(torch.int16)), (K, M)
+
+
 def test_seeded_shape_sweep_both_gemms(d, orc):
     """Thirty seeded (M, N, K) drawn across every tiling rule (narrow and wide packings, row-cut, 64- and
     128-column tiles, several row tiles, ragged M): a sample of each product within the fp64 bound, one
