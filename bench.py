@@ -710,7 +710,7 @@ def decode_numbers(torch, det, ds, dev):
               g(3, (H,), 0.0, 1.0), det.pack_gate_up(g(4, (H, 2 * F))), det.pack_weight(g(5, (F, H)))]
     struct = det.layer_weights(*packed)
     # the same layer with 4-bit weights and 8-bit activations (det_qdecoder_layer)
-    qpacked = [packed[0], det.quant_pack_weight(g(1, (H, (Hq + 2 * Hkv) * D))), det.quant_pack_weight(g(2, (Hq * D, H))),
+    qpacked = [packed[0], det.quant_pack_qkv(g(1, (H, (Hq + 2 * Hkv) * D)), Hq, Hkv, D), det.quant_pack_weight(g(2, (Hq * D, H))),
                packed[3], det.quant_pack_gate_up(g(4, (H, 2 * F))), det.quant_pack_weight(g(5, (F, H)))]
     qstruct = det.layer_weights(*qpacked)
     qwbytes = float(sum(t.numel() * t.element_size() for t in qpacked))

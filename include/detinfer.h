@@ -385,6 +385,17 @@ int det_qgemm_w4a8_residual(const void *codes, const void *scales, const void *p
                             int ldr, void *C, int ldc, int M, int N, int K, void *stream);
 int det_qgemm_w4a8_swiglu(const void *codes, const void *scales, const void *packed_gate_up, void *Y,
                           int ldy, int M, int F, int K, void *stream);
+/* det_quant_pack_w4_qkv / det_qgemm_w4a8_qkv_rope_append: the quantized layer's fused projection, as
+ *   det_gemm_pack_qkv / det_gemm_qkv_rope_append are the bf16 layer's: the packing makes the columns d
+ *   and d + D/2 of every head neighbours (the quantizer's blocks run along K, so codes and scales are
+ *   those of det_quant_pack_w4 in another column order), and the GEMM's epilogue rotates the query and
+ *   key heads at the row's position and writes query heads to qbuf, key and value heads to the row's
+ *   cache slot: the bytes of det_qgemm_w4a8 (bf16 out), det_rope and the append.  D must be 128. */
+int det_quant_pack_w4_qkv(const void *B_kn, void *packed, int Hq, int Hkv, int D, int K, void *stream);
+int det_qgemm_w4a8_qkv_rope_append(const void *codes, const void *scales, const void *packed_qkv,
+                                   void *qbuf, void *kcache, void *vcache, const int32_t *positions,
+                                   const int32_t *slots, const float *rope_cos, const float *rope_sin,
+                                   int M, int Hq, int Hkv, int D, int Lmax, int K, void *stream);
 int det_rmsnorm_quant_q8(const void *x, const void *w, void *codes, void *scales, int M, int H, float eps,
                          void *stream);
 /* det_attn_decode_quant_q8: det_quant_act_q8 of the [R, Hq*D] output of det_attn_decode_rows (slots may be
@@ -405,7 +416,7 @@ int det_attn_decode_quant_q8(const void *q, const void *kcache, const void *vcac
 /* The decoder layer with every projection block-quantized (the engine the paper measures runs
  * quantized models, section 6.4): the steps of det_decoder_layer in the same order, each projection
  * det_qgemm_w4a8 on the det_quant_act_q8 codes of the bf16 activations it would have taken.  Weights:
- * w_norm1, w_norm2 bf16 [H]; wqkv, wo, wdown from det_quant_pack_w4; wgu from
+ * w_norm1, w_norm2 bf16 [H]; wqkv from det_quant_pack_w4_qkv; wo, wdown from det_quant_pack_w4; wgu from
  * det_quant_pack_w4_gate_up.  Other arguments as det_decoder_layer_rows; slots may be NULL (row r is
  * the sequence in cache slot r).  Same invariance: a row's bytes and its cache rows do not depend on
  * R or on the other rows.  Workspace: det_qdecoder_layer_workspace_bytes(cfg, R). */

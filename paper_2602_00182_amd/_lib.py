@@ -70,6 +70,8 @@ SIGNATURES = {
     "det_quant_pack_w4_gate_up": (_i, [_vp, _vp, _i, _i, _vp]),
     "det_qgemm_w4a8_residual": (_i, [_vp, _vp, _vp, _vp, _i, _vp, _i, _i, _i, _i, _vp]),
     "det_qgemm_w4a8_swiglu": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),
+    "det_quant_pack_w4_qkv": (_i, [_vp, _vp, _i, _i, _i, _i, _vp]),
+    "det_qgemm_w4a8_qkv_rope_append": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp]),
     "det_rmsnorm_quant_q8": (_i, [_vp, _vp, _vp, _vp, _i, _i, _f, _vp]),
     "det_qgemm_w4a8_swiglu_quant_supported": (_i, [_i, _i]),
     "det_qgemm_w4a8_swiglu_quant": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _vp]),

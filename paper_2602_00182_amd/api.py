@@ -21,7 +21,7 @@ __all__ = [
     "layer_weights", "pack_weight", "det_sha256_init", "det_sha256_update", "det_sha256_final",
     "det_commit_sha256", "det_sha256_force_portable", "det_qgemm_packed_w_bytes", "det_quant_pack_w4",
     "det_quant_unpack_w4", "det_quant_act_codes_bytes", "det_quant_act_scales_bytes", "det_quant_act_q8",
-    "det_qgemm_w4a8", "quant_pack_weight", "quant_activations", "det_qgemm_w4a8_residual",
+    "det_qgemm_w4a8", "quant_pack_weight", "quant_pack_qkv", "det_quant_pack_w4_qkv", "det_qgemm_w4a8_qkv_rope_append", "quant_activations", "det_qgemm_w4a8_residual",
     "det_qgemm_w4a8_swiglu", "det_quant_pack_w4_gate_up", "quant_pack_gate_up", "det_rmsnorm_quant_q8",
     "det_qdecoder_layer_workspace_bytes", "det_qdecoder_layer", "det_attn_decode_quant_q8",
     "det_qgemm_w4a8_swiglu_quant_supported", "det_qgemm_w4a8_swiglu_quant",
@@ -184,6 +184,42 @@ def quant_pack_weight(b_kn: torch.Tensor) -> torch.Tensor:
     packed = torch.empty(det_qgemm_packed_w_bytes(N, K), dtype=torch.uint8, device=b_kn.device)
     det_quant_pack_w4(b_kn.contiguous(), packed)
     return packed
+
+
+def det_quant_pack_w4_qkv(b_kn: torch.Tensor, packed: torch.Tensor, Hq: int, Hkv: int, D: int = 128, stream=None) -> None:
+    K, N = b_kn.shape
+    if N != (Hq + 2 * Hkv) * D or packed.numel() * packed.element_size() < det_qgemm_packed_w_bytes(N, K):
+        raise ValueError("bad fused query/key/value weight")
+    _check("det_quant_pack_w4_qkv", lib().det_quant_pack_w4_qkv(_contig(b_kn, torch.bfloat16), _contig(packed), Hq, Hkv, D, K,
+                                                                 _stream(stream)))
+
+
+def quant_pack_qkv(b_kn: torch.Tensor, Hq: int, Hkv: int, D: int = 128, stream=None) -> torch.Tensor:
+    """Allocates and fills the packed 4-bit form of a [K, (Hq+2Hkv)D] weight for det_qgemm_w4a8_qkv_rope_append
+    (the form det_qdecoder_layer takes as wqkv)."""
+    K, N = b_kn.shape
+    packed = torch.empty(det_qgemm_packed_w_bytes(N, K), dtype=torch.uint8, device=b_kn.device)
+    det_quant_pack_w4_qkv(b_kn, packed, Hq, Hkv, D, stream)
+    return packed
+
+
+def det_qgemm_w4a8_qkv_rope_append(codes, scales, packed_qkv, qbuf, kcache, vcache, positions, slots, rope_cos, rope_sin,
+                                   stream=None) -> None:
+    """The quantized layer's fused projection (see det_gemm_qkv_rope_append); weight from quant_pack_qkv."""
+    M, K = codes.shape
+    _, Hq, D = qbuf.shape
+    _, Hkv, Lmax, _ = kcache.shape
+    if qbuf.shape[0] != M or vcache.shape != kcache.shape or positions.numel() != M:
+        raise ValueError("bad fused projection operands")
+    if slots is not None and slots.numel() != M:
+        raise ValueError("bad slots")
+    if rope_cos.shape != (Lmax, D // 2) or rope_sin.shape != (Lmax, D // 2):
+        raise ValueError("bad rope tables")
+    _check("det_qgemm_w4a8_qkv_rope_append", lib().det_qgemm_w4a8_qkv_rope_append(
+        _contig(codes, torch.int8), _contig(scales, torch.float32), _contig(packed_qkv), _contig(qbuf, torch.bfloat16),
+        _contig(kcache, torch.bfloat16), _contig(vcache, torch.bfloat16), _contig(positions, torch.int32),
+        None if slots is None else _contig(slots, torch.int32), _contig(rope_cos, torch.float32),
+        _contig(rope_sin, torch.float32), M, Hq, Hkv, D, Lmax, K, _stream(stream)))
 
 
 def quant_activations(a: torch.Tensor):

@@ -24,40 +24,6 @@ __global__ __launch_bounds__(256) void rope_kernel(const uint16_t* __restrict__ 
     }
 }
 
-// The layer's fused form: rotate the Hq query heads of row b of the fused projection into qbuf,
-// rotate its Hkv key heads into cache row positions[b], copy its Hkv value heads there too.
-// qkv: [B, (Hq+2Hkv)*D]; qbuf: [B, Hq*D]; caches: [S, Hkv, Lmax, D].
-// Grid (Hq + 2*Hkv, B), one wavefront per head (D = 128: one rotation pair, or two value elements,
-// per thread): the work of a row is a single round trip to memory wide instead of ten deep.
-__global__ __launch_bounds__(64) void rope_append_kernel(const uint16_t* __restrict__ qkv,
-                                                         uint16_t* __restrict__ qbuf,
-                                                         uint16_t* __restrict__ kcache,
-                                                         uint16_t* __restrict__ vcache,
-                                                         const int32_t* __restrict__ pos,
-                                                         const int32_t* __restrict__ slots,
-                                                         const float* __restrict__ cos_t,
-                                                         const float* __restrict__ sin_t, int Hq, int Hkv,
-                                                         int D, int Lmax)
-{
-    const int hh = blockIdx.x, b = blockIdx.y, half = D >> 1, k = threadIdx.x;
-    int p = pos[b];
-    p = p < 0 ? 0 : (p >= Lmax ? Lmax - 1 : p);
-    const int slot = slots ? slots[b] : b;  // cache slot the row's key and value go to
-    const uint16_t* row = qkv + (size_t)b * (Hq + 2 * Hkv) * D;
-    if (hh < Hq + Hkv) {
-        if (k >= half) return;
-        const uint16_t* src = row + (size_t)hh * D;
-        uint16_t* dst = hh < Hq ? qbuf + ((size_t)b * Hq + hh) * D
-                                : kcache + (((size_t)slot * Hkv + (hh - Hq)) * Lmax + p) * D;
-        rope_pair(src[k], src[k + half], cos_t[(size_t)p * half + k], sin_t[(size_t)p * half + k], dst[k], dst[k + half]);
-    } else {
-        const int h = hh - Hq - Hkv;
-        const uint32_t* src = reinterpret_cast<const uint32_t*>(row + (size_t)(Hq + Hkv + h) * D);
-        uint32_t* dst = reinterpret_cast<uint32_t*>(vcache + (((size_t)slot * Hkv + h) * Lmax + p) * D);
-        for (int i = k; i < half; i += 64) dst[i] = src[i];
-    }
-}
-
 // y = bf16( (g / (1 + det_expf(-g))) * u ), 8 elements per thread.  Grid (ceil(F/2048), R).
 __global__ __launch_bounds__(256) void swiglu_kernel(const uint16_t* __restrict__ g, int ldg,
                                                      const uint16_t* __restrict__ u, int ldu,
@@ -144,17 +110,6 @@ __global__ __launch_bounds__(256) void advance_kernel(const int32_t* __restrict_
 
 using namespace det;
 
-int det::rope_append(const void* qkv, void* qbuf, void* kcache, void* vcache, const int32_t* positions,
-                     const int32_t* slots,
-                     const float* cos_t, const float* sin_t, int B, int Hq, int Hkv, int D, int Lmax,
-                     hipStream_t s)
-{
-    if (D != 128 || B > 65535) return DET_ESHAPE;
-    hipLaunchKernelGGL(rope_append_kernel, dim3(Hq + 2 * Hkv, B), dim3(64), 0, s, static_cast<const uint16_t*>(qkv),
-                       static_cast<uint16_t*>(qbuf), static_cast<uint16_t*>(kcache),
-                       static_cast<uint16_t*>(vcache), positions, slots, cos_t, sin_t, Hq, Hkv, D, Lmax);
-    return check_launch();
-}
 
 extern "C" int det_rope(const void* x, int ldx, void* y, int ldy, const int32_t* pos, const float* cos_t,
                         const float* sin_t, int R, int nh, int D, int Lmax, void* stream)

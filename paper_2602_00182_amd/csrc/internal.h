@@ -14,11 +14,5 @@ int attn_decode_impl(const void* q, const void* kcache, const void* vcache, cons
                      const int32_t* slots, int len_offset, void* out, void* ws, size_t ws_bytes, int B, int Hq, int Hkv, int D,
                      int Lmax, float scale, hipStream_t s, void* qscales = nullptr);
 
-// Rotary embedding of the q and k heads of the fused projection, k and v written into the caches
-// at row positions[b].  qkv [B,(Hq+2Hkv)D]; qbuf [B,Hq*D]; caches [B,Hkv,Lmax,D].
-int rope_append(const void* qkv, void* qbuf, void* kcache, void* vcache, const int32_t* positions,
-                const int32_t* slots,
-                const float* cos_t, const float* sin_t, int B, int Hq, int Hkv, int D, int Lmax,
-                hipStream_t s);
 
 }  // namespace det

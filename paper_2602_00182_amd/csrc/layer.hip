@@ -32,14 +32,13 @@ static LayerWs layer_ws(const det_layer_cfg& c, int B)
 // Workspace of the quantized layer: the bf16 buffers of the plain one that are still needed, plus one
 // set of activation codes and scales (the widest projection input), reused by the four projections.
 struct QLayerWs {
-    size_t qkv, qbuf, mm, codes, scales, codes2, scales2, attn, attn_bytes, total;
+    size_t qbuf, mm, codes, scales, codes2, scales2, attn, attn_bytes, total;
 };
 
 static QLayerWs qlayer_ws(const det_layer_cfg& c, int R)
 {
     QLayerWs w{};
     size_t off = 0;
-    const size_t nqkv = (size_t)(c.Hq + 2 * c.Hkv) * c.D;
     auto take = [&](size_t bytes) {
         const size_t o = off;
         off += up256(bytes);
@@ -47,7 +46,6 @@ static QLayerWs qlayer_ws(const det_layer_cfg& c, int R)
     };
     const int nq = c.Hq * c.D;
     const int kmax = c.H > nq ? (c.H > c.F ? c.H : c.F) : (nq > c.F ? nq : c.F);
-    w.qkv = take(2 * (size_t)R * nqkv);
     w.qbuf = take(2 * (size_t)R * nq);
     w.mm = take(2 * (size_t)R * c.F);
     w.codes = take(det_quant_act_codes_bytes(R, kmax));
@@ -152,7 +150,6 @@ extern "C" int det_qdecoder_layer(const det_layer_weights* w, const det_layer_cf
     const QLayerWs l = qlayer_ws(c, R);
     if (ws_bytes < l.total) return DET_EWORKSPACE;
     char* base = static_cast<char*>(ws);
-    void* qkv = base + l.qkv;
     void* qbuf = base + l.qbuf;
     void* mm = base + l.mm;
     void* codes = base + l.codes;
@@ -160,7 +157,6 @@ extern "C" int det_qdecoder_layer(const det_layer_weights* w, const det_layer_cf
     void* codes2 = base + l.codes2;
     void* scales2 = base + l.scales2;
     void* aws = base + l.attn;
-    const int nqkv = (c.Hq + 2 * c.Hkv) * c.D;
     const int nq = c.Hq * c.D;
     hipStream_t s = static_cast<hipStream_t>(stream);
     int rc;
@@ -170,9 +166,8 @@ extern "C" int det_qdecoder_layer(const det_layer_weights* w, const det_layer_cf
         if (rc != DET_OK) return rc; \
     } while (0)
     DET_TRY(det_rmsnorm_quant_q8(x_inout, w->w_norm1, codes, scales, R, c.H, c.eps, stream));
-    DET_TRY(det_qgemm_w4a8(codes, scales, w->wqkv, qkv, nqkv, R, nqkv, c.H, DET_BF16, stream));
-    DET_TRY(rope_append(qkv, qbuf, kcache, vcache, positions, slots, rope_cos, rope_sin, R, c.Hq, c.Hkv, c.D, c.Lmax,
-                        s));
+    DET_TRY(det_qgemm_w4a8_qkv_rope_append(codes, scales, w->wqkv, qbuf, kcache, vcache, positions, slots, rope_cos,
+                                           rope_sin, R, c.Hq, c.Hkv, c.D, c.Lmax, c.H, stream));
     DET_TRY(attn_decode_impl(qbuf, kcache, vcache, positions, slots, 1, codes, aws, l.attn_bytes, R, c.Hq, c.Hkv, c.D,
                              c.Lmax, c.scale, s, scales));
     DET_TRY(det_qgemm_w4a8_residual(codes, scales, w->wo, x_inout, c.H, x_inout, c.H, R, c.H, nq, stream));

@@ -51,14 +51,20 @@ __host__ __device__ constexpr int qstage_w_bytes(int cb) { return 544 * cb; }
 // stage: dword t = 0,1, byte i = 0..3: low nibble = code of k = 16g + 8t + i, high nibble = code of
 // k = 16g + 8t + 4 + i, each stored as q + 8); then at 512*cb the scales, 16 bf16 per column block.
 // gate_up_f > 0: packed column 2j is logical column j (gate) and 2j+1 is gate_up_f + j (up).
+// rope_d > 0: within every head of rope_d columns, packed columns 2i and 2i+1 are the head's logical columns i
+// and i + rope_d/2 (a rotation pair).
 __global__ __launch_bounds__(256) void quant_pack_w4_kernel(const uint16_t* __restrict__ W, uint8_t* __restrict__ packed,
-                                                            int N, int K, int cb, int gate_up_f)
+                                                            int N, int K, int cb, int gate_up_f, int rope_d)
 {
     const int nblk = K >> 6;
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (size_t)nblk * N) return;
     const int n = (int)(idx % N), b = (int)(idx / N);
-    const int nsrc = gate_up_f > 0 ? ((n & 1) ? gate_up_f + (n >> 1) : (n >> 1)) : n;
+    int nsrc = gate_up_f > 0 ? ((n & 1) ? gate_up_f + (n >> 1) : (n >> 1)) : n;
+    if (rope_d > 0) {
+        const int r = n % rope_d;
+        nsrc = n - r + (r >> 1) + ((r & 1) ? rope_d >> 1 : 0);
+    }
     float w[64];
     float amax = 0.0f;
 #pragma unroll
@@ -206,7 +212,8 @@ static qgemm_plan make_qgemm_plan(int mrem, int cb, int K)
 template <int CB, int EPI>
 __global__ __launch_bounds__(64 * (kQWaves + kQLoaders)) void qgemm_kernel(
     const int8_t* __restrict__ qa, int K, const float* __restrict__ da, int ldd, const uint8_t* __restrict__ wp, void* C,
-    int ldc, const uint16_t* R, int ldr, int out_f32, qgemm_plan plan_full, qgemm_plan plan_tail, float* qscales_out)
+    int ldc, const uint16_t* R, int ldr, int out_f32, qgemm_plan plan_full, qgemm_plan plan_tail, float* qscales_out,
+    gemm_rope_args ra)
 {
     __shared__ uint4 ring[kQRing * 64];
     __shared__ float rowmax[EPI == kEpiSwigluQuant ? 8 * 256 : 1];  // row maxima of the eight waves, that epilogue only
@@ -461,7 +468,16 @@ __global__ __launch_bounds__(64 * (kQWaves + kQLoaders)) void qgemm_kernel(
         chain(nchunks - 1);
         const int n = blockIdx.x * (16 * CB) + 16 * j + 4 * g;
         const int rowl = 16 * rg + lr;
-        if (rowl < mrem) gemm_epilogue_store<EPI>(acc, C, ldc, R, ldr, (size_t)(m0 + rowl), n, out_f32);
+        if (rowl < mrem) {
+            const size_t row = (size_t)(m0 + rowl);
+            if constexpr (EPI == kEpiRopeAppend) {
+                int p = ra.pos[row];
+                p = p < 0 ? 0 : (p >= ra.Lmax ? ra.Lmax - 1 : p);
+                gemm_epilogue_rope_append(acc, ra, row, p, ra.slots ? ra.slots[row] : (int)row, n);
+            } else {
+                gemm_epilogue_store<EPI>(acc, C, ldc, R, ldr, row, n, out_f32);
+            }
+        }
     };
     if (tp.SG > 1) {
         run_sp();
@@ -608,7 +624,13 @@ __global__ __launch_bounds__(64 * (kQWaves + kQLoaders)) void qgemm_kernel(
             if (r < cnt && rowl < mrem) {
                 const size_t row = (size_t)(m0 + rowl);
                 const float v[4] = {acc[r][0], acc[r][1], acc[r][2], acc[r][3]};
-                gemm_epilogue_store<EPI>(v, C, ldc, R, ldr, row, n, out_f32);
+                if constexpr (EPI == kEpiRopeAppend) {
+                    int p = ra.pos[row];
+                    p = p < 0 ? 0 : (p >= ra.Lmax ? ra.Lmax - 1 : p);
+                    gemm_epilogue_rope_append(v, ra, row, p, ra.slots ? ra.slots[row] : (int)row, n);
+                } else {
+                    gemm_epilogue_store<EPI>(v, C, ldc, R, ldr, row, n, out_f32);
+                }
             }
         }
     };
@@ -630,7 +652,8 @@ static int q_ldd(int M) { return (M + 3) & ~3; }
 
 template <int CB, int EPI>
 static void launch_qgemm(const void* qa, const void* da, int ldd, const void* wp, void* C, int ldc, const void* R, int ldr,
-                         int M, int N, int K, int out_f32, hipStream_t s, float* qscales_out = nullptr)
+                         int M, int N, int K, int out_f32, hipStream_t s, float* qscales_out = nullptr,
+                         const gemm_rope_args& ra = gemm_rope_args{})
 {
     // Matrices too narrow to give every compute unit a column tile: the rows are cut into as many tiles as
     // fill the chip (a tile's rows are whole 16-row blocks; which tile a row falls in does not touch its
@@ -647,19 +670,19 @@ static void launch_qgemm(const void* qa, const void* da, int ldd, const void* wp
     const qgemm_plan tail = make_qgemm_plan(M - tile_rows * ((M - 1) / tile_rows), CB, K);
     hipLaunchKernelGGL((qgemm_kernel<CB, EPI>), grid, dim3(64 * (kQWaves + kQLoaders)), 0, s,
                        static_cast<const int8_t*>(qa), K, static_cast<const float*>(da), ldd, static_cast<const uint8_t*>(wp),
-                       C, ldc, static_cast<const uint16_t*>(R), ldr, out_f32, full, tail, qscales_out);
+                       C, ldc, static_cast<const uint16_t*>(R), ldr, out_f32, full, tail, qscales_out, ra);
 }
 
 // N: columns of the packed matrix (2F for the SwiGLU epilogue).
 template <int EPI>
 static int qgemm_dispatch(const void* codes, const void* scales, const void* packed_w, void* C, int ldc, const void* R,
-                          int ldr, int M, int N, int K, int f32, hipStream_t s)
+                          int ldr, int M, int N, int K, int f32, hipStream_t s, const gemm_rope_args& ra = gemm_rope_args{})
 {
     switch (qgemm_cols_per_block(N)) {
-        case 1: launch_qgemm<1, EPI>(codes, scales, q_ldd(M), packed_w, C, ldc, R, ldr, M, N, K, f32, s); break;
-        case 2: launch_qgemm<2, EPI>(codes, scales, q_ldd(M), packed_w, C, ldc, R, ldr, M, N, K, f32, s); break;
-        case 4: launch_qgemm<4, EPI>(codes, scales, q_ldd(M), packed_w, C, ldc, R, ldr, M, N, K, f32, s); break;
-        default: launch_qgemm<8, EPI>(codes, scales, q_ldd(M), packed_w, C, ldc, R, ldr, M, N, K, f32, s); break;
+        case 1: launch_qgemm<1, EPI>(codes, scales, q_ldd(M), packed_w, C, ldc, R, ldr, M, N, K, f32, s, nullptr, ra); break;
+        case 2: launch_qgemm<2, EPI>(codes, scales, q_ldd(M), packed_w, C, ldc, R, ldr, M, N, K, f32, s, nullptr, ra); break;
+        case 4: launch_qgemm<4, EPI>(codes, scales, q_ldd(M), packed_w, C, ldc, R, ldr, M, N, K, f32, s, nullptr, ra); break;
+        default: launch_qgemm<8, EPI>(codes, scales, q_ldd(M), packed_w, C, ldc, R, ldr, M, N, K, f32, s, nullptr, ra); break;
     }
     return check_launch();
 }
@@ -676,7 +699,7 @@ extern "C" size_t det_qgemm_packed_w_bytes(int N, int K)
     return (size_t)(N / 16) * (K / 64) * qstage_w_bytes(1);
 }
 
-static int quant_pack_impl(const void* B_kn, void* packed, int N, int K, int gate_up_f, void* stream)
+static int quant_pack_impl(const void* B_kn, void* packed, int N, int K, int gate_up_f, void* stream, int rope_d = 0)
 {
     if (!B_kn || !packed) return DET_EINVAL;
     if (!qgemm_shape_ok(N, K)) return DET_ESHAPE;
@@ -684,8 +707,14 @@ static int quant_pack_impl(const void* B_kn, void* packed, int N, int K, int gat
     const size_t total = (size_t)N * (K / 64);
     hipLaunchKernelGGL(quant_pack_w4_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
                        static_cast<hipStream_t>(stream), static_cast<const uint16_t*>(B_kn), static_cast<uint8_t*>(packed), N,
-                       K, qgemm_cols_per_block(N), gate_up_f);
+                       K, qgemm_cols_per_block(N), gate_up_f, rope_d);
     return check_launch();
+}
+
+extern "C" int det_quant_pack_w4_qkv(const void* B_kn, void* packed, int Hq, int Hkv, int D, int K, void* stream)
+{
+    if (Hq < 1 || Hkv < 1 || D != 128) return DET_ESHAPE;
+    return quant_pack_impl(B_kn, packed, (Hq + 2 * Hkv) * D, K, 0, stream, D);
 }
 
 extern "C" int det_quant_pack_w4(const void* B_kn, void* packed, int N, int K, void* stream)
@@ -788,4 +817,28 @@ extern "C" int det_qgemm_w4a8_swiglu_quant(const void* codes, const void* scales
     launch_qgemm<8, kEpiSwigluQuant>(codes, scales, q_ldd(M), packed_gate_up, codes_out, F, nullptr, q_ldd(M), M, 2 * F, K, 0,
                                      static_cast<hipStream_t>(stream), static_cast<float*>(scales_out));
     return check_launch();
+}
+
+extern "C" int det_qgemm_w4a8_qkv_rope_append(const void* codes, const void* scales, const void* packed_qkv, void* qbuf,
+                                              void* kcache, void* vcache, const int32_t* positions, const int32_t* slots,
+                                              const float* rope_cos, const float* rope_sin, int M, int Hq, int Hkv, int D,
+                                              int Lmax, int K, void* stream)
+{
+    if (Hq < 1 || Hkv < 1 || D != 128 || Lmax < 1) return DET_ESHAPE;
+    const int N = (Hq + 2 * Hkv) * D;
+    const int rc = qgemm_args_ok(codes, scales, packed_qkv, qbuf, 4, M, N, 4, K);
+    if (rc != DET_OK) return rc;
+    if (!kcache || !vcache || !positions || !rope_cos || !rope_sin) return DET_EINVAL;
+    if (!aligned16(kcache) || !aligned16(vcache) || !aligned16(rope_cos) || !aligned16(rope_sin)) return DET_EALIGN;
+    gemm_rope_args ra;
+    ra.pos = positions;
+    ra.slots = slots;
+    ra.cos_t = rope_cos;
+    ra.sin_t = rope_sin;
+    ra.qbuf = static_cast<uint16_t*>(qbuf);
+    ra.kcache = static_cast<uint16_t*>(kcache);
+    ra.vcache = static_cast<uint16_t*>(vcache);
+    ra.Hq = Hq, ra.Hkv = Hkv, ra.Lmax = Lmax;
+    return qgemm_dispatch<kEpiRopeAppend>(codes, scales, packed_qkv, qbuf, 4, nullptr, 0, M, N, K, 0,
+                                          static_cast<hipStream_t>(stream), ra);
 }

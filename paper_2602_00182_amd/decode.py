@@ -52,7 +52,7 @@ class DecodeModel:
         self.lm_head = pack(weights["lm_head"])
         self.layers = []
         for lw in weights["layers"]:
-            wqkv = pack(lw["wqkv"]) if quantized else api.pack_qkv(lw["wqkv"], cfg.Hq, cfg.Hkv, cfg.D)
+            wqkv = (api.quant_pack_qkv if quantized else api.pack_qkv)(lw["wqkv"], cfg.Hq, cfg.Hkv, cfg.D)
             packed = dict(norm1=lw["norm1"].contiguous(), wqkv=wqkv,
                           wo=pack(lw["wo"]), norm2=lw["norm2"].contiguous(),
                           wgu=pack_gu(lw["wgu"]), wdown=pack(lw["wdown"]))

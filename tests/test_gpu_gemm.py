@@ -377,7 +377,7 @@ def test_fused_rope_append_epilogue_equals_unfused_bytes(d, M, Hq, Hkv, K, Lmax,
 
 
 @pytest.mark.parametrize("K,Hq,Hkv,F", [(4096, 32, 8, 14336), (2048, 16, 4, 5632), (1024, 4, 2, 2048), (256, 2, 1, 8000),
-                                        (4096, 8, 8, 24000), (3072, 24, 8, 8192)])
+                                        (4096, 8, 8, 24000), (3072, 24, 8, 8192), (1024, 4, 2, 3112)])
 def test_gemm_that_normalizes_its_rows_equals_rmsnorm_then_gemm(d, K, Hq, Hkv, F):
     """det_rmsnorm_gemm_qkv_rope_append / det_rmsnorm_gemm_swiglu_bf16 = det_rmsnorm, then the GEMM, byte for
     byte, for every M in 1..6 (1..4: the workgroups normalize the rows themselves; 5, 6: two launches)."""

@@ -87,7 +87,7 @@ def test_quantized_layer_and_sampling_graph_replays_match_eager():
     H, Hq, Hkv, D, F, Lmax, B, V = 1024, 8, 2, 128, 4096, 512, 5, 4096
     scale = float(np.float32(1.0 / math.sqrt(D)))
     g = lambda i, shape, std=0.03, mean=0.0: ds.normal_bf16_torch(9100 + i, shape, std, mean, DEV)
-    tensors = [g(0, (H,), 0.1, 1.0), d.quant_pack_weight(g(1, (H, (Hq + 2 * Hkv) * D))),
+    tensors = [g(0, (H,), 0.1, 1.0), d.quant_pack_qkv(g(1, (H, (Hq + 2 * Hkv) * D)), Hq, Hkv, D),
                d.quant_pack_weight(g(2, (Hq * D, H))), g(3, (H,), 0.1, 1.0), d.quant_pack_gate_up(g(4, (H, 2 * F))),
                d.quant_pack_weight(g(5, (F, H)))]
     w = d.layer_weights(*tensors)

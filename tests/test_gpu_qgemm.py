@@ -215,3 +215,51 @@ def test_qgemm_swiglu_quant_unsupported_shapes(d):
     p = buf.data_ptr()
     assert lib().det_qgemm_w4a8_swiglu_quant(p, p, p, p, p, 1, 5632, 2048, None) == 2
     assert lib().det_qgemm_w4a8_swiglu_quant(p, p, p, p, None, 1, 14336, 256, None) == 1
+
+
+@pytest.mark.parametrize("M,Hq,Hkv,K,Lmax,use_slots", [(1, 32, 8, 4096, 64, False), (5, 4, 2, 256, 40, True),
+                                                       (8, 16, 4, 2048, 96, True), (33, 8, 2, 1024, 96, True),
+                                                       (300, 32, 8, 4096, 320, False), (130, 2, 1, 512, 130, True)])
+def test_qgemm_rope_append_epilogue_equals_unfused_bytes(d, M, Hq, Hkv, K, Lmax, use_slots):
+    """det_qgemm_w4a8_qkv_rope_append on the pair-interleaved packing = det_qgemm_w4a8 on the plain packing,
+    then det_rope on the query and key heads and a copy of the key and value heads into the caches, byte for
+    byte (the quantized GEMM itself is compared with the oracle above); other cache rows keep their bytes."""
+    D = 128
+    N = (Hq + 2 * Hkv) * D
+    A = up_bf16(ds.normal_bf16(820 + M, (M, K)))
+    W = up_bf16(ds.normal_bf16(821 + Hq, (K, N), 0.05))
+    codes, scales = d.quant_activations(A)
+    cos_h, sin_h = ds.rope_tables(Lmax, D, 5.0e5)
+    cos_t, sin_t = torch.from_numpy(cos_h).to(DEV), torch.from_numpy(sin_h).to(DEV)
+    rng = np.random.default_rng(822 + M)
+    if use_slots:
+        S = max(2, (M + Lmax - 1) // Lmax + 1)
+        cells = rng.permutation(S * Lmax)[:M]
+        slots_h, pos_h = (cells // Lmax).astype(np.int32), (cells % Lmax).astype(np.int32)
+    else:
+        S = M
+        slots_h, pos_h = np.arange(M, dtype=np.int32), rng.integers(0, Lmax, M).astype(np.int32)
+        pos_h[0] = -3  # clamped to 0
+    pos = torch.from_numpy(pos_h).to(DEV)
+    slots = torch.from_numpy(slots_h).to(DEV) if use_slots else None
+    kc0 = up_bf16(ds.normal_bf16(823, (S, Hkv, Lmax, D)))
+    vc0 = up_bf16(ds.normal_bf16(824, (S, Hkv, Lmax, D)))
+    step(f"qgemm rope/append epilogue M={M} Hq={Hq} Hkv={Hkv} K={K}")
+    qkv = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+    d.det_qgemm_w4a8(codes, scales, d.quant_pack_weight(W), qkv, N)
+    qk = qkv[:, :(Hq + Hkv) * D].contiguous().view(M, Hq + Hkv, D)
+    qk_rot = torch.empty_like(qk)
+    d.det_rope(qk, qk_rot, pos, cos_t, sin_t)
+    torch.cuda.synchronize()
+    pc = torch.from_numpy(np.clip(pos_h, 0, Lmax - 1).astype(np.int64)).to(DEV)
+    sl = torch.from_numpy(slots_h.astype(np.int64)).to(DEV)
+    k_ref, v_ref = kc0.clone(), vc0.clone()
+    k_ref[sl, :, pc, :] = qk_rot[:, Hq:, :]
+    v_ref[sl, :, pc, :] = qkv[:, (Hq + Hkv) * D:].view(M, Hkv, D)
+    qbuf = torch.zeros((M, Hq, D), dtype=torch.bfloat16, device=DEV)
+    kc, vc = kc0.clone(), vc0.clone()
+    d.det_qgemm_w4a8_qkv_rope_append(codes, scales, d.quant_pack_qkv(W, Hq, Hkv, D), qbuf, kc, vc, pos, slots, cos_t, sin_t)
+    torch.cuda.synchronize()
+    assert torch.equal(qbuf.view(torch.int16), qk_rot[:, :Hq, :].contiguous().view(torch.int16))
+    assert torch.equal(kc.view(torch.int16), k_ref.view(torch.int16))
+    assert torch.equal(vc.view(torch.int16), v_ref.view(torch.int16))

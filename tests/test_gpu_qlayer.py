@@ -35,7 +35,8 @@ def layer(d):
         wgu=ds.normal_bf16_torch(s + 4, (H, 2 * F), 0.02, 0.0, DEV),
         wdown=ds.normal_bf16_torch(s + 5, (F, H), 0.02, 0.0, DEV),
     )
-    packed = dict(norm1=logical["norm1"], norm2=logical["norm2"], wqkv=d.quant_pack_weight(logical["wqkv"]),
+    packed = dict(norm1=logical["norm1"], norm2=logical["norm2"], wqkv=d.quant_pack_qkv(logical["wqkv"], Hq, Hkv, D),
+                  wqkv_plain=d.quant_pack_weight(logical["wqkv"]),
                   wo=d.quant_pack_weight(logical["wo"]), wgu=d.quant_pack_gate_up(logical["wgu"]),
                   wgu_plain=d.quant_pack_weight(logical["wgu"]), wdown=d.quant_pack_weight(logical["wdown"]))
     struct = d.layer_weights(packed["norm1"], packed["wqkv"], packed["wo"], packed["norm2"], packed["wgu"],
@@ -120,7 +121,7 @@ def test_qlayer_equals_unfused_calls(d, layer):
 
     h = torch.empty_like(x)
     d.det_rmsnorm(x, pk["norm1"], h, CFG["eps"])
-    qkv = qlinear(h, pk["wqkv"], (Hq + 2 * Hkv) * D)
+    qkv = qlinear(h, pk["wqkv_plain"], (Hq + 2 * Hkv) * D)
     q = torch.empty((B, Hq, D), dtype=torch.bfloat16, device=DEV)
     k = torch.empty((B, Hkv, D), dtype=torch.bfloat16, device=DEV)
     d.det_rope(qkv[:, :Hq * D].reshape(B, Hq, D).contiguous(), q, pos, layer["cos"], layer["sin"])
