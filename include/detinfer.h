@@ -115,9 +115,11 @@ int det_gemm_bf16_residual(const void *A, int lda, const void *B_packed, const v
 int det_gemm_pack_gate_up(const void *B_kn, void *B_packed, int F, int K, void *stream);
 int det_gemm_swiglu_bf16(const void *A, int lda, const void *B_gate_up, void *Y, int ldy, int M,
                          int F, int K, void *stream);
-/* The two projections that follow an RMSNorm in the layer, with the norm in the same call:
+/* The projections that follow an RMSNorm (two in the layer, the output head after the last layer), with the
+ * norm in the same call:
  *   det_rmsnorm_gemm_qkv_rope_append(x, ...) = det_gemm_qkv_rope_append(det_rmsnorm(x, w_norm, eps), ...)
  *   det_rmsnorm_gemm_swiglu_bf16(x, ...)     = det_gemm_swiglu_bf16(det_rmsnorm(x, w_norm, eps), ...)
+ *   det_rmsnorm_gemm_bf16(x, ...)            = det_gemm_bf16(det_rmsnorm(x, w_norm, eps), ...)
  * byte for byte.  x [M, K] bf16 raw rows with row stride ldx; w_norm [K] bf16; h [M, K] bf16 scratch that
  * the call may or may not write (M <= 4 and K <= 4096: the GEMM's workgroups normalize the rows themselves,
  * one launch instead of two, and h is untouched; otherwise det_rmsnorm into h, then the GEMM, and ldx must
@@ -130,6 +132,8 @@ int det_rmsnorm_gemm_qkv_rope_append(const void *x, int ldx, const void *w_norm,
 int det_rmsnorm_gemm_swiglu_bf16(const void *x, int ldx, const void *w_norm, float eps,
                                  const void *B_gate_up, void *h, void *Y, int ldy, int M, int F, int K,
                                  void *stream);
+int det_rmsnorm_gemm_bf16(const void *x, int ldx, const void *w_norm, float eps, const void *B_packed,
+                          void *h, void *C, int ldc, int M, int N, int K, int out_dtype, void *stream);
 int det_gemm_pack_qkv(const void *B_kn, void *B_packed, int Hq, int Hkv, int D, int K, void *stream);
 int det_gemm_qkv_rope_append(const void *A, int lda, const void *B_qkv, void *qbuf, void *kcache,
                              void *vcache, const int32_t *positions, const int32_t *slots,

@@ -40,6 +40,7 @@ SIGNATURES = {
     "det_rmsnorm_gemm_qkv_rope_append": (_i, [_vp, _i, _vp, _f, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i,
                                               _i, _i, _i, _vp]),
     "det_rmsnorm_gemm_swiglu_bf16": (_i, [_vp, _i, _vp, _f, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),
+    "det_rmsnorm_gemm_bf16": (_i, [_vp, _i, _vp, _f, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp]),
     "det_rmsnorm": (_i, [_vp, _vp, _vp, _i, _i, _f, _vp]),
     "det_attn_decode_workspace_bytes": (_sz, [_i, _i, _i, _i]),
     "det_attn_decode": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _sz, _i, _i, _i, _i, _i, _f, _vp]),

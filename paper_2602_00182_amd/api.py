@@ -13,7 +13,7 @@ from ._lib import LayerCfg, LayerWeights, Sha256Ctx, lib
 __all__ = [
     "DetError", "det_gemm_bf16", "det_gemm_bf16_fixed_tile", "det_probe_lds_fill", "det_gemm_packed_b_bytes", "det_gemm_pack_b", "det_gemm_bf16_residual",
     "det_gemm_pack_gate_up", "det_gemm_swiglu_bf16", "pack_gate_up", "det_gemm_pack_qkv", "pack_qkv",
-    "det_gemm_qkv_rope_append", "det_rmsnorm_gemm_qkv_rope_append", "det_rmsnorm_gemm_swiglu_bf16", "det_rmsnorm",
+    "det_gemm_qkv_rope_append", "det_rmsnorm_gemm_qkv_rope_append", "det_rmsnorm_gemm_swiglu_bf16", "det_rmsnorm_gemm_bf16", "det_rmsnorm",
     "det_attn_decode_workspace_bytes", "det_attn_decode", "det_attn_decode_static", "det_attn_decode_rows", "det_decoder_layer_rows",
     "det_softmax_f32", "det_argmax", "det_sample", "det_rope",
     "det_swiglu", "det_residual_add", "det_embed_gather", "det_decoder_layer_workspace_bytes",
@@ -429,6 +429,19 @@ def det_rmsnorm_gemm_swiglu_bf16(x, w_norm, eps: float, B_gate_up, h, Y, F: int,
     _check("det_rmsnorm_gemm_swiglu_bf16", lib().det_rmsnorm_gemm_swiglu_bf16(
         _ptr(x, torch.bfloat16), _ld(x, K), _contig(w_norm, torch.bfloat16), eps, _contig(B_gate_up),
         _contig(h, torch.bfloat16), _ptr(Y, torch.bfloat16), _ld(Y, F), M, F, K, _stream(stream)))
+
+
+def det_rmsnorm_gemm_bf16(x, w_norm, eps: float, B_packed, h, C_out, N: int, stream=None) -> None:
+    """det_gemm_bf16 of det_rmsnorm(x, w_norm, eps); h [M, K] bf16 is scratch; C_out bf16 or fp32."""
+    M, K = x.shape
+    if C_out.shape != (M, N) or x.stride(1) != 1 or C_out.stride(1) != 1 or w_norm.shape != (K,) or h.shape != (M, K):
+        raise ValueError("bad operand shapes")
+    if C_out.dtype not in (torch.bfloat16, torch.float32):
+        raise ValueError("output must be bf16 or fp32")
+    _check("det_rmsnorm_gemm_bf16", lib().det_rmsnorm_gemm_bf16(
+        _ptr(x, torch.bfloat16), _ld(x, K), _contig(w_norm, torch.bfloat16), eps, _contig(B_packed),
+        _contig(h, torch.bfloat16), C_out.data_ptr(), _ld(C_out, N), M, N, K,
+        DET_F32 if C_out.dtype == torch.float32 else DET_BF16, _stream(stream)))
 
 
 def _ld(t: torch.Tensor, cols: int) -> int:

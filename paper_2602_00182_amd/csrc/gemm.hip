@@ -765,14 +765,14 @@ static bool launch_gemm(const void* A, int lda, const void* Bp, void* C, int ldc
 // The launch that normalizes its rows itself (see the kernel): M <= 4, K <= 4096, R = the norm's weight vector.
 template <int EPI>
 static int gemm_dispatch_norm(const void* X, int ldx, const void* wn, float eps, const void* Bp, void* C, int ldc, int M,
-                              int N, int K, hipStream_t s, const gemm_rope_args& ra)
+                              int N, int K, hipStream_t s, const gemm_rope_args& ra, int f32 = 0)
 {
     bool ok = true;
     switch (gemm_cols_per_block(N)) {
 #define DET_GEMM_NORM_CASE(CBV)                                                                                        \
     case CBV:                                                                                                          \
         ok = launch_gemm<CBV, kRingBig, EPI, gemm_waves(CBV), gemm_loader_waves(CBV, false), CBV, true>(               \
-            X, ldx, Bp, C, ldc, wn, 0, ra, M, N, K, 0, s, 256, eps);                                                   \
+            X, ldx, Bp, C, ldc, wn, 0, ra, M, N, K, f32, s, 256, eps);                                                 \
         break;
         DET_GEMM_NORM_CASE(1)
         DET_GEMM_NORM_CASE(2)
@@ -1051,4 +1051,23 @@ extern "C" int det_rmsnorm_gemm_swiglu_bf16(const void* x, int ldx, const void* 
     if (ldy < F) return DET_EINVAL;
     return gemm_dispatch_norm<kEpiSwiglu>(x, ldx, w_norm, eps, B_gate_up, Y, ldy, M, 2 * F, K,
                                           static_cast<hipStream_t>(stream), gemm_rope_args{});
+}
+
+extern "C" int det_rmsnorm_gemm_bf16(const void* x, int ldx, const void* w_norm, float eps, const void* B_packed, void* h,
+                                     void* C, int ldc, int M, int N, int K, int out_dtype, void* stream)
+{
+    if (!x || !w_norm || !h) return DET_EINVAL;
+    if (out_dtype != DET_BF16 && out_dtype != DET_F32) return DET_EINVAL;
+    if (!aligned16(w_norm) || !aligned16(h)) return DET_EALIGN;
+    if (!gemm_norm_fusable(M, K)) {
+        if (ldx != K) return DET_EINVAL;
+        const int rc = det_rmsnorm(x, w_norm, h, M, K, eps, stream);
+        if (rc != DET_OK) return rc;
+        return det_gemm_bf16(h, K, B_packed, C, ldc, M, N, K, out_dtype, stream);
+    }
+    const int rc = gemm_args_ok(x, ldx, B_packed, C, ldc, M, N, K);
+    if (rc != DET_OK) return rc;
+    if (ldc < N) return DET_EINVAL;
+    return gemm_dispatch_norm<kEpiStore>(x, ldx, w_norm, eps, B_packed, C, ldc, M, N, K, static_cast<hipStream_t>(stream),
+                                         gemm_rope_args{}, out_dtype == DET_F32);
 }

@@ -119,8 +119,7 @@ class DecodeState:
             api.det_rmsnorm_quant_q8(self.x, m.final_norm, self.xn_codes, self.xn_scales, c.eps, stream)
             api.det_qgemm_w4a8(self.xn_codes, self.xn_scales, m.lm_head, self.logits, c.V, stream)
         else:
-            api.det_rmsnorm(self.x, m.final_norm, self.xn, c.eps, stream)
-            api.det_gemm_bf16(self.xn, m.lm_head, self.logits, c.V, c.H, stream)
+            api.det_rmsnorm_gemm_bf16(self.x, m.final_norm, c.eps, m.lm_head, self.xn, self.logits, c.V, stream)
 
 
 @dataclass

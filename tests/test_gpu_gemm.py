@@ -280,6 +280,26 @@ def test_error_codes(d):
     assert lib.det_gemm_bf16(None, 64, Bp.data_ptr(), C.data_ptr(), 16, 4, 16, 64, 0, s) == 1
     assert lib.det_gemm_bf16(A.data_ptr(), 64, Bp.data_ptr(), C.data_ptr(), 16, 0, 16, 64, 0, s) == 1
     assert lib.det_gemm_bf16(A.data_ptr(), 64, Bp.data_ptr(), C.data_ptr(), 16, 4, 16, 64, 7, s) == 1
+    # the fused projections: argument errors launch nothing
+    buf = torch.zeros(1 << 20, dtype=torch.uint8, device=DEV)
+    p = buf.data_ptr()
+    qkv = lib.det_gemm_qkv_rope_append
+    assert qkv(p, 64, p, p, p, p, p, None, p, p, 2, 1, 1, 128, 8, 64, s) == 0          # N = 384, K = 64: fine
+    assert qkv(p, 64, p, p, p, p, p, None, p, p, 2, 1, 1, 64, 8, 64, s) == 2           # head size
+    assert qkv(p, 64, p, p, p, p, p, None, p, p, 2, 0, 1, 128, 8, 64, s) == 2          # no query heads
+    assert qkv(p, 64, p, p, p, p, None, None, p, p, 2, 1, 1, 128, 8, 64, s) == 1       # no positions
+    assert qkv(p, 64, p, p, p + 4, p, p, None, p, p, 2, 1, 1, 128, 8, 64, s) == 3      # cache alignment
+    assert qkv(p, 32, p, p, p, p, p, None, p, p, 2, 1, 1, 128, 8, 64, s) == 1          # lda < K
+    assert lib.det_gemm_pack_qkv(p, p, 1, 1, 96, 64, s) == 2
+    nq = lib.det_rmsnorm_gemm_qkv_rope_append
+    assert nq(p, 64, p, 1e-5, p, p, p, p, p, p, None, p, p, 2, 1, 1, 128, 8, 64, s) == 0
+    assert nq(p, 64, None, 1e-5, p, p, p, p, p, p, None, p, p, 2, 1, 1, 128, 8, 64, s) == 1    # no norm weight
+    assert nq(p, 64, p, 1e-5, p, None, p, p, p, p, None, p, p, 2, 1, 1, 128, 8, 64, s) == 1    # no scratch
+    assert nq(p, 128, p, 1e-5, p, p, p, p, p, p, None, p, p, 9, 1, 1, 128, 16, 64, s) == 1     # two launches need ldx == K
+    ns = lib.det_rmsnorm_gemm_swiglu_bf16
+    assert ns(p, 64, p, 1e-5, p, p, p, 8, 2, 8, 64, s) == 0
+    assert ns(p, 64, p, 1e-5, p, p, p, 4, 2, 8, 64, s) == 1                              # ldy < F
+    assert ns(p, 64, p, 1e-5, p, p, p, 12, 2, 12, 64, s) == 2                            # F % 8
     torch.cuda.synchronize()
 
 
@@ -379,12 +399,13 @@ def test_fused_rope_append_epilogue_equals_unfused_bytes(d, M, Hq, Hkv, K, Lmax,
 @pytest.mark.parametrize("K,Hq,Hkv,F", [(4096, 32, 8, 14336), (2048, 16, 4, 5632), (1024, 4, 2, 2048), (256, 2, 1, 8000),
                                         (4096, 8, 8, 24000), (3072, 24, 8, 8192), (1024, 4, 2, 3112)])
 def test_gemm_that_normalizes_its_rows_equals_rmsnorm_then_gemm(d, K, Hq, Hkv, F):
-    """det_rmsnorm_gemm_qkv_rope_append / det_rmsnorm_gemm_swiglu_bf16 = det_rmsnorm, then the GEMM, byte for
-    byte, for every M in 1..6 (1..4: the workgroups normalize the rows themselves; 5, 6: two launches)."""
+    """det_rmsnorm_gemm_qkv_rope_append / det_rmsnorm_gemm_swiglu_bf16 / det_rmsnorm_gemm_bf16 (bf16 and fp32
+    out) = det_rmsnorm, then the GEMM, byte for byte, for every M in 1..6 (1..4: the workgroups normalize the rows themselves; 5, 6: two launches)."""
     D, Lmax = 128, 48
     N = (Hq + 2 * Hkv) * D
     Wq = d.pack_qkv(up_bf16(ds.normal_bf16(731 + K, (K, N), 0.05)), Hq, Hkv, D)
-    Wg = d.pack_gate_up(up_bf16(ds.normal_bf16(732 + F, (K, 2 * F), 0.05)))
+    Wg_logical = up_bf16(ds.normal_bf16(732 + F, (K, 2 * F), 0.05))
+    Wg, Wplain = d.pack_gate_up(Wg_logical), d.pack_weight(Wg_logical)
     wn = up_bf16(ds.normal_bf16(733 + K, (K,), 0.3, 1.0))
     cos_h, sin_h = ds.rope_tables(Lmax, D, 5.0e5)
     cos_t, sin_t = torch.from_numpy(cos_h).to(DEV), torch.from_numpy(sin_h).to(DEV)
@@ -408,7 +429,16 @@ def test_gemm_that_normalizes_its_rows_equals_rmsnorm_then_gemm(d, K, Hq, Hkv, F
         d.det_rmsnorm_gemm_qkv_rope_append(x, wn, eps, Wq, h2, q, kc, vc, pos, None, cos_t, sin_t)
         y = torch.empty_like(y_ref)
         d.det_rmsnorm_gemm_swiglu_bf16(x, wn, eps, Wg, h2, y, F)
+        plain = {}
+        for dt in (torch.bfloat16, torch.float32):
+            want_c = torch.empty((M, 2 * F), dtype=dt, device=DEV)
+            d.det_gemm_bf16(h, Wplain, want_c, 2 * F, K)
+            got_c = torch.zeros_like(want_c)
+            d.det_rmsnorm_gemm_bf16(x, wn, eps, Wplain, h2, got_c, 2 * F)
+            plain[dt] = (got_c, want_c)
         torch.cuda.synchronize()
+        for got, want in plain.values():
+            assert torch.equal(got.view(torch.uint8), want.view(torch.uint8)), (K, M, got.dtype)
         for got, want in ((q, q_ref), (kc, kc_ref), (vc, vc_ref), (y, y_ref)):
             assert torch.equal(got.view(torch.int16), want.view(torch.int16)), (K, M)
 
