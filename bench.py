@@ -68,7 +68,7 @@ def main():
                          "FETCH_SIZE / WRITE_SIZE readings) and exit")
     ap.add_argument("--probe", default=None, metavar="SPEC",
                     help="run a few launches of ONE operation and exit (the program that rocprofv3 counter "
-                         "passes run): gemm:K:N:M, gemm_fixed:K:N:M, qgemm:K:N:M, attn:B:L, prefill:S:T, layer:B")
+                         "passes run): gemm:K:N:M, gemm_fixed:K:N:M, qgemm:K:N:M, attn:B:L, prefill:S:T, layer:B, step:B")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -325,6 +325,26 @@ def probe(torch, det, ds, dev, spec):
         ws = torch.empty(det.det_decoder_layer_workspace_bytes(cfg, B), dtype=torch.uint8, device=dev)
         for _ in range(reps):
             det.det_decoder_layer(w, cfg, x, kc, vc, pos, cos_d, sin_d, ws)
+    elif kind == "step":
+        # one greedy decode step of the 8-layer model of decode_numbers (context 512), B sequences
+        from paper_2602_00182_amd.decode import DecodeModel, ModelCfg
+        (B,) = nums
+        H, Hq, Hkv, D, F, V, NL, Lm = 2048, 16, 4, 128, 5632, 32000, 8, 640
+        s = ds.tensor_seed(5, 0)
+        g = lambda i, shape, std=0.02, mean=0.0: ds.normal_bf16_torch(s + i, shape, std, mean, dev)
+        layers = [dict(norm1=g(10 + 10 * l, (H,), 0.0, 1.0), wqkv=g(11 + 10 * l, (H, (Hq + 2 * Hkv) * D)),
+                       wo=g(12 + 10 * l, (Hq * D, H)), norm2=g(13 + 10 * l, (H,), 0.0, 1.0),
+                       wgu=g(14 + 10 * l, (H, 2 * F)), wdown=g(15 + 10 * l, (F, H))) for l in range(NL)]
+        model = DecodeModel(ModelCfg(H, Hq, Hkv, D, F, V, NL),
+                            dict(embed=g(1, (V, H), 1.0), lm_head=g(2, (H, V)), final_norm=g(3, (H,), 0.0, 1.0), layers=layers))
+        cos_t, sin_t = ds.rope_tables(Lm, D, 5.0e5)
+        st = model.new_state(B, Lm, torch.from_numpy(cos_t).to(dev), torch.from_numpy(sin_t).to(dev))
+        st.tokens.copy_(torch.from_numpy(ds.uniform_int(s + 900, (B,), 0, V - 1)).to(dev))
+        st.positions.fill_(511)
+        idx = torch.empty(B, dtype=torch.int32, device=dev)
+        for _ in range(reps):
+            st.forward()
+            det.det_argmax(st.logits, idx)
     else:
         raise SystemExit(f"bench.py: unknown probe {spec!r}")
     torch.cuda.synchronize()
