@@ -387,10 +387,27 @@ def measured_peaks(torch, dev, roofline):
     copy_gbs = 2 * n / copy_ms / 1e6
     read_gbs = n / read_ms / 1e6
     best = max(copy_gbs, read_gbs)
+    # What a launch of a shape's size can reach at all: a plain device copy that moves as many bytes as the
+    # shape's weights (K*N bytes read, K*N written), buffers rotating through the 1 GiB arrays so that every
+    # copy is HBM-cold, launches back to back.  A launch of 33 MB is over before the chip streams at its rate.
+    same_bytes = []
+    for (K, N) in SHAPES:
+        kn = K * N
+        slots = max(2, n // kn)
+        state = [0]
+
+        def one(kn=kn, slots=slots, state=state):
+            i = state[0] % slots
+            state[0] += 1
+            b[i * kn:(i + 1) * kn].copy_(a[i * kn:(i + 1) * kn])
+        ms = timed(one, reps=3 * slots)
+        same_bytes.append({"K": K, "N": N, "bytes_mb": round(2 * kn / 1e6, 1), "copy_us": round(ms * 1e3, 2),
+                           "copy_frac_hbm": round(2 * kn / ms / 1e6 / PEAK_HBM_GBS, 4)})
     del a, b, f
     torch.cuda.empty_cache()
     return {"copy_1GiB_gbs": round(copy_gbs, 1), "read_1GiB_gbs": round(read_gbs, 1),
             "dominant_kernel_frac_of_measured": round(roofline["achieved"] / best, 4),
+            "copy_of_a_shapes_bytes": same_bytes,
             "lds_fill_l2_resident": fill,
             "note": "device-to-device copy counts read + written bytes; the read pass is torch's sum over fp32"}
 
