@@ -17,15 +17,23 @@ constexpr int kChunk = 256;
 constexpr int kD = 128;
 constexpr int kHalfTok = 128;  // tokens of the half chunk whose V^T sits in LDS at a time
 
-// Softmax statistics of one 256-token chunk of one row, computed by ONE wavefront: lane l holds the scores
-// of tokens l, l+64, l+128 and l+192 of the chunk (s[k], valid[k] for token 64k + l).
+// Softmax statistics of one 256-token chunk of one row, computed by ONE wavefront.  Lane 16r + i holds the
+// scores of the tokens 64r + 16k + i, k = 0..3, of the chunk (s[k], valid[k]; chunk_token(lane, k)): the sixteen
+// lanes of a row hold one group of 64 leaves of the 256-leaf tree, so the tree's strides 32 and 16 pair values
+// of one lane, its strides 8, 4, 2, 1 are shifts inside a row of sixteen lanes (a modifier of the adding
+// instruction), and only the four group sums cross rows, through scalar registers.
 //   m_c = max of the valid scores (-inf if there is none);
 //   e   = det_expf(s - m_c) for a valid token, 0 otherwise;
-//   l_c = the 256-leaf sum of e: inside each group of 64 tokens lane i takes lane i+off for off = 32, 16,
-//         .., 1, and the four group sums q0..q3 combine as (q0+q2)+(q1+q3).
-// m_c is returned in every lane, l_c is meaningful in lane 0 only.  No LDS, no barrier: the waves of a
-// workgroup run it independently on different rows.  This is the only implementation of these statistics
-// in the library: the attention kernel and det_softmax_f32 both call it.
+//   l_c = the 256-leaf sum of e: inside each group of 64 leaves, leaf j takes leaf j+off for off = 32, 16, .., 1,
+//         and the four group sums q0..q3 combine as (q0+q2)+(q1+q3).
+// m_c and l_c are returned in every lane.  No LDS, no barrier: the waves of a workgroup run it independently
+// on different rows.  This is the only implementation of these statistics in the library: the attention kernel
+// and det_softmax_f32 both call it.
+__device__ __forceinline__ int chunk_token(int lane, int k) { return ((lane >> 4) << 6) + (k << 4) + (lane & 15); }
+__device__ __forceinline__ float lane_value(float v, int lane)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
 __device__ __forceinline__ void chunk_stats(const float (&s)[4], const bool (&valid)[4], float& m_c, float (&e)[4],
                                             float& l_c)
 {
@@ -33,34 +41,23 @@ __device__ __forceinline__ void chunk_stats(const float (&s)[4], const bool (&va
 #pragma unroll
     for (int k = 0; k < 4; ++k) sv[k] = valid[k] ? s[k] : -INFINITY;
     float m = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));  // max is exact: any order
-    m = fmaxf(m, lane_plus<32>(m));
-    m = fmaxf(m, lane_plus<16>(m));
-    m = fmaxf(m, lane_plus<8>(m));
-    m = fmaxf(m, lane_plus<4>(m));
+    m = fmaxf(m, lane_plus<8>(m));  // (a lane past its row's end reads 0 here and holds nothing of use afterwards:
+    m = fmaxf(m, lane_plus<4>(m));  //  lane 0 of a row only ever takes lanes inside the row)
     m = fmaxf(m, lane_plus<2>(m));
     m = fmaxf(m, lane_plus<1>(m));
-    m = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, m)));  // lane 0 holds the maximum
+    m = fmaxf(fmaxf(lane_value(m, 0), lane_value(m, 16)), fmaxf(lane_value(m, 32), lane_value(m, 48)));
     m_c = m;
-    float red[4];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        e[k] = valid[k] ? det_expf(sv[k] - m) : 0.0f;
-        red[k] = e[k];
-    }
-#pragma unroll
-    for (int k = 0; k < 4; ++k) red[k] = red[k] + lane_plus<32>(red[k]);
-#pragma unroll
-    for (int k = 0; k < 4; ++k) red[k] = red[k] + lane_plus<16>(red[k]);
-#pragma unroll
-    for (int k = 0; k < 4; ++k) red[k] = red[k] + lane_plus<8>(red[k]);
-#pragma unroll
-    for (int k = 0; k < 4; ++k) red[k] = red[k] + lane_plus<4>(red[k]);
-#pragma unroll
-    for (int k = 0; k < 4; ++k) red[k] = red[k] + lane_plus<2>(red[k]);
-#pragma unroll
-    for (int k = 0; k < 4; ++k) red[k] = red[k] + lane_plus<1>(red[k]);
-    const float qa = red[0] + red[2];
-    const float qb = red[1] + red[3];
+    for (int k = 0; k < 4; ++k) e[k] = valid[k] ? det_expf(sv[k] - m) : 0.0f;
+    const float a = e[0] + e[2];  // stride 32: leaf j takes leaf j + 32, j = i and j = 16 + i
+    const float b = e[1] + e[3];
+    float t = a + b;              // stride 16
+    t = t + lane_plus<8>(t);
+    t = t + lane_plus<4>(t);
+    t = t + lane_plus<2>(t);
+    t = t + lane_plus<1>(t);
+    const float qa = lane_value(t, 0) + lane_value(t, 32);
+    const float qb = lane_value(t, 16) + lane_value(t, 48);
     l_c = qa + qb;
 }
 
@@ -283,12 +280,12 @@ __global__ __launch_bounds__(256, RT == 1 ? 4 : 2) void attn_tile_kernel(const u
                 bool vd[4];
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
-                    vd[k] = in_group && t0 + 64 * k + lane < l;
-                    sv[k] = sc[sc_index(p, 64 * k + lane)];
+                    vd[k] = in_group && t0 + chunk_token(lane, k) < l;
+                    sv[k] = sc[sc_index(p, chunk_token(lane, k))];
                 }
                 chunk_stats(sv, vd, m_c, e, l_c);
 #pragma unroll
-                for (int k = 0; k < 4; ++k) sc[sc_index(p, 64 * k + lane)] = e[k];
+                for (int k = 0; k < 4; ++k) sc[sc_index(p, chunk_token(lane, k))] = e[k];
                 if (lane == 0 && in_group) {
                     const size_t part = ((size_t)(tile * RT + ri) * Hq + (size_t)hgrp * G + p % G) * ncmax + c;
                     ws_m[part] = m_c;
@@ -518,14 +515,14 @@ __global__ __launch_bounds__(256) void softmax_kernel(const float* __restrict__ 
         bool vd[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const int j = c * kChunk + 64 * k + lane;
+            const int j = c * kChunk + chunk_token(lane, k);
             vd[k] = j < len;
             sv[k] = vd[k] ? sr[j] : 0.0f;
         }
         chunk_stats(sv, vd, m_c, e, l_c);
 #pragma unroll
         for (int k = 0; k < 4; ++k)
-            if (vd[k]) pr[c * kChunk + 64 * k + lane] = e[k];
+            if (vd[k]) pr[c * kChunk + chunk_token(lane, k)] = e[k];
         if (lane == 0) {
             mc[c] = m_c;
             lc[c] = l_c;
