@@ -34,6 +34,10 @@
 //     store is one 8- or 16-byte write.  Rows of the operand are independent in the matrix core,
 //     so rows past M may hold anything: their lanes load nothing and their outputs are never
 //     stored.
+//   * Fused forms of the same kernel, each giving the bytes of the unfused sequence: epilogues on the
+//     accumulator rounded to bf16 (residual add, SwiGLU on gate/up-interleaved columns, rotation and cache
+//     append on pair-interleaved query/key/value columns), and, up to four rows, the RMSNorm of the rows
+//     computed by the workgroup itself in front of the K loop (template parameter NORM).
 //
 // K order: matrix-core step t (t = 0 .. K/32-1, ascending) takes k in [32t, 32t+32); inside a step
 // lane group g supplies k = 32t + 8g + e, e = 0..7.
